@@ -1,0 +1,201 @@
+/*
+ * nestpipe.h - C ABI of the MI355X (gfx950) sparse-embedding hot path.
+ *
+ * One worker's share of the embedding work that the paper's nested pipelines exist to hide
+ * (Section IV-A, stages "Key Routing", "Embedding Retrieval" and "Fwd/Bwd"; Section IV-B for
+ * the in-place update; Section VI, Eq. (1)-(2) for what an update must and must not touch):
+ *
+ *     np_dedup -> np_route -> [key All2All] -> np_lookup_fwd -> [embedding All2All, dense model]
+ *              -> np_lookup_bwd -> [gradient All2All] -> np_sparse_adagrad
+ *
+ * The bracketed exchanges are not part of this library: an All2All is represented by the packed
+ * send buffer and the per-shard split counts that np_route produces.
+ *
+ * General rules
+ *  - Every pointer is DEVICE memory owned by the caller unless a comment says "host".  The
+ *    library never allocates, frees or keeps a pointer after the call returns.  Scratch memory
+ *    is the caller's `ws` buffer, sized by the matching np_*_workspace_bytes() (a pure host
+ *    function).  `ws` must be 256-byte aligned.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *    work: they never synchronise with the host.  The number of distinct keys U is data
+ *    dependent and lives in device memory (`d_num_unique` / `d_num_list`); the host passes an
+ *    upper bound `cap` that sizes buffers and grids.
+ *  - Return value: NP_OK or a negative np_status.  Arguments are validated on the host before
+ *    anything is enqueued, so a call that returns NP_ERR_INVALID_ARG, NP_ERR_WORKSPACE or
+ *    NP_ERR_UNSUPPORTED has written nothing.  Nothing throws, aborts or prints.
+ *  - Keys are int64 row ids of one fused table, 0 <= key < num_rows (the caller adds a per-table
+ *    base to form them).  Every index, offset and count is int32, so n <= 2^31 - 1.
+ *  - Bags: the lookups of bag b are keys[bag_offsets[b] .. bag_offsets[b+1]), bag_offsets is
+ *    non-decreasing with bag_offsets[0] = 0 and bag_offsets[num_bags] = n.  Empty bags are legal.
+ *  - Out-of-range keys, repeated keys in an update list, or offsets that break the rules above
+ *    are precondition violations (not checked on the device).
+ *  - Supported row widths: dim a multiple of 4, 4 <= dim <= 1024; table, gradient and output
+ *    buffers 16-byte aligned.
+ */
+#ifndef NESTPIPE_H_
+#define NESTPIPE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum np_status {
+    NP_OK = 0,
+    NP_ERR_INVALID_ARG = -1, /* null required pointer, negative size, bad enum value, misaligned buffer */
+    NP_ERR_WORKSPACE = -2,   /* ws is NULL/misaligned or ws_bytes is below np_*_workspace_bytes() */
+    NP_ERR_UNSUPPORTED = -3, /* legal request outside what the kernels cover (dim, num_shards, sizes) */
+    NP_ERR_HIP = -4          /* a launch failed; the HIP error was consumed with hipGetLastError */
+} np_status;
+
+enum { NP_SHARD_MOD = 0, NP_SHARD_HASH = 1 };
+enum { NP_POOL_SUM = 0, NP_POOL_MEAN = 1, NP_SEQ = 2 };
+enum { NP_F32 = 0, NP_BF16 = 1 };
+
+#define NP_MAX_SHARDS 4096
+#define NP_MAX_DIM 1024
+
+/* Library version (major * 10000 + minor * 100 + patch).  Host function. */
+int np_version(void);
+
+/* Static text for a status code.  Host function; the pointer is to a string literal. */
+const char* np_status_string(int status);
+
+/*
+ * np_dedup - Section IV-A, "Key Routing": the sparse keys of the batch are deduplicated first
+ * (and again on the owner over the keys received from all sources, "Embedding Retrieval").
+ *
+ *   keys         [n]   in   int64, only the low key_bits bits may be non-zero (1 <= key_bits <= 63)
+ *   unique       [n]   out  the U distinct keys, ascending; entries >= U are not written
+ *   inverse      [n]   out  inverse[j] = index of keys[j] in unique
+ *   counts       [n]   out  counts[u] = multiplicity of unique[u], u < U
+ *   occ_offsets  [n+1] out  exclusive prefix sum of counts; occ_offsets[U] = n
+ *   occ          [n]   out  positions 0..n-1 sorted by (key, position): the stable argsort of keys.
+ *                           occ[occ_offsets[u] .. occ_offsets[u+1]) are the lookups of unique[u].
+ *   d_num_unique [1]   out  U
+ *
+ * All outputs are bit-exact functions of the input (no dependence on scheduling).
+ * n = 0 is legal: writes U = 0 and occ_offsets[0] = 0.
+ */
+int np_dedup(const int64_t* keys, int32_t n, int32_t key_bits, int64_t* unique, int32_t* inverse, int32_t* counts,
+             int32_t* occ_offsets, int32_t* occ, int32_t* d_num_unique, void* ws, size_t ws_bytes, void* stream);
+size_t np_dedup_workspace_bytes(int32_t n, int32_t key_bits);
+
+/*
+ * np_route - Section IV-A, "Key Routing": the deduplicated keys are partitioned into buckets by the
+ * table-sharding rule; the buckets laid end to end are the payload of the key All2All.
+ *
+ *   unique          [cap]   in   ascending distinct keys, the first U = *d_num_unique are valid
+ *   d_num_unique    [1]     in   U (device), U <= cap
+ *   num_shards              1 <= S <= NP_MAX_SHARDS
+ *   shard_fn                NP_SHARD_MOD: shard = key mod S.
+ *                           NP_SHARD_HASH: shard = mix(key) mod S with, on uint64 and C = 0x9E3779B97F4A7C15,
+ *                           a = key*C; a ^= a>>32; a *= C; a ^= a>>29; mix = a.
+ *   send_keys       [cap]   out  keys grouped by shard 0..S-1, ascending inside a shard (stable bucketing)
+ *   splits          [S]     out  keys per shard (the All2All send counts); sums to U
+ *   send_offsets    [S+1]   out  exclusive prefix sum of splits
+ *   send_from_unique[cap]   out  send_keys[p] = unique[send_from_unique[p]]
+ *   unique_to_send  [cap]   out  inverse permutation: send_keys[unique_to_send[u]] = unique[u]
+ *   inverse         [n]     in   optional (NULL with lookup_to_send NULL): np_dedup's inverse
+ *   lookup_to_send  [n]     out  optional: lookup_to_send[j] = unique_to_send[inverse[j]], the send slot whose
+ *                                vector lookup j consumes once the owners have answered
+ */
+int np_route(const int64_t* unique, const int32_t* d_num_unique, int32_t cap, int32_t num_shards, int32_t shard_fn,
+             int64_t* send_keys, int32_t* splits, int32_t* send_offsets, int32_t* send_from_unique,
+             int32_t* unique_to_send, const int32_t* inverse, int32_t n, int32_t* lookup_to_send, void* ws,
+             size_t ws_bytes, void* stream);
+size_t np_route_workspace_bytes(int32_t cap, int32_t num_shards);
+
+/*
+ * np_lookup_fwd - Section IV-A, "Embedding Retrieval" (the owner reads the vectors of the deduplicated
+ * keys from its table shard) and the start of "Fwd/Bwd" (the requester holds the vector of every lookup
+ * of its batch).  value_j = table[list_keys[idx[j]], :].
+ *
+ *   table      [num_rows, dim] in  fp32, row-major, HBM resident
+ *   list_keys  [cap]  in   key list (np_route's send_keys, or np_dedup's unique)
+ *   d_num_list [1]    in   number of valid list entries; read only when rows_out != NULL (may be NULL otherwise)
+ *   idx        [n]    in   lookup -> list slot; NULL means list_keys has n entries and lookup j reads slot j
+ *   mode / out:
+ *     NP_POOL_SUM   out[b,:] = sum of value_j over bag b                  out is [num_bags, dim]
+ *     NP_POOL_MEAN  the sum times 1/length; an empty bag gives zeros       out is [num_bags, dim]
+ *     NP_SEQ        out[b,p,:] = value of the p-th lookup of bag b, zeros for p >= length
+ *                   out is [num_bags, max_len, dim]; every bag length must be <= max_len
+ *   out_dtype  NP_F32 or NP_BF16 (round to nearest even from the fp32 result); sums accumulate in fp32 in
+ *              ascending lookup order
+ *   rows_out   [cap, dim]  out, optional: rows_out[p,:] = table[list_keys[p],:] for p < *d_num_list (a bit
+ *              copy: the payload of the embedding All2All)
+ */
+int np_lookup_fwd(const float* table, int64_t num_rows, int32_t dim, const int64_t* list_keys,
+                  const int32_t* d_num_list, int32_t cap, const int32_t* idx, const int32_t* bag_offsets,
+                  int32_t num_bags, int32_t n, int32_t mode, int32_t max_len, int32_t out_dtype, void* out,
+                  float* rows_out, void* ws, size_t ws_bytes, void* stream);
+size_t np_lookup_fwd_workspace_bytes(int32_t num_bags, int32_t n, int32_t dim, int32_t mode);
+
+/*
+ * np_lookup_bwd - Section II-A and IV-A: embedding gradients are routed to the owner and aggregated per
+ * key; Eq. (2): the update of key k uses the sum over the batch of the gradients of e_k.
+ *
+ *   g[u,:] = sum over lookups j of key unique[u] of  w_j * dY_j
+ *     NP_POOL_SUM   dY_j = dY[bag(j),:]                      w_j = 1
+ *     NP_POOL_MEAN  dY_j = dY[bag(j),:]                      w_j = 1/length(bag(j))
+ *     NP_SEQ        dY_j = dY[bag(j), j - start(bag(j)), :]  w_j = 1   (dY is [num_bags, max_len, dim];
+ *                                                                      padding positions are never read)
+ *   dY          in   fp32 or bf16 (dy_dtype)
+ *   occ_offsets, occ  in   np_dedup's occurrence lists
+ *   d_num_unique[1]   in   U (device), U <= cap
+ *   unique_to_send [cap] in  optional: the row of key u is written at grads[unique_to_send[u],:]
+ *                            (NULL: at grads[u,:])
+ *   grads       [cap, dim] out fp32; rows >= U are not written
+ *
+ * Deterministic: fp32 accumulation in an order that depends only on occ_offsets (never on scheduling),
+ * no floating-point atomics; two runs on the same input give identical bits.
+ */
+int np_lookup_bwd(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
+                  const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
+                  const int32_t* occ, const int32_t* d_num_unique, int32_t cap, const int32_t* unique_to_send,
+                  float* grads, void* ws, size_t ws_bytes, void* stream);
+size_t np_lookup_bwd_workspace_bytes(int32_t num_bags, int32_t n, int32_t dim, int32_t mode);
+
+/*
+ * np_sparse_adagrad - Section IV-B: gradients are applied directly to the vectors held in HBM; Eq. (2):
+ * keys outside the batch keep their vectors bit for bit.  The paper's update is plain SGD; this build's
+ * benchmark definition asks for row-wise Adagrad, one fp32 accumulator per row:
+ *
+ *   for each list slot p < *d_num_list, k = list_keys[p], g = grads[p,:]:
+ *     G = state[k] + (1/dim) * sum_d g_d^2 ;  state[k] = G ;  table[k,d] -= lr * g_d / (sqrt(G) + eps)
+ *
+ *   table [num_rows, dim] in/out,  state [num_rows] in/out,  list_keys pairwise distinct.
+ */
+int np_sparse_adagrad(float* table, float* state, int64_t num_rows, int32_t dim, const int64_t* list_keys,
+                      const float* grads, const int32_t* d_num_list, int32_t cap, float lr, float eps,
+                      void* stream);
+
+/* ---- harness utilities (not on the hot path) ------------------------------------------------------ */
+
+/*
+ * Fill table[row, col] with the stateless initialiser used by the synthetic workloads:
+ *   h = (row*dim + col) + seed*0x2545F4914F6CDD1D; h ^= h>>31; h *= 0xD6E8FEB86659FD93; h ^= h>>27;
+ *   h *= 0xA3B195354A39B70D; h ^= h>>33;  value = (float)((int)(h>>40) - 2^23) * (0.01f / 2^23)
+ * uniform on [-0.01, 0.01), one rounding, identical on every platform.
+ */
+int np_util_table_init(float* table, int64_t num_rows, int32_t dim, uint64_t seed, void* stream);
+
+/* Plain device copy of `bytes` (multiple of 16) with 16-byte loads and stores: the bandwidth yardstick. */
+int np_util_stream_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+/*
+ * Per-kernel timing with HIP events on the caller's stream.  np_prof_enable(1) makes every kernel launch
+ * of the library record a start and stop event (events are created on first use and reused);
+ * np_prof_collect synchronises those events and copies up to `max_entries` records, in launch order, into
+ * host arrays: names[i] points to a static string, ms[i] is the kernel's duration.  Returns the number of
+ * records and clears the log.  Host functions; not thread safe; meant for the benchmark only.
+ */
+int np_prof_enable(int on);
+int np_prof_collect(const char** names /* host */, float* ms /* host */, int max_entries);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NESTPIPE_H_ */

@@ -1,0 +1,228 @@
+"""Thin Python layer over the C-ABI HIP library (``include/nestpipe.h``).
+
+Argument marshalling only: every step of the path runs in the library's kernels.  torch supplies device
+memory and the stream; no torch op takes part in the computation.  The functions carry the names of the
+C entry points.  Output and workspace tensors are allocated here unless the caller passes them in
+(``out=...`` dictionaries / ``ws=`` tensors), which the benchmark does to keep allocation out of the loop.
+
+The library must have been built (``python -m paper_2604_06956_amd.build``); if it is missing the import
+fails: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+import torch  # imported before the library so that the library binds to torch's HIP runtime
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libnestpipe_hip.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_06956_amd.build`")
+
+lib = ctypes.CDLL(LIB_PATH)
+
+NP_OK = 0
+SHARD_MOD, SHARD_HASH = 0, 1
+POOL_SUM, POOL_MEAN, SEQ = 0, 1, 2
+F32, BF16 = 0, 1
+MAX_SHARDS = 4096
+
+_vp, _i32, _i64, _sz, _f32, _u64 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float,
+                                    ctypes.c_uint64)
+
+lib.np_version.restype = ctypes.c_int
+lib.np_status_string.restype = ctypes.c_char_p
+lib.np_status_string.argtypes = [ctypes.c_int]
+lib.np_dedup.restype = ctypes.c_int
+lib.np_dedup.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.np_dedup_workspace_bytes.restype = _sz
+lib.np_dedup_workspace_bytes.argtypes = [_i32, _i32]
+lib.np_route.restype = ctypes.c_int
+lib.np_route.argtypes = [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
+lib.np_route_workspace_bytes.restype = _sz
+lib.np_route_workspace_bytes.argtypes = [_i32, _i32]
+lib.np_lookup_fwd.restype = ctypes.c_int
+lib.np_lookup_fwd.argtypes = [_vp, _i64, _i32, _vp, _vp, _i32, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _sz,
+                              _vp]
+lib.np_lookup_fwd_workspace_bytes.restype = _sz
+lib.np_lookup_fwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
+lib.np_lookup_bwd.restype = ctypes.c_int
+lib.np_lookup_bwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
+lib.np_lookup_bwd_workspace_bytes.restype = _sz
+lib.np_lookup_bwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
+lib.np_sparse_adagrad.restype = ctypes.c_int
+lib.np_sparse_adagrad.argtypes = [_vp, _vp, _i64, _i32, _vp, _vp, _vp, _i32, _f32, _f32, _vp]
+lib.np_util_table_init.restype = ctypes.c_int
+lib.np_util_table_init.argtypes = [_vp, _i64, _i32, _u64, _vp]
+lib.np_util_stream_copy.restype = ctypes.c_int
+lib.np_util_stream_copy.argtypes = [_vp, _vp, _sz, _vp]
+lib.np_prof_enable.restype = ctypes.c_int
+lib.np_prof_enable.argtypes = [ctypes.c_int]
+lib.np_prof_collect.restype = ctypes.c_int
+lib.np_prof_collect.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float), ctypes.c_int]
+
+
+class NestPipeError(RuntimeError):
+    def __init__(self, call: str, status: int):
+        self.status = status
+        super().__init__(f"{call} failed: {status} ({lib.np_status_string(status).decode()})")
+
+
+def _chk(call: str, rc: int) -> None:
+    if rc != NP_OK:
+        raise NestPipeError(call, rc)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> int:
+    if t is None:
+        return 0
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors handed to the library must be contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ws(nbytes: int, ws: Optional[torch.Tensor], device) -> Tuple[Optional[torch.Tensor], int]:
+    if nbytes == 0 and ws is None:
+        return None, 0
+    if ws is None:
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    return ws, ws.numel() * ws.element_size()
+
+
+def _dt(dtype: int):
+    return torch.bfloat16 if dtype == BF16 else torch.float32
+
+
+def version() -> int:
+    return int(lib.np_version())
+
+
+def np_dedup_workspace_bytes(n: int, key_bits: int) -> int:
+    return int(lib.np_dedup_workspace_bytes(n, key_bits))
+
+
+def np_dedup(keys: torch.Tensor, key_bits: int, out: Optional[Dict[str, torch.Tensor]] = None,
+             ws: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """-> dict(unique[n] i64, inverse[n] i32, counts[n] i32, occ_offsets[n+1] i32, occ[n] i32, num_unique[1] i32).
+    Only the first U = num_unique entries of unique / counts / occ_offsets(+1) are meaningful."""
+    n = keys.numel()
+    dev = keys.device
+    if out is None:
+        out = dict(unique=torch.empty(max(n, 1), dtype=torch.int64, device=dev),
+                   inverse=torch.empty(max(n, 1), dtype=torch.int32, device=dev),
+                   counts=torch.empty(max(n, 1), dtype=torch.int32, device=dev),
+                   occ_offsets=torch.empty(n + 1, dtype=torch.int32, device=dev),
+                   occ=torch.empty(max(n, 1), dtype=torch.int32, device=dev),
+                   num_unique=torch.empty(1, dtype=torch.int32, device=dev))
+    ws, ws_bytes = _ws(np_dedup_workspace_bytes(n, key_bits), ws, dev)
+    rc = lib.np_dedup(_ptr(keys), n, key_bits, _ptr(out["unique"]), _ptr(out["inverse"]), _ptr(out["counts"]),
+                      _ptr(out["occ_offsets"]), _ptr(out["occ"]), _ptr(out["num_unique"]), _ptr(ws), ws_bytes, _stream())
+    _chk("np_dedup", rc)
+    return out
+
+
+def np_route_workspace_bytes(cap: int, num_shards: int) -> int:
+    return int(lib.np_route_workspace_bytes(cap, num_shards))
+
+
+def np_route(unique: torch.Tensor, num_unique: torch.Tensor, cap: int, num_shards: int, shard_fn: int,
+             inverse: Optional[torch.Tensor] = None, n: int = 0, out: Optional[Dict[str, torch.Tensor]] = None,
+             ws: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """-> dict(send_keys[cap] i64, splits[S] i32, send_offsets[S+1] i32, send_from_unique[cap] i32,
+    unique_to_send[cap] i32, lookup_to_send[n] i32 when ``inverse`` is given)."""
+    dev = unique.device
+    if out is None:
+        out = dict(send_keys=torch.empty(max(cap, 1), dtype=torch.int64, device=dev),
+                   splits=torch.empty(max(num_shards, 1), dtype=torch.int32, device=dev),
+                   send_offsets=torch.empty(max(num_shards, 1) + 1, dtype=torch.int32, device=dev),
+                   send_from_unique=torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
+                   unique_to_send=torch.empty(max(cap, 1), dtype=torch.int32, device=dev))
+        if inverse is not None:
+            out["lookup_to_send"] = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    ws, ws_bytes = _ws(np_route_workspace_bytes(cap, num_shards), ws, dev)
+    rc = lib.np_route(_ptr(unique), _ptr(num_unique), cap, num_shards, shard_fn, _ptr(out["send_keys"]),
+                      _ptr(out["splits"]), _ptr(out["send_offsets"]), _ptr(out["send_from_unique"]),
+                      _ptr(out["unique_to_send"]), _ptr(inverse), n if inverse is not None else 0,
+                      _ptr(out.get("lookup_to_send")) if inverse is not None else 0, _ptr(ws), ws_bytes, _stream())
+    _chk("np_route", rc)
+    return out
+
+
+def np_lookup_fwd(table: torch.Tensor, list_keys: torch.Tensor, idx: Optional[torch.Tensor], bag_offsets: torch.Tensor,
+                  n: int, mode: int, max_len: int = 1, out_dtype: int = F32, num_list: Optional[torch.Tensor] = None,
+                  cap: int = 0, want_rows: bool = False, out: Optional[torch.Tensor] = None,
+                  rows_out: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    """-> (out [B, D] or [B, max_len, D], rows_out [cap, D] or None)."""
+    num_rows, dim = table.shape
+    num_bags = bag_offsets.numel() - 1
+    dev = table.device
+    if out is None:
+        shape = (num_bags, max_len, dim) if mode == SEQ else (num_bags, dim)
+        out = torch.empty(shape, dtype=_dt(out_dtype), device=dev)
+    if want_rows and rows_out is None:
+        rows_out = torch.empty((max(cap, 1), dim), dtype=torch.float32, device=dev)
+    rc = lib.np_lookup_fwd(_ptr(table), num_rows, dim, _ptr(list_keys), _ptr(num_list), cap, _ptr(idx), _ptr(bag_offsets),
+                           num_bags, n, mode, max_len, out_dtype, _ptr(out), _ptr(rows_out), 0, 0, _stream())
+    _chk("np_lookup_fwd", rc)
+    return out, rows_out
+
+
+def np_lookup_bwd_workspace_bytes(num_bags: int, n: int, dim: int, mode: int) -> int:
+    return int(lib.np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode))
+
+
+def np_lookup_bwd(dY: torch.Tensor, dim: int, mode: int, max_len: int, bag_offsets: torch.Tensor, n: int,
+                  occ_offsets: torch.Tensor, occ: torch.Tensor, num_unique: torch.Tensor, cap: int,
+                  unique_to_send: Optional[torch.Tensor] = None, grads: Optional[torch.Tensor] = None,
+                  ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """-> grads [cap, D] fp32 (rows >= U untouched)."""
+    dev = dY.device
+    num_bags = bag_offsets.numel() - 1
+    dy_dtype = BF16 if dY.dtype == torch.bfloat16 else F32
+    if dY.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("dY must be fp32 or bf16")
+    if grads is None:
+        grads = torch.empty((max(cap, 1), dim), dtype=torch.float32, device=dev)
+    ws, ws_bytes = _ws(np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode), ws, dev)
+    rc = lib.np_lookup_bwd(_ptr(dY), dy_dtype, dim, mode, max_len, _ptr(bag_offsets), num_bags, n, _ptr(occ_offsets),
+                           _ptr(occ), _ptr(num_unique), cap, _ptr(unique_to_send), _ptr(grads), _ptr(ws), ws_bytes,
+                           _stream())
+    _chk("np_lookup_bwd", rc)
+    return grads
+
+
+def np_sparse_adagrad(table: torch.Tensor, state: torch.Tensor, list_keys: torch.Tensor, grads: torch.Tensor,
+                      num_list: torch.Tensor, cap: int, lr: float, eps: float) -> None:
+    num_rows, dim = table.shape
+    rc = lib.np_sparse_adagrad(_ptr(table), _ptr(state), num_rows, dim, _ptr(list_keys), _ptr(grads), _ptr(num_list), cap,
+                               lr, eps, _stream())
+    _chk("np_sparse_adagrad", rc)
+
+
+def np_util_table_init(table: torch.Tensor, seed: int) -> None:
+    num_rows, dim = table.shape
+    _chk("np_util_table_init", lib.np_util_table_init(_ptr(table), num_rows, dim, seed, _stream()))
+
+
+def np_util_stream_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    _chk("np_util_stream_copy", lib.np_util_stream_copy(_ptr(dst), _ptr(src), nbytes, _stream()))
+
+
+def np_prof_enable(on: bool) -> None:
+    lib.np_prof_enable(1 if on else 0)
+
+
+def np_prof_collect(max_entries: int = 4096):
+    """-> list of (kernel name, milliseconds) in launch order since the last collect."""
+    names = (ctypes.c_char_p * max_entries)()
+    ms = (ctypes.c_float * max_entries)()
+    k = lib.np_prof_collect(names, ms, max_entries)
+    return [(names[i].decode(), float(ms[i])) for i in range(k)]

@@ -1,0 +1,147 @@
+// Shared host/device helpers of the gfx950 sparse-embedding library: launch bookkeeping, wave64
+// primitives, the XCD-aware block mapping and the routing hash.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nestpipe.h"
+
+namespace np {
+
+constexpr int kWave = 64;
+constexpr int kNumXcd = 8;  // MI355X: 8 accelerator dies, workgroup i is dispatched to die i % 8
+
+// ---------------------------------------------------------------- host side -----------------------
+
+void prof_begin(const char* name, hipStream_t stream);
+void prof_end(hipStream_t stream);
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? NP_OK : NP_ERR_HIP; }
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Carves 256-byte aligned pieces out of the caller's workspace.
+struct WsCursor {
+    char* base;
+    size_t used;
+    explicit WsCursor(void* p) : base(static_cast<char*>(p)), used(0) {}
+    template <typename T>
+    T* take(size_t count) {
+        T* r = reinterpret_cast<T*>(base + used);
+        used += align_up(count * sizeof(T), 256);
+        return r;
+    }
+};
+
+#define NP_LAUNCH(name, kernel, grid, block, shmem, stream, ...)                       \
+    do {                                                                              \
+        ::np::prof_begin(name, stream);                                               \
+        hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);          \
+        ::np::prof_end(stream);                                                       \
+    } while (0)
+
+// ---------------------------------------------------------------- device side ---------------------
+
+// Logical block index such that consecutive logical blocks run on the same die (they then share one L2,
+// so partial cache lines written by neighbours merge before they reach HBM).  A bijection on [0, nblocks).
+__device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
+    const int q = nblocks / kNumXcd, r = nblocks % kNumXcd;
+    const int x = bid % kNumXcd, i = bid / kNumXcd;
+    return x * q + (x < r ? x : r) + i;
+}
+
+__device__ __forceinline__ int lane_id() { return __lane_id(); }
+
+__device__ __forceinline__ uint64_t lanemask_lt() {
+    const int l = __lane_id();
+    return l == 0 ? 0ull : (~0ull >> (64 - l));
+}
+
+// Routing hash (a bijection of 64-bit words): odd multiplier, xor-shift, twice.
+__host__ __device__ __forceinline__ uint64_t mix64(uint64_t k) {
+    const uint64_t C = 0x9E3779B97F4A7C15ull;
+    uint64_t a = k * C;
+    a ^= a >> 32;
+    a *= C;
+    a ^= a >> 29;
+    return a;
+}
+
+// x mod s for s < 2^16 through a precomputed reciprocal: magic = floor(2^32 / s).
+struct FastMod {
+    uint32_t s, magic, pow32;  // pow32 = 2^32 mod s
+};
+
+inline FastMod make_fastmod(uint32_t s) {
+    FastMod f;
+    f.s = s;
+    f.magic = s == 1 ? 0xFFFFFFFFu : static_cast<uint32_t>((1ull << 32) / s);
+    f.pow32 = static_cast<uint32_t>((1ull << 32) % s);
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fastmod32(uint32_t x, const FastMod& f) {
+    uint32_t q = __umulhi(x, f.magic);
+    uint32_t r = x - q * f.s;
+    while (r >= f.s) r -= f.s;
+    return r;
+}
+
+__device__ __forceinline__ uint32_t fastmod64(uint64_t x, const FastMod& f) {
+    const uint32_t hi = fastmod32(static_cast<uint32_t>(x >> 32), f);
+    const uint32_t lo = fastmod32(static_cast<uint32_t>(x), f);
+    return fastmod32(hi * f.pow32 + lo, f);  // hi, pow32 < 2^16: the product fits in 32 bits
+}
+
+__device__ __forceinline__ int wave_incl_scan(int v) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        int t = __shfl_up(v, d, kWave);
+        if (__lane_id() >= d) v += t;
+    }
+    return v;
+}
+
+// Exclusive scan of one int per thread over a block of NW waves.  `smem` holds NW + 1 ints.  Returns the
+// exclusive prefix; *total receives the block sum.  Contains two __syncthreads.
+template <int NW>
+__device__ __forceinline__ int block_excl_scan(int v, int* smem, int* total) {
+    const int w = threadIdx.x / kWave;
+    const int inc = wave_incl_scan(v);
+    __syncthreads();  // smem may still be read from a previous call
+    if (__lane_id() == kWave - 1) smem[w] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        const int s = smem[i];
+        if (i < w) base += s;
+        tot += s;
+    }
+    *total = tot;
+    return base + inc - v;
+}
+
+// fp32 -> bf16, round to nearest even; NaN becomes a quiet NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16(float x) {
+    uint32_t b = __float_as_uint(x);
+    if ((b & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((b >> 16) | 0x0040u);
+    b += 0x7FFFu + ((b >> 16) & 1u);
+    return static_cast<uint16_t>(b >> 16);
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(static_cast<uint32_t>(h) << 16); }
+
+// Row geometry shared by the row kernels: a row of `dim` floats is dim/4 float4 words, handled by LPR
+// lanes holding NV words each (word index = lane_in_group + v * LPR).
+template <int LPR, int NV>
+struct RowGeom {
+    static constexpr int kLanes = LPR;
+    static constexpr int kWords = NV;
+    static constexpr int kGroupsPerBlock = 256 / LPR;
+};
+
+}  // namespace np

@@ -1,0 +1,425 @@
+// np_lookup_bwd: per-key gradient = sum over the key's lookups of the upstream gradient of the bag (or
+// sequence position) the lookup belongs to (Section II-A / IV-A: gradients are aggregated per key at the
+// owner; Eq. (2) sums the per-sample gradients of a key over the batch).
+//
+// A deterministic segmented reduction over np_dedup's occurrence lists, balanced under any skew:
+//
+//   bwd_expand     src_row[j] = the dY row lookup j reads (its bag, or its padded sequence position)
+//   bwd_tile_seg0  for every tile of 256 consecutive sorted positions, the key segment its first position is in
+//   bwd_main       one block per tile.  Every thread prepares one position (dY row, weight, head/tail flags
+//                  of its segment); then each LPR-lane group walks its LPR positions in order, several dY row
+//                  loads in flight, and closes a running sum whenever a segment ends.  Sums of segments that
+//                  lie inside one group's strip go straight to grads.  Sums cut by a strip edge are combined
+//                  across the groups of the block in strip order; sums cut by a tile edge are parked in the
+//                  workspace as the tile's "left" (continues from an earlier tile) and "right" (continues
+//                  into later tiles) partials.
+//   bwd_fixup      the tile where a cut segment starts adds its right partial and the left partials of the
+//                  following tiles in tile order, with a fixed split of long chains over the block.
+//
+// The order of every floating-point addition is a function of occ_offsets alone: no atomics, no dependence
+// on scheduling, so two runs give the same bits.  A hot key with millions of lookups costs the same per
+// lookup as a cold one.
+#include "np_common.hpp"
+
+namespace np {
+
+constexpr int kBwdTile = 256;
+constexpr int kBwdUnroll = 8;
+
+template <int G>
+__global__ void __launch_bounds__(256)
+bwd_expand_kernel(const int32_t* __restrict__ bag_offsets, int num_bags, int seq, int max_len, int32_t* __restrict__ src_row) {
+    const int r = threadIdx.x % G;
+    const int64_t b = static_cast<int64_t>(blockIdx.x) * (256 / G) + threadIdx.x / G;
+    if (b >= num_bags) return;
+    const int lo = bag_offsets[b], hi = bag_offsets[b + 1];
+    for (int j = lo + r; j < hi; j += G) src_row[j] = seq ? static_cast<int32_t>(b * max_len + (j - lo)) : static_cast<int32_t>(b);
+}
+
+__global__ void __launch_bounds__(256)
+bwd_tile_seg0_kernel(const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ d_num_unique, int num_tiles,
+                     int32_t* __restrict__ tile_seg0) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= num_tiles) return;
+    const int pos = t * kBwdTile;
+    int lo = 0, hi = *d_num_unique;  // the answer is the last u in [lo, hi) with occ_offsets[u] <= pos
+    while (hi - lo > 1) {
+        const int mid = lo + (hi - lo) / 2;
+        if (occ_offsets[mid] <= pos) lo = mid;
+        else hi = mid;
+    }
+    tile_seg0[t] = lo;
+}
+
+template <int LPR>
+__device__ __forceinline__ int group_bcast(int v, int src_in_group) {
+    return __shfl(v, (__lane_id() & ~(LPR - 1)) + src_in_group, kWave);
+}
+
+__device__ __forceinline__ float4 load_dy(const float* dY, size_t row, int dim, int word) {
+    return reinterpret_cast<const float4*>(dY + row * dim)[word];
+}
+
+__device__ __forceinline__ float4 load_dy(const uint16_t* dY, size_t row, int dim, int word) {
+    const uint2 p = reinterpret_cast<const uint2*>(dY + row * dim)[word];
+    return make_float4(__uint_as_float(p.x << 16), __uint_as_float(p.x & 0xFFFF0000u), __uint_as_float(p.y << 16),
+                       __uint_as_float(p.y & 0xFFFF0000u));
+}
+
+template <int LPR, int NV, bool MEAN, typename DyT>
+__global__ void __launch_bounds__(256)
+bwd_main_kernel(const DyT* __restrict__ dY, int dim, const int32_t* __restrict__ bag_offsets, int n,
+                const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ occ, const int32_t* __restrict__ d_num_unique,
+                const int32_t* __restrict__ unique_to_send, const int32_t* __restrict__ src_row,
+                const int32_t* __restrict__ tile_seg0, float* __restrict__ grads, float* __restrict__ tile_left,
+                float* __restrict__ tile_right, int32_t* __restrict__ tile_rseg) {
+    constexpr int GPB = 256 / LPR;
+    constexpr int ROWW = LPR * NV;  // float4 words per (padded) row
+    __shared__ int headmark[kBwdTile + 1];
+    __shared__ int scan_tmp[16];
+    __shared__ float4 lpart[GPB * ROWW];
+    __shared__ float4 rpart[GPB * ROWW];
+    __shared__ int l_exists[GPB], l_closed[GPB], l_dst[GPB], r_exists[GPB];
+
+    const int t = threadIdx.x;
+    const int tile = blockIdx.x;
+    const int tile_start = tile * kBwdTile;
+    const int i = tile_start + t;
+    const bool valid = i < n;
+    const int U = *d_num_unique;
+    const int u0 = tile_seg0[tile];
+    const int words = dim / 4;
+
+    headmark[t] = 0;
+    if (t == 0) headmark[kBwdTile] = 0;
+    __syncthreads();
+    {
+        const int cand = u0 + 1 + t;
+        if (cand <= U) {
+            const int rel = occ_offsets[cand] - tile_start;  // >= 1
+            if (rel <= kBwdTile) headmark[rel] = 1;
+        }
+    }
+    __syncthreads();
+    const int flag = t > 0 ? headmark[t] : 0;
+    int is_head = flag;
+    if (t == 0) is_head = occ_offsets[u0] == tile_start ? 1 : 0;
+    const int is_tail = headmark[t + 1];
+    int total;
+    const int seg = u0 + block_excl_scan<4>(flag, scan_tmp, &total) + flag;
+
+    int sr = 0, dst = -1;
+    float w = 1.f;
+    if (valid) {
+        sr = src_row[occ[i]];
+        if (MEAN) {
+            const int len = bag_offsets[sr + 1] - bag_offsets[sr];
+            w = 1.f / static_cast<float>(len);
+        }
+        if (is_tail) dst = unique_to_send ? unique_to_send[seg] : seg;
+    }
+    if (valid && t == min(n - tile_start, kBwdTile) - 1) {
+        // the tile owns the segment that runs past its end only if that segment starts inside the tile
+        const bool starts_here = seg > u0 || occ_offsets[u0] == tile_start;
+        tile_rseg[tile] = (!is_tail && starts_here) ? seg : -1;
+    }
+
+    // ---- each group walks its strip of LPR positions -------------------------------------------------
+    const int g = t / LPR, r = t % LPR;
+    int cnt = n - (tile_start + g * LPR);
+    cnt = cnt < 0 ? 0 : (cnt > LPR ? LPR : cnt);
+    const int wbits = __float_as_int(w);
+    float4 acc[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+    bool open_left = false, le = false, lc = false, re = false;
+    int ld = -1;
+    bool last_tail = true;
+    for (int k0 = 0; k0 < cnt; k0 += kBwdUnroll) {
+        float4 x[kBwdUnroll][NV];
+#pragma unroll
+        for (int q = 0; q < kBwdUnroll; ++q) {
+            const bool on = k0 + q < cnt;
+            const int srk = group_bcast<LPR>(sr, on ? k0 + q : 0);
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int wv = r + v * LPR;
+                x[q][v] = (on && wv < words) ? load_dy(dY, static_cast<size_t>(srk), dim, wv) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < kBwdUnroll; ++q) {
+            const int k = k0 + q;
+            if (k < cnt) {
+                const int hk = group_bcast<LPR>(is_head, k);
+                const int tk = group_bcast<LPR>(is_tail, k);
+                const int dk = group_bcast<LPR>(dst, k);
+                const float wk = MEAN ? __int_as_float(group_bcast<LPR>(wbits, k)) : 1.f;
+                if (k == 0) open_left = !hk;
+                else if (hk) open_left = false;
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    if (MEAN) {
+                        acc[v].x = fmaf(wk, x[q][v].x, acc[v].x);
+                        acc[v].y = fmaf(wk, x[q][v].y, acc[v].y);
+                        acc[v].z = fmaf(wk, x[q][v].z, acc[v].z);
+                        acc[v].w = fmaf(wk, x[q][v].w, acc[v].w);
+                    } else {
+                        acc[v].x += x[q][v].x;
+                        acc[v].y += x[q][v].y;
+                        acc[v].z += x[q][v].z;
+                        acc[v].w += x[q][v].w;
+                    }
+                }
+                last_tail = tk != 0;
+                if (tk) {
+                    if (!open_left) {
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) {
+                            const int wv = r + v * LPR;
+                            if (wv < words) reinterpret_cast<float4*>(grads + static_cast<size_t>(dk) * dim)[wv] = acc[v];
+                        }
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) lpart[g * ROWW + r + v * LPR] = acc[v];
+                        le = true;
+                        lc = true;
+                        ld = dk;
+                    }
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+        }
+    }
+    if (cnt > 0 && !last_tail) {
+        if (open_left) {  // one segment covers the whole strip and goes on
+#pragma unroll
+            for (int v = 0; v < NV; ++v) lpart[g * ROWW + r + v * LPR] = acc[v];
+            le = true;
+            lc = false;
+        } else {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) rpart[g * ROWW + r + v * LPR] = acc[v];
+            re = true;
+        }
+    }
+    if (r == 0) {
+        l_exists[g] = le;
+        l_closed[g] = lc;
+        l_dst[g] = ld;
+        r_exists[g] = re;
+    }
+    __syncthreads();
+
+    // ---- combine the cut sums across the groups, in strip order; thread c owns word c of the row ----
+    if (t < ROWW) {
+        float4 carry = make_float4(0.f, 0.f, 0.f, 0.f);
+        bool open = false, started_here = false;
+        for (int gg = 0; gg < GPB; ++gg) {
+            if (l_exists[gg]) {
+                const float4 p = lpart[gg * ROWW + t];
+                if (open) {
+                    carry.x += p.x;
+                    carry.y += p.y;
+                    carry.z += p.z;
+                    carry.w += p.w;
+                } else {
+                    carry = p;
+                    started_here = false;
+                    open = true;
+                }
+                if (l_closed[gg]) {
+                    if (t < words) {
+                        if (started_here) reinterpret_cast<float4*>(grads + static_cast<size_t>(l_dst[gg]) * dim)[t] = carry;
+                        else reinterpret_cast<float4*>(tile_left + static_cast<size_t>(tile) * dim)[t] = carry;
+                    }
+                    open = false;
+                }
+            }
+            if (r_exists[gg]) {
+                carry = rpart[gg * ROWW + t];
+                open = true;
+                started_here = true;
+            }
+        }
+        if (open && t < words) {
+            if (started_here) reinterpret_cast<float4*>(tile_right + static_cast<size_t>(tile) * dim)[t] = carry;
+            else reinterpret_cast<float4*>(tile_left + static_cast<size_t>(tile) * dim)[t] = carry;
+        }
+    }
+}
+
+// One block per tile whose last segment runs on into later tiles.
+template <int LPR, int NV>
+__global__ void __launch_bounds__(256)
+bwd_fixup_kernel(int dim, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
+                 const float* __restrict__ tile_left, const float* __restrict__ tile_right, const int32_t* __restrict__ tile_rseg,
+                 float* __restrict__ grads) {
+    constexpr int GPB = 256 / LPR;
+    constexpr int ROWW = LPR * NV;
+    __shared__ float4 part[GPB * ROWW];
+    const int tile = blockIdx.x;
+    const int seg = tile_rseg[tile];
+    if (seg < 0) return;
+    const int end = occ_offsets[seg + 1];
+    const int last_tile = (end - 1) / kBwdTile;
+    const int count = last_tile - tile;  // left partials to add, >= 1
+    const int g = threadIdx.x / LPR, r = threadIdx.x % LPR;
+    const int words = dim / 4;
+    const int per = (count + GPB - 1) / GPB;
+    const int c0 = g * per;
+    const int c1 = c0 + per < count ? c0 + per : count;
+    float4 acc[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = c0; c < c1; ++c) {
+        const float4* src = reinterpret_cast<const float4*>(tile_left + static_cast<size_t>(tile + 1 + c) * dim);
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int wv = r + v * LPR;
+            if (wv < words) {
+                const float4 p = src[wv];
+                acc[v].x += p.x;
+                acc[v].y += p.y;
+                acc[v].z += p.z;
+                acc[v].w += p.w;
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < NV; ++v) part[g * ROWW + r + v * LPR] = acc[v];
+    __syncthreads();
+    const int t = threadIdx.x;
+    if (t < words) {
+        float4 s = reinterpret_cast<const float4*>(tile_right + static_cast<size_t>(tile) * dim)[t];
+        for (int gg = 0; gg < GPB; ++gg) {
+            if (gg * per < count) {
+                const float4 p = part[gg * ROWW + t];
+                s.x += p.x;
+                s.y += p.y;
+                s.z += p.z;
+                s.w += p.w;
+            }
+        }
+        const int dst = unique_to_send ? unique_to_send[seg] : seg;
+        reinterpret_cast<float4*>(grads + static_cast<size_t>(dst) * dim)[t] = s;
+    }
+}
+
+struct BwdWs {
+    size_t total;
+    int num_tiles;
+};
+
+inline BwdWs bwd_ws_layout(int32_t n, int32_t dim) {
+    BwdWs w;
+    w.num_tiles = (n + kBwdTile - 1) / kBwdTile;
+    w.total = align_up(4 * static_cast<size_t>(n), 256)                              // src_row
+              + 2 * align_up(4 * static_cast<size_t>(w.num_tiles) * dim, 256)        // tile_left, tile_right
+              + 2 * align_up(4 * static_cast<size_t>(w.num_tiles), 256);             // tile_seg0, tile_rseg
+    return w;
+}
+
+struct BwdArgs {
+    const void* dY;
+    int dy_dtype, dim, mode, max_len;
+    const int32_t* bag_offsets;
+    int num_bags, n;
+    const int32_t* occ_offsets;
+    const int32_t* occ;
+    const int32_t* d_num_unique;
+    const int32_t* unique_to_send;
+    float* grads;
+    void* ws;
+    hipStream_t stream;
+};
+
+template <int LPR, int NV>
+void bwd_launch(const BwdArgs& a) {
+    const BwdWs L = bwd_ws_layout(a.n, a.dim);
+    WsCursor cur(a.ws);
+    int32_t* src_row = cur.take<int32_t>(a.n);
+    float* tile_left = cur.take<float>(static_cast<size_t>(L.num_tiles) * a.dim);
+    float* tile_right = cur.take<float>(static_cast<size_t>(L.num_tiles) * a.dim);
+    int32_t* tile_seg0 = cur.take<int32_t>(L.num_tiles);
+    int32_t* tile_rseg = cur.take<int32_t>(L.num_tiles);
+    const int seq = a.mode == NP_SEQ ? 1 : 0;
+    const int64_t avg = a.n / (a.num_bags > 0 ? a.num_bags : 1);
+    if (avg <= 6) {
+        NP_LAUNCH("bwd_expand", bwd_expand_kernel<4>, dim3((a.num_bags + 63) / 64), dim3(256), 0, a.stream, a.bag_offsets,
+                  a.num_bags, seq, a.max_len, src_row);
+    } else if (avg <= 24) {
+        NP_LAUNCH("bwd_expand", bwd_expand_kernel<16>, dim3((a.num_bags + 15) / 16), dim3(256), 0, a.stream, a.bag_offsets,
+                  a.num_bags, seq, a.max_len, src_row);
+    } else {
+        NP_LAUNCH("bwd_expand", bwd_expand_kernel<64>, dim3((a.num_bags + 3) / 4), dim3(256), 0, a.stream, a.bag_offsets,
+                  a.num_bags, seq, a.max_len, src_row);
+    }
+    NP_LAUNCH("bwd_tile_seg0", bwd_tile_seg0_kernel, dim3((L.num_tiles + 255) / 256), dim3(256), 0, a.stream, a.occ_offsets,
+              a.d_num_unique, L.num_tiles, tile_seg0);
+    const bool mean = a.mode == NP_POOL_MEAN;
+    if (a.dy_dtype == NP_BF16) {
+        const uint16_t* dy = static_cast<const uint16_t*>(a.dY);
+        if (mean)
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, uint16_t>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
+                      a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, src_row, tile_seg0, a.grads,
+                      tile_left, tile_right, tile_rseg);
+        else
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, uint16_t>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
+                      a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, src_row, tile_seg0, a.grads,
+                      tile_left, tile_right, tile_rseg);
+    } else {
+        const float* dy = static_cast<const float*>(a.dY);
+        if (mean)
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, float>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
+                      a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, src_row, tile_seg0, a.grads,
+                      tile_left, tile_right, tile_rseg);
+        else
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, float>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
+                      a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, src_row, tile_seg0, a.grads,
+                      tile_left, tile_right, tile_rseg);
+    }
+    NP_LAUNCH("bwd_fixup", (bwd_fixup_kernel<LPR, NV>), dim3(L.num_tiles), dim3(256), 0, a.stream, a.dim, a.occ_offsets,
+              a.unique_to_send, tile_left, tile_right, tile_rseg, a.grads);
+}
+
+}  // namespace np
+
+extern "C" {
+
+size_t np_lookup_bwd_workspace_bytes(int32_t num_bags, int32_t n, int32_t dim, int32_t mode) {
+    (void)num_bags;
+    (void)mode;
+    if (n <= 0 || dim < 4) return 0;
+    return np::bwd_ws_layout(n, dim).total;
+}
+
+int np_lookup_bwd(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
+                  const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
+                  const int32_t* occ, const int32_t* d_num_unique, int32_t cap, const int32_t* unique_to_send,
+                  float* grads, void* ws, size_t ws_bytes, void* stream) {
+    if (num_bags < 0 || n < 0 || cap < 0 || !d_num_unique) return NP_ERR_INVALID_ARG;
+    if (mode != NP_POOL_SUM && mode != NP_POOL_MEAN && mode != NP_SEQ) return NP_ERR_INVALID_ARG;
+    if (dy_dtype != NP_F32 && dy_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
+    if (mode == NP_SEQ && max_len < 1) return NP_ERR_INVALID_ARG;
+    if (dim < 4 || dim % 4 != 0 || dim > NP_MAX_DIM) return NP_ERR_UNSUPPORTED;
+    if (mode == NP_SEQ && static_cast<int64_t>(num_bags) * max_len > INT32_MAX) return NP_ERR_UNSUPPORTED;
+    if (n == 0) return NP_OK;  // no lookups: no key receives a gradient, nothing to write
+    if (!dY || !bag_offsets || !occ_offsets || !occ || !grads || num_bags < 1) return NP_ERR_INVALID_ARG;
+    if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(grads, 16)) return NP_ERR_INVALID_ARG;
+    if (!ws || !np::aligned(ws, 256) || ws_bytes < np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode)) return NP_ERR_WORKSPACE;
+    np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, unique_to_send,
+                  grads, ws, static_cast<hipStream_t>(stream)};
+    const int words = dim / 4;
+    if (words <= 4) np::bwd_launch<4, 1>(a);
+    else if (words <= 8) np::bwd_launch<8, 1>(a);
+    else if (words <= 16) np::bwd_launch<16, 1>(a);
+    else if (words <= 32) np::bwd_launch<32, 1>(a);
+    else if (words <= 64) np::bwd_launch<64, 1>(a);
+    else if (words <= 128) np::bwd_launch<64, 2>(a);
+    else np::bwd_launch<64, 4>(a);
+    return np::launch_status();
+}
+
+}  // extern "C"

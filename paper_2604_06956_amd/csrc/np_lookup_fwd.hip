@@ -1,0 +1,237 @@
+// np_lookup_fwd: gather rows of the key list from the HBM-resident table and pool them per bag, or lay
+// them out as a padded sequence (Section IV-A, "Embedding Retrieval" and the start of "Fwd/Bwd").
+//
+// A row of dim floats is dim/4 float4 words.  LPR lanes (a power of two, 4..64) share a row, each holding
+// NV words, so every row access is a run of 16-byte loads from consecutive lanes.  One LPR-lane group owns
+// one bag (pooled modes) or one output position (sequence mode); a 64-lane wave therefore works on
+// 64/LPR bags at once.  The group first fetches the slot and key of up to LPR lookups with one lane each,
+// then walks them in ascending order broadcasting the key, several row loads in flight at a time.
+#include "np_common.hpp"
+
+namespace np {
+
+template <int LPR>
+__device__ __forceinline__ int64_t group_bcast64(int64_t v, int src_in_group) {
+    const int src = (__lane_id() & ~(LPR - 1)) + src_in_group;
+    const int lo = __shfl(static_cast<int>(v & 0xFFFFFFFFll), src, kWave);
+    const int hi = __shfl(static_cast<int>(v >> 32), src, kWave);
+    return (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
+}
+
+__device__ __forceinline__ void store_words(float* p, const float4& a) { *reinterpret_cast<float4*>(p) = a; }
+
+__device__ __forceinline__ void store_words(uint16_t* p, const float4& a) {
+    uint2 o;
+    o.x = static_cast<uint32_t>(f32_to_bf16(a.x)) | (static_cast<uint32_t>(f32_to_bf16(a.y)) << 16);
+    o.y = static_cast<uint32_t>(f32_to_bf16(a.z)) | (static_cast<uint32_t>(f32_to_bf16(a.w)) << 16);
+    *reinterpret_cast<uint2*>(p) = o;
+}
+
+constexpr int kFwdUnroll = 4;
+
+template <int LPR, int NV, bool MEAN, typename OutT>
+__global__ void __launch_bounds__(256)
+fwd_pool_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx,
+                const int32_t* __restrict__ bag_offsets, int num_bags, OutT* __restrict__ out) {
+    constexpr int GPB = 256 / LPR;
+    const int r = threadIdx.x % LPR;
+    const int64_t b = static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR;
+    if (b >= num_bags) return;  // whole groups leave together
+    const int lo = bag_offsets[b], hi = bag_offsets[b + 1];
+    const int words = dim / 4;
+    float4 acc[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    for (int base = lo; base < hi; base += LPR) {
+        const int j = base + r;
+        int64_t row = 0;
+        if (j < hi) row = list_keys[idx ? idx[j] : j];
+        const int cnt = hi - base < LPR ? hi - base : LPR;
+        for (int k0 = 0; k0 < cnt; k0 += kFwdUnroll) {
+            float4 x[kFwdUnroll][NV];
+#pragma unroll
+            for (int q = 0; q < kFwdUnroll; ++q) {
+                const bool on = k0 + q < cnt;  // uniform inside the group
+                const int64_t rk = group_bcast64<LPR>(row, on ? k0 + q : 0);
+                const float4* src = reinterpret_cast<const float4*>(table + static_cast<size_t>(rk) * dim);
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const int wv = r + v * LPR;
+                    x[q][v] = (on && wv < words) ? src[wv] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kFwdUnroll; ++q) {
+                if (k0 + q < cnt) {
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) {
+                        acc[v].x += x[q][v].x;
+                        acc[v].y += x[q][v].y;
+                        acc[v].z += x[q][v].z;
+                        acc[v].w += x[q][v].w;
+                    }
+                }
+            }
+        }
+    }
+    float scale = 1.f;
+    if (MEAN && hi > lo) scale = 1.f / static_cast<float>(hi - lo);
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int wv = r + v * LPR;
+        if (wv < words) {
+            float4 a = acc[v];
+            if (MEAN) {
+                a.x *= scale;
+                a.y *= scale;
+                a.z *= scale;
+                a.w *= scale;
+            }
+            store_words(out + static_cast<size_t>(b) * dim + wv * 4, a);
+        }
+    }
+}
+
+template <int LPR, int NV, typename OutT>
+__global__ void __launch_bounds__(256)
+fwd_seq_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx,
+               const int32_t* __restrict__ bag_offsets, int num_bags, int max_len, OutT* __restrict__ out) {
+    constexpr int GPB = 256 / LPR;
+    const int r = threadIdx.x % LPR;
+    const int64_t q = static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR;  // output position
+    const int64_t total = static_cast<int64_t>(num_bags) * max_len;
+    if (q >= total) return;
+    int b;
+    if (total <= 0xFFFFFFFFll)
+        b = static_cast<int>(static_cast<uint32_t>(q) / static_cast<uint32_t>(max_len));
+    else
+        b = static_cast<int>(q / max_len);
+    const int p = static_cast<int>(q - static_cast<int64_t>(b) * max_len);
+    const int lo = bag_offsets[b], len = bag_offsets[b + 1] - lo;
+    const int words = dim / 4;
+    const float4* src = nullptr;
+    if (p < len) {
+        const int j = lo + p;
+        const int64_t row = list_keys[idx ? idx[j] : j];
+        src = reinterpret_cast<const float4*>(table + static_cast<size_t>(row) * dim);
+    }
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int wv = r + v * LPR;
+        if (wv < words) {
+            const float4 a = src ? src[wv] : make_float4(0.f, 0.f, 0.f, 0.f);
+            store_words(out + static_cast<size_t>(q) * dim + wv * 4, a);
+        }
+    }
+}
+
+template <int LPR, int NV>
+__global__ void __launch_bounds__(256)
+fwd_rows_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys,
+                const int32_t* __restrict__ d_num_list, float* __restrict__ rows_out) {
+    constexpr int GPB = 256 / LPR;
+    const int r = threadIdx.x % LPR;
+    const int words = dim / 4;
+    const int L = *d_num_list;
+    for (int64_t p = static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR; p < L; p += static_cast<int64_t>(gridDim.x) * GPB) {
+        const float4* src = reinterpret_cast<const float4*>(table + static_cast<size_t>(list_keys[p]) * dim);
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int wv = r + v * LPR;
+            if (wv < words) *reinterpret_cast<float4*>(rows_out + static_cast<size_t>(p) * dim + wv * 4) = src[wv];
+        }
+    }
+}
+
+struct FwdArgs {
+    const float* table;
+    int dim;
+    const int64_t* list_keys;
+    const int32_t* d_num_list;
+    int cap;
+    const int32_t* idx;
+    const int32_t* bag_offsets;
+    int num_bags, mode, max_len, out_dtype;
+    void* out;
+    float* rows_out;
+    hipStream_t stream;
+};
+
+template <int LPR, int NV>
+void fwd_launch(const FwdArgs& a) {
+    constexpr int GPB = 256 / LPR;
+    if (a.num_bags > 0) {
+        if (a.mode == NP_SEQ) {
+            const int64_t total = static_cast<int64_t>(a.num_bags) * a.max_len;
+            const unsigned grid = static_cast<unsigned>((total + GPB - 1) / GPB);
+            if (a.out_dtype == NP_BF16)
+                NP_LAUNCH("fwd_seq", (fwd_seq_kernel<LPR, NV, uint16_t>), dim3(grid), dim3(256), 0, a.stream, a.table, a.dim,
+                          a.list_keys, a.idx, a.bag_offsets, a.num_bags, a.max_len, static_cast<uint16_t*>(a.out));
+            else
+                NP_LAUNCH("fwd_seq", (fwd_seq_kernel<LPR, NV, float>), dim3(grid), dim3(256), 0, a.stream, a.table, a.dim,
+                          a.list_keys, a.idx, a.bag_offsets, a.num_bags, a.max_len, static_cast<float*>(a.out));
+        } else {
+            const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(a.num_bags) + GPB - 1) / GPB);
+            const bool mean = a.mode == NP_POOL_MEAN;
+            if (a.out_dtype == NP_BF16) {
+                if (mean)
+                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, true, uint16_t>), dim3(grid), dim3(256), 0, a.stream, a.table,
+                              a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, static_cast<uint16_t*>(a.out));
+                else
+                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, false, uint16_t>), dim3(grid), dim3(256), 0, a.stream, a.table,
+                              a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, static_cast<uint16_t*>(a.out));
+            } else {
+                if (mean)
+                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, true, float>), dim3(grid), dim3(256), 0, a.stream, a.table,
+                              a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, static_cast<float*>(a.out));
+                else
+                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, false, float>), dim3(grid), dim3(256), 0, a.stream, a.table,
+                              a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, static_cast<float*>(a.out));
+            }
+        }
+    }
+    if (a.rows_out && a.cap > 0) {
+        int64_t want = (static_cast<int64_t>(a.cap) + GPB - 1) / GPB;
+        const unsigned grid = static_cast<unsigned>(want < 16384 ? want : 16384);
+        NP_LAUNCH("fwd_rows", (fwd_rows_kernel<LPR, NV>), dim3(grid), dim3(256), 0, a.stream, a.table, a.dim, a.list_keys,
+                  a.d_num_list, a.rows_out);
+    }
+}
+
+}  // namespace np
+
+extern "C" {
+
+size_t np_lookup_fwd_workspace_bytes(int32_t, int32_t, int32_t, int32_t) { return 0; }
+
+int np_lookup_fwd(const float* table, int64_t num_rows, int32_t dim, const int64_t* list_keys,
+                  const int32_t* d_num_list, int32_t cap, const int32_t* idx, const int32_t* bag_offsets,
+                  int32_t num_bags, int32_t n, int32_t mode, int32_t max_len, int32_t out_dtype, void* out,
+                  float* rows_out, void* ws, size_t ws_bytes, void* stream) {
+    (void)ws;
+    (void)ws_bytes;
+    if (!table || num_rows < 1 || num_bags < 0 || n < 0 || cap < 0 || !bag_offsets) return NP_ERR_INVALID_ARG;
+    if (mode != NP_POOL_SUM && mode != NP_POOL_MEAN && mode != NP_SEQ) return NP_ERR_INVALID_ARG;
+    if (out_dtype != NP_F32 && out_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
+    if (mode == NP_SEQ && max_len < 1) return NP_ERR_INVALID_ARG;
+    if (dim < 4 || dim % 4 != 0 || dim > NP_MAX_DIM) return NP_ERR_UNSUPPORTED;
+    if ((num_bags > 0 && !out) || (n > 0 && !list_keys)) return NP_ERR_INVALID_ARG;
+    if (rows_out && (!d_num_list || !list_keys)) return NP_ERR_INVALID_ARG;
+    if (!np::aligned(table, 16) || !np::aligned(out, out_dtype == NP_BF16 ? 8 : 16) || !np::aligned(rows_out, 16))
+        return NP_ERR_INVALID_ARG;
+    if (mode == NP_SEQ && static_cast<int64_t>(num_bags) * max_len > (int64_t(1) << 40)) return NP_ERR_UNSUPPORTED;
+    np::FwdArgs a{table, dim, list_keys, d_num_list, cap, idx, bag_offsets, num_bags, mode, max_len, out_dtype, out, rows_out,
+                  static_cast<hipStream_t>(stream)};
+    const int words = dim / 4;
+    if (words <= 4) np::fwd_launch<4, 1>(a);
+    else if (words <= 8) np::fwd_launch<8, 1>(a);
+    else if (words <= 16) np::fwd_launch<16, 1>(a);
+    else if (words <= 32) np::fwd_launch<32, 1>(a);
+    else if (words <= 64) np::fwd_launch<64, 1>(a);
+    else if (words <= 128) np::fwd_launch<64, 2>(a);
+    else np::fwd_launch<64, 4>(a);
+    return np::launch_status();
+}
+
+}  // extern "C"

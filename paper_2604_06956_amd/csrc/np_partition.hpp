@@ -1,0 +1,267 @@
+// Stable multi-way partition of a sequence by a small integer "digit", the building block of both the
+// radix sort inside np_dedup (digit = a bit field of the key) and the bucketing of np_route (digit =
+// owner shard).  Three kernels per pass, no inter-block waiting:
+//
+//   part_hist     one block per chunk: LDS histogram of the chunk's digits           -> H[chunk][bin]
+//   part_colscan  exclusive scan of every column of H over the chunks (in place)      -> binTotal[bin]
+//   part_scatter  one block per chunk, tile by tile: wave-ballot ranking gives every item its stable
+//                 rank inside the tile, the tile is reordered through LDS and written out in runs
+//
+// A chunk is a run of consecutive tiles owned by one block, sized so that at most kTargetChunks blocks
+// cover the input: all of them are resident at once (no tail wave) and the histogram matrix stays small.
+// The scatter kernel maps chunks to blocks so that neighbouring chunks run on the same die: the short
+// runs they append to each bin then merge in that die's L2 instead of reaching HBM as partial lines.
+#pragma once
+
+#include "np_common.hpp"
+
+namespace np {
+
+constexpr int kPartThreads = 256;
+constexpr int kPartWaves = kPartThreads / kWave;
+constexpr int kPartIPT = 16;
+constexpr int kPartTile = kPartThreads * kPartIPT;
+constexpr int kPartMaxBins = 4096;
+constexpr int kTargetChunks = 1024;
+constexpr int kColscanThreads = 1024;
+
+struct ChunkPlan {
+    int num_chunks;
+    int chunk_items;  // multiple of kPartTile
+};
+
+inline ChunkPlan make_chunk_plan(int64_t cap) {
+    int64_t tiles = (cap + kPartTile - 1) / kPartTile;
+    if (tiles < 1) tiles = 1;
+    const int64_t tpc = (tiles + kTargetChunks - 1) / kTargetChunks;
+    ChunkPlan p;
+    p.num_chunks = static_cast<int>((tiles + tpc - 1) / tpc);
+    p.chunk_items = static_cast<int>(tpc * kPartTile);
+    return p;
+}
+
+inline size_t part_hist_elems(const ChunkPlan& p, int bins) { return static_cast<size_t>(p.num_chunks) * bins; }
+
+template <typename KeyT>
+inline size_t part_scatter_lds_bytes(int bins, bool stage_digit) {
+    const size_t fixed = 3 * sizeof(uint32_t) * bins + 64;  // gofs, binstart, btot, scan scratch
+    const size_t cnt = sizeof(uint32_t) * kPartWaves * bins;
+    size_t stage = (sizeof(KeyT) + sizeof(uint32_t)) * kPartTile;
+    if (stage_digit) stage += sizeof(uint16_t) * kPartTile;
+    return fixed + (cnt > stage ? cnt : stage);
+}
+
+// Lanes of the wave holding the same digit as this lane (only lanes with valid == true take part).
+__device__ __forceinline__ uint64_t match_any(uint32_t d, int nbits, bool valid) {
+    uint64_t peers = __ballot(valid);
+    for (int b = 0; b < nbits; ++b) {
+        const bool bit = (d >> b) & 1u;
+        const uint64_t bal = __ballot(bit);
+        peers &= bit ? bal : ~bal;
+    }
+    return peers;
+}
+
+// A policy supplies:
+//   using KeyT; static constexpr bool kStageDigit;
+//   __device__ void load(int64_t i, KeyT& k, uint32_t& v) const;   item i of the input
+//   __device__ KeyT load_key(int64_t i) const;
+//   __device__ uint32_t digit(KeyT k) const;
+//   __device__ void store(uint32_t dst, KeyT k, uint32_t v) const; item placed at output slot dst
+//   __device__ void placed(int64_t i, uint32_t dst) const;         input item i went to dst (may be a no-op)
+
+template <class P>
+__global__ void __launch_bounds__(kPartThreads)
+part_hist_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, ChunkPlan plan, uint32_t* __restrict__ H) {
+    extern __shared__ uint32_t lh[];
+    const int c = blockIdx.x;
+    const int64_t n = d_n ? *d_n : n_host;
+    for (int b = threadIdx.x; b < bins; b += kPartThreads) lh[b] = 0;
+    __syncthreads();
+    const int64_t lo = static_cast<int64_t>(c) * plan.chunk_items;
+    int64_t hi = lo + plan.chunk_items;
+    if (hi > n) hi = n;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kPartThreads) atomicAdd(&lh[pol.digit(pol.load_key(i))], 1u);
+    __syncthreads();
+    for (int b = threadIdx.x; b < bins; b += kPartThreads) H[static_cast<size_t>(c) * bins + b] = lh[b];
+}
+
+// Block = 16 waves x 64 bins: wave y sums, then rewrites as exclusive prefixes, its slice of the chunks.
+template <int THREADS>
+__global__ void __launch_bounds__(THREADS)
+part_colscan_kernel(uint32_t* __restrict__ H, int num_chunks, int bins, uint32_t* __restrict__ bin_total) {
+    constexpr int NY = THREADS / kWave;
+    __shared__ uint32_t part[NY][kWave];
+    const int lane = threadIdx.x % kWave, y = threadIdx.x / kWave;
+    const int bin = blockIdx.x * kWave + lane;
+    const int per = (num_chunks + NY - 1) / NY;
+    const int c0 = y * per;
+    const int c1 = c0 + per < num_chunks ? c0 + per : num_chunks;
+    uint32_t sum = 0;
+    if (bin < bins)
+        for (int c = c0; c < c1; ++c) sum += H[static_cast<size_t>(c) * bins + bin];
+    part[y][lane] = sum;
+    __syncthreads();
+    uint32_t base = 0, total = 0;
+#pragma unroll
+    for (int yy = 0; yy < NY; ++yy) {
+        const uint32_t s = part[yy][lane];
+        if (yy < y) base += s;
+        total += s;
+    }
+    if (bin < bins) {
+        uint32_t run = base;
+        for (int c = c0; c < c1; ++c) {
+            const size_t a = static_cast<size_t>(c) * bins + bin;
+            const uint32_t t = H[a];
+            H[a] = run;
+            run += t;
+        }
+        if (y == 0) bin_total[bin] = total;
+    }
+}
+
+template <class P>
+__global__ void __launch_bounds__(kPartThreads)
+part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, int nbits, ChunkPlan plan,
+                    const uint32_t* __restrict__ H, const uint32_t* __restrict__ bin_total,
+                    int32_t* __restrict__ totals_out /* nullable: [bins] */, int32_t* __restrict__ offsets_out /* nullable: [bins+1] */) {
+    using KeyT = typename P::KeyT;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    uint32_t* gofs = reinterpret_cast<uint32_t*>(smem_raw);
+    uint32_t* binstart = gofs + bins;
+    uint32_t* btot = binstart + bins;
+    int* scan_tmp = reinterpret_cast<int*>(btot + bins);  // 16 ints
+    unsigned char* un = reinterpret_cast<unsigned char*>(scan_tmp + 16);
+    volatile uint32_t* cnt = reinterpret_cast<volatile uint32_t*>(un);  // [waves][bins], aliased with the staging area
+    KeyT* skey = reinterpret_cast<KeyT*>(un);
+    uint32_t* sval = reinterpret_cast<uint32_t*>(skey + kPartTile);
+    uint16_t* sdig = reinterpret_cast<uint16_t*>(sval + kPartTile);
+
+    const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
+    const int c = xcd_remap(blockIdx.x, gridDim.x);
+    const int64_t n = d_n ? *d_n : n_host;
+    const int bpt = (bins + kPartThreads - 1) / kPartThreads;
+    const int b0 = tid * bpt;
+    const int b1 = b0 + bpt < bins ? b0 + bpt : bins;
+
+    // global offset of this chunk's first item of every bin
+    {
+        int local = 0;
+        for (int b = b0; b < b1; ++b) local += static_cast<int>(bin_total[b]);
+        int total;
+        int run = block_excl_scan<kPartWaves>(local, scan_tmp, &total);
+        for (int b = b0; b < b1; ++b) {
+            const uint32_t t = bin_total[b];
+            gofs[b] = static_cast<uint32_t>(run) + H[static_cast<size_t>(c) * bins + b];
+            if (c == 0 && totals_out) totals_out[b] = static_cast<int32_t>(t);
+            if (c == 0 && offsets_out) offsets_out[b] = run;
+            run += static_cast<int>(t);
+        }
+        if (c == 0 && offsets_out && tid == 0) offsets_out[bins] = total;
+    }
+    __syncthreads();
+
+    const int64_t lo = static_cast<int64_t>(c) * plan.chunk_items;
+    int64_t hi = lo + plan.chunk_items;
+    if (hi > n) hi = n;
+    const uint64_t lt = lanemask_lt();
+
+    for (int64_t tile_base = lo; tile_base < hi; tile_base += kPartTile) {
+        const int tile_count = hi - tile_base < kPartTile ? static_cast<int>(hi - tile_base) : kPartTile;
+        for (int i = tid; i < kPartWaves * bins; i += kPartThreads) cnt[i] = 0;
+        __syncthreads();
+
+        KeyT k[kPartIPT];
+        uint32_t v[kPartIPT], d[kPartIPT], r[kPartIPT];
+#pragma unroll
+        for (int i = 0; i < kPartIPT; ++i) {
+            const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
+            k[i] = KeyT(0);
+            v[i] = 0;
+            d[i] = 0;
+            if (idx < tile_count) {
+                pol.load(tile_base + idx, k[i], v[i]);
+                d[i] = pol.digit(k[i]);
+            }
+        }
+        // stable rank of every item among the items of its wave with the same digit
+#pragma unroll
+        for (int i = 0; i < kPartIPT; ++i) {
+            const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
+            const bool valid = idx < tile_count;
+            const uint64_t peers = match_any(d[i], nbits, valid);
+            volatile uint32_t* ctr = cnt + w * bins + d[i];
+            const uint32_t pre = *ctr;
+            const uint64_t below = peers & lt;
+            r[i] = pre + __popcll(below);
+            __builtin_amdgcn_wave_barrier();
+            if (valid && below == 0) *ctr = pre + __popcll(peers);
+            __builtin_amdgcn_wave_barrier();
+        }
+        __syncthreads();
+        // per bin: exclusive scan over the waves, total of the tile
+        int local = 0;
+        for (int b = b0; b < b1; ++b) {
+            uint32_t s = 0;
+#pragma unroll
+            for (int ww = 0; ww < kPartWaves; ++ww) {
+                const uint32_t t = cnt[ww * bins + b];
+                cnt[ww * bins + b] = s;
+                s += t;
+            }
+            btot[b] = s;
+            local += static_cast<int>(s);
+        }
+        int total;
+        int run = block_excl_scan<kPartWaves>(local, scan_tmp, &total);
+        for (int b = b0; b < b1; ++b) {
+            binstart[b] = static_cast<uint32_t>(run);
+            run += static_cast<int>(btot[b]);
+        }
+        __syncthreads();
+        uint32_t pos[kPartIPT];
+#pragma unroll
+        for (int i = 0; i < kPartIPT; ++i) {
+            const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
+            const uint32_t in_bin = cnt[w * bins + d[i]] + r[i];
+            pos[i] = binstart[d[i]] + in_bin;
+            if (idx < tile_count) pol.placed(tile_base + idx, gofs[d[i]] + in_bin);
+        }
+        __syncthreads();  // the counters are dead from here on: their storage becomes the staging area
+#pragma unroll
+        for (int i = 0; i < kPartIPT; ++i) {
+            const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
+            if (idx < tile_count) {
+                skey[pos[i]] = k[i];
+                sval[pos[i]] = v[i];
+                if (P::kStageDigit) sdig[pos[i]] = static_cast<uint16_t>(d[i]);
+            }
+        }
+        __syncthreads();
+        for (int p = tid; p < tile_count; p += kPartThreads) {
+            const KeyT key = skey[p];
+            const uint32_t dd = P::kStageDigit ? static_cast<uint32_t>(sdig[p]) : pol.digit(key);
+            pol.store(gofs[dd] + (static_cast<uint32_t>(p) - binstart[dd]), key, sval[p]);
+        }
+        __syncthreads();
+        for (int b = b0; b < b1; ++b) gofs[b] += btot[b];
+        // the next iteration's first barrier orders these updates before any use
+    }
+}
+
+// Enqueue one partition pass.  H needs part_hist_elems() words, bin_total needs `bins` words.
+template <class P>
+inline void run_partition_pass(const P& pol, int n_host, const int* d_n, int bins, int nbits, const ChunkPlan& plan,
+                               uint32_t* H, uint32_t* bin_total, int32_t* totals_out, int32_t* offsets_out,
+                               hipStream_t stream, const char* tag_hist, const char* tag_scan, const char* tag_scatter) {
+    NP_LAUNCH(tag_hist, part_hist_kernel<P>, dim3(plan.num_chunks), dim3(kPartThreads), sizeof(uint32_t) * bins, stream,
+              pol, n_host, d_n, bins, plan, H);
+    NP_LAUNCH(tag_scan, part_colscan_kernel<kColscanThreads>, dim3((bins + kWave - 1) / kWave), dim3(kColscanThreads), 0, stream, H,
+              plan.num_chunks, bins, bin_total);
+    const size_t lds = part_scatter_lds_bytes<typename P::KeyT>(bins, P::kStageDigit);
+    NP_LAUNCH(tag_scatter, part_scatter_kernel<P>, dim3(plan.num_chunks), dim3(kPartThreads), lds, stream, pol, n_host,
+              d_n, bins, nbits, plan, H, bin_total, totals_out, offsets_out);
+}
+
+}  // namespace np

@@ -1,0 +1,132 @@
+// Host-side odds and ends of the library (version, status text, per-kernel event timing) and the two
+// harness kernels: the stateless table initialiser and the plain copy used as a bandwidth yardstick.
+#include <vector>
+
+#include "np_common.hpp"
+
+namespace np {
+
+namespace {
+struct ProfRecord {
+    const char* name;
+    hipEvent_t start, stop;
+};
+bool g_prof_on = false;
+std::vector<ProfRecord> g_prof_log;                       // records of the current collection window
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_pool;  // events created so far, reused
+size_t g_prof_next = 0;
+}  // namespace
+
+void prof_begin(const char* name, hipStream_t stream) {
+    if (!g_prof_on) return;
+    if (g_prof_next == g_prof_pool.size()) {
+        hipEvent_t a = nullptr, b = nullptr;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+            (void)hipGetLastError();
+            return;
+        }
+        g_prof_pool.emplace_back(a, b);
+    }
+    auto& ev = g_prof_pool[g_prof_next];
+    g_prof_log.push_back({name, ev.first, ev.second});
+    (void)hipEventRecord(ev.first, stream);
+}
+
+void prof_end(hipStream_t stream) {
+    if (!g_prof_on || g_prof_log.size() != g_prof_next + 1) return;
+    (void)hipEventRecord(g_prof_log.back().stop, stream);
+    ++g_prof_next;
+}
+
+// ---------------------------------------------------------------- harness kernels -----------------
+
+__global__ void __launch_bounds__(256) table_init_kernel(float4* __restrict__ table, uint64_t num_words, uint64_t seed_term) {
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+    for (uint64_t w = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; w < num_words; w += stride) {
+        float v[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            uint64_t h = w * 4 + c + seed_term;
+            h ^= h >> 31;
+            h *= 0xD6E8FEB86659FD93ull;
+            h ^= h >> 27;
+            h *= 0xA3B195354A39B70Dull;
+            h ^= h >> 33;
+            const int q = static_cast<int>(h >> 40) - 8388608;
+            v[c] = static_cast<float>(q) * (0.01f / 8388608.0f);
+        }
+        table[w] = make_float4(v[0], v[1], v[2], v[3]);
+    }
+}
+
+__global__ void __launch_bounds__(256) stream_copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src, uint64_t num_words) {
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+    for (uint64_t w = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; w < num_words; w += stride)
+        dst[w] = src[w];
+}
+
+}  // namespace np
+
+extern "C" {
+
+int np_version(void) { return 100; }
+
+const char* np_status_string(int status) {
+    switch (status) {
+        case NP_OK: return "ok";
+        case NP_ERR_INVALID_ARG: return "invalid argument";
+        case NP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case NP_ERR_UNSUPPORTED: return "unsupported configuration";
+        case NP_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int np_util_table_init(float* table, int64_t num_rows, int32_t dim, uint64_t seed, void* stream) {
+    if (!table || num_rows < 0 || dim < 4 || dim % 4 != 0 || !np::aligned(table, 16)) return NP_ERR_INVALID_ARG;
+    const uint64_t words = static_cast<uint64_t>(num_rows) * static_cast<uint64_t>(dim) / 4;
+    if (words == 0) return NP_OK;
+    const uint64_t want = (words + 255) / 256;
+    const unsigned grid = static_cast<unsigned>(want < 65536 ? want : 65536);
+    NP_LAUNCH("table_init", np::table_init_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+              reinterpret_cast<float4*>(table), words, seed * 0x2545F4914F6CDD1Dull);
+    return np::launch_status();
+}
+
+int np_util_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || bytes % 16 != 0 || !np::aligned(dst, 16) || !np::aligned(src, 16)) return NP_ERR_INVALID_ARG;
+    const uint64_t words = bytes / 16;
+    if (words == 0) return NP_OK;
+    const uint64_t want = (words + 255) / 256;
+    const unsigned grid = static_cast<unsigned>(want < 16384 ? want : 16384);
+    NP_LAUNCH("stream_copy", np::stream_copy_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+              static_cast<float4*>(dst), static_cast<const float4*>(src), words);
+    return np::launch_status();
+}
+
+int np_prof_enable(int on) {
+    np::g_prof_on = on != 0;
+    np::g_prof_log.clear();
+    np::g_prof_next = 0;
+    return NP_OK;
+}
+
+int np_prof_collect(const char** names, float* ms, int max_entries) {
+    int count = 0;
+    for (size_t i = 0; i < np::g_prof_next && count < max_entries; ++i) {
+        auto& r = np::g_prof_log[i];
+        float t = 0.f;
+        if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&t, r.start, r.stop) != hipSuccess) {
+            (void)hipGetLastError();
+            t = -1.f;
+        }
+        if (names) names[count] = r.name;
+        if (ms) ms[count] = t;
+        ++count;
+    }
+    np::g_prof_log.clear();
+    np::g_prof_next = 0;
+    return count;
+}
+
+}  // extern "C"

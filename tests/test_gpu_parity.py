@@ -1,0 +1,341 @@
+"""GPU parity: every C-ABI call against the CPU oracle, element by element, on seeded inputs that span
+several tiles and ragged tails, plus the degenerate cases of each step.  Integer outputs must be bit
+exact; values must be within 1e-5 (fp32) / 1e-2 (bf16) of the oracle, measured against the sum of the
+absolute terms of each element."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import gpu_helpers
+    return gpu_helpers
+
+
+# ------------------------------------------------------------------------------------------ harness
+
+def test_table_init_matches_the_numpy_generator(H):
+    import torch
+    for R, D in ((1000, 16), (777, 64), (50, 128)):
+        t = torch.empty((R, D), dtype=torch.float32, device="cuda")
+        H.B.np_util_table_init(t, 7)
+        ref = H.wl.table_init_rows(np.arange(R), D, 7)
+        assert H.host(t).tobytes() == ref.tobytes()
+
+
+# ------------------------------------------------------------------------------------------ dedup
+
+def _keys_case(name):
+    import zlib
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    if name == "one":
+        return np.array([5], np.int64), 3
+    if name == "all_equal":
+        return np.full(10000, 123456, np.int64), 17
+    if name == "all_distinct":
+        return rng.permutation(50000).astype(np.int64), 16
+    if name == "wave_edges":
+        return rng.integers(0, 50, size=64 * 16 * 4 + 1).astype(np.int64), 6
+    if name == "tile_minus_1":
+        return rng.integers(0, 1 << 20, size=4095).astype(np.int64), 20
+    if name == "tile_exact":
+        return rng.integers(0, 1 << 20, size=4096).astype(np.int64), 20
+    if name == "tile_plus_1":
+        return rng.integers(0, 1 << 20, size=4097).astype(np.int64), 20
+    if name == "multi_chunk":
+        return rng.integers(0, 1 << 27, size=5_000_000).astype(np.int64), 27
+    if name == "bits_1":
+        return rng.integers(0, 2, size=30000).astype(np.int64), 1
+    if name == "bits_33":
+        return rng.integers(0, 1 << 33, size=200000).astype(np.int64), 33
+    if name == "bits_40_dups":
+        base = rng.integers(0, 1 << 40, size=3000).astype(np.int64)
+        return base[rng.integers(0, 3000, size=100000)], 40
+    if name == "bits_63":
+        base = rng.integers(0, (1 << 63) - 1, size=5000).astype(np.int64)
+        return base[rng.integers(0, 5000, size=60000)], 63
+    if name == "hot_key":
+        k = rng.integers(0, 1 << 28, size=300000).astype(np.int64)
+        k[rng.random(300000) < 0.4] = 77777777
+        return k, 28
+    raise KeyError(name)
+
+
+DEDUP_CASES = ["one", "all_equal", "all_distinct", "wave_edges", "tile_minus_1", "tile_exact", "tile_plus_1",
+               "multi_chunk", "bits_1", "bits_33", "bits_40_dups", "bits_63", "hot_key"]
+
+
+@pytest.mark.parametrize("case", DEDUP_CASES)
+def test_dedup_bit_exact(H, case):
+    keys, bits = _keys_case(case)
+    g, _ = H.gpu_dedup(keys, bits)
+    H.assert_dedup_equal(g, keys)
+
+
+def test_dedup_empty(H):
+    import torch
+    d = H.B.np_dedup(torch.empty(0, dtype=torch.int64, device="cuda"), 10)
+    torch.cuda.synchronize()
+    assert int(d["num_unique"].item()) == 0 and int(d["occ_offsets"][0].item()) == 0
+
+
+def test_dedup_is_deterministic(H):
+    keys, bits = _keys_case("hot_key")
+    a, _ = H.gpu_dedup(keys, bits)
+    b, _ = H.gpu_dedup(keys, bits)
+    for k in ("unique", "inverse", "counts", "occ_offsets", "occ"):
+        assert a[k].tobytes() == b[k].tobytes()
+
+
+# ------------------------------------------------------------------------------------------ route
+
+@pytest.mark.parametrize("S,fn", [(1, 0), (8, 0), (8, 1), (64, 1), (1000, 0), (1536, 1), (4096, 1)])
+@pytest.mark.parametrize("U", [1, 4097, 300000])
+def test_route_bit_exact(H, S, fn, U):
+    import torch
+    rng = np.random.default_rng(S * 7 + fn + U)
+    unique = np.unique(rng.integers(0, 1 << 33, size=U)).astype(np.int64)
+    U = unique.shape[0]
+    inv = rng.integers(0, U, size=2 * U + 3).astype(np.int32)
+    cap = U + 100                                       # the host bound may exceed the device count
+    ubuf = np.zeros(cap, np.int64)
+    ubuf[:U] = unique
+    r = H.B.np_route(H.dev(ubuf), H.dev(np.array([U], np.int32)), cap, S, fn, inverse=H.dev(inv), n=inv.shape[0])
+    torch.cuda.synchronize()
+    send_keys, splits, send_offsets, sfu, uts = H.O.route(unique, S, fn)
+    assert np.array_equal(H.host(r["send_keys"])[:U], send_keys)
+    assert np.array_equal(H.host(r["splits"])[:S], splits)
+    assert np.array_equal(H.host(r["send_offsets"])[:S + 1], send_offsets)
+    assert np.array_equal(H.host(r["send_from_unique"])[:U], sfu)
+    assert np.array_equal(H.host(r["unique_to_send"])[:U], uts)
+    assert np.array_equal(H.host(r["lookup_to_send"])[:inv.shape[0]], H.O.compose(inv, uts))
+
+
+def test_route_zero_keys(H):
+    import torch
+    r = H.B.np_route(torch.zeros(16, dtype=torch.int64, device="cuda"), H.dev(np.array([0], np.int32)), 16, 8, 1)
+    torch.cuda.synchronize()
+    assert not H.host(r["splits"]).any() and not H.host(r["send_offsets"]).any()
+
+
+# ------------------------------------------------------------------------------------------ forward
+
+def _bags(rng, B, max_l, R, allow_empty=True):
+    lens = rng.integers(0 if allow_empty else 1, max_l + 1, size=B)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    keys = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+    return off, keys
+
+
+@pytest.mark.parametrize("dim", [4, 8, 16, 48, 64, 128, 256, 512, 768, 1024])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_fwd_pooled(H, dim, mode):
+    import torch
+    rng = np.random.default_rng(dim * 3 + mode)
+    R, Bn = 3000, 1237
+    table = rng.standard_normal((R, dim)).astype(np.float32)
+    off, keys = _bags(rng, Bn, 70 if dim <= 128 else 9, R)
+    unique, inverse, *_ = H.O.dedup(keys)
+    ref, _, ab = H.O.lookup_fwd(table, unique, inverse, off, mode, want_abs=True)
+    out, _ = H.B.np_lookup_fwd(H.dev(table), H.dev(unique), H.dev(inverse), H.dev(off), keys.shape[0], mode)
+    torch.cuda.synchronize()
+    H.assert_close(H.host(out), ref, ab, H.RTOL_F32, f"fwd pooled dim={dim} mode={mode}")
+    empty = np.diff(off) == 0
+    assert not H.host(out)[empty].any()
+    # direct path (no slot indirection) and bf16 output
+    out2, _ = H.B.np_lookup_fwd(H.dev(table), H.dev(keys), None, H.dev(off), keys.shape[0], mode)
+    torch.cuda.synchronize()
+    assert H.host(out2).tobytes() == H.host(out).tobytes()
+    out3, _ = H.B.np_lookup_fwd(H.dev(table), H.dev(unique), H.dev(inverse), H.dev(off), keys.shape[0], mode, out_dtype=H.B.BF16)
+    torch.cuda.synchronize()
+    H.assert_close(H.O.bf16_bits_to_f32(H.host(out3)), ref, ab, H.RTOL_BF16, "fwd pooled bf16")
+
+
+@pytest.mark.parametrize("dim", [16, 128, 512])
+def test_fwd_seq_bit_exact_and_rows_out(H, dim):
+    import torch
+    rng = np.random.default_rng(dim)
+    R, Bn = 5000, 211
+    table = rng.standard_normal((R, dim)).astype(np.float32)
+    off, keys = _bags(rng, Bn, 37, R)
+    max_len = int(np.diff(off).max())
+    unique, inverse, *_ = H.O.dedup(keys)
+    U = unique.shape[0]
+    for dt in (H.B.BF16, H.B.F32):
+        ref, rows, _ = H.O.lookup_fwd(table, unique, inverse, off, 2, max_len, dt, want_rows=True)
+        out = torch.full((Bn, max_len, dim), 7.0, dtype=torch.bfloat16 if dt == H.B.BF16 else torch.float32, device="cuda")
+        out, rows_g = H.B.np_lookup_fwd(H.dev(table), H.dev(unique), H.dev(inverse), H.dev(off), keys.shape[0], 2, max_len, dt,
+                                        num_list=H.dev(np.array([U], np.int32)), cap=U + 5, want_rows=True, out=out)
+        torch.cuda.synchronize()
+        assert H.host(out).tobytes() == ref.tobytes()                 # a copy / one rounding: bit exact, zero padding
+        assert H.host(rows_g)[:U].tobytes() == rows.tobytes()
+
+
+# ------------------------------------------------------------------------------------------ backward
+
+def _bwd_case(rng, dim, Bn, max_l, R, hot=0.0):
+    off, keys = _bags(rng, Bn, max_l, R)
+    if hot > 0:
+        keys[rng.random(keys.shape[0]) < hot] = 3
+    dY = rng.standard_normal((Bn, dim)).astype(np.float32)
+    return off, keys, dY
+
+
+@pytest.mark.parametrize("dim", [4, 16, 64, 128, 256, 512, 1024])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("hot", [0.0, 0.5])
+def test_bwd_pooled(H, dim, mode, hot):
+    import torch
+    rng = np.random.default_rng(dim + mode * 5 + int(hot * 10))
+    Bn = 3001 if dim <= 128 else 400
+    off, keys, dY = _bwd_case(rng, dim, Bn, 11, 2000, hot)
+    n = keys.shape[0]
+    g, d = H.gpu_dedup(keys, 11)
+    unique, inverse, counts, _, _ = H.assert_dedup_equal(g, keys)
+    U = unique.shape[0]
+    _, _, _, _, uts = H.O.route(unique, 16, 1)
+    ref, ab = H.O.lookup_bwd(dY, 0, dim, mode, 1, off, inverse, U, uts, want_abs=True)
+    grads = H.B.np_lookup_bwd(H.dev(dY), dim, mode, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], n,
+                              unique_to_send=H.dev(uts))
+    torch.cuda.synchronize()
+    got = H.host(grads)[:U]
+    H.assert_close(got, ref, ab, H.RTOL_F32, f"bwd dim={dim} mode={mode} hot={hot}")
+    # deterministic: a second run gives the same bits
+    grads2 = H.B.np_lookup_bwd(H.dev(dY), dim, mode, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], n,
+                               unique_to_send=H.dev(uts))
+    torch.cuda.synchronize()
+    assert H.host(grads2)[:U].tobytes() == got.tobytes()
+    if mode == 0:
+        # unit gradient: every key receives exactly its multiplicity; unique order when no permutation is given
+        ones = torch.ones((Bn, dim), dtype=torch.float32, device="cuda")
+        gc = H.B.np_lookup_bwd(ones, dim, 0, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], n)
+        torch.cuda.synchronize()
+        assert np.array_equal(H.host(gc)[:U], np.repeat(counts[:, None], dim, 1).astype(np.float32))
+
+
+@pytest.mark.parametrize("dim", [16, 128])
+def test_bwd_seq_bf16(H, dim):
+    import torch
+    rng = np.random.default_rng(dim + 99)
+    Bn, R = 97, 900
+    off, keys = _bags(rng, Bn, 300, R)
+    max_len = int(np.diff(off).max())
+    n = keys.shape[0]
+    dY = H.wl.round_to_bf16(rng.standard_normal((Bn, max_len, dim)).astype(np.float32))
+    dYt = H.bf16_dev(dY)
+    bits = H.host(dYt).copy()
+    lens = np.diff(off)
+    poisoned = bits.copy()
+    for b in range(Bn):
+        poisoned[b, lens[b]:] = 0x7FC0                                   # NaN in the padding must never be read
+    dYp = torch.from_numpy(poisoned.view(np.int16)).cuda().view(torch.bfloat16)
+    g, d = H.gpu_dedup(keys, 10)
+    unique, inverse, *_ = H.assert_dedup_equal(g, keys)
+    U = unique.shape[0]
+    ref, ab = H.O.lookup_bwd(bits, 1, dim, 2, max_len, off, inverse, U, None, want_abs=True)
+    grads = H.B.np_lookup_bwd(dYp, dim, 2, max_len, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], n)
+    torch.cuda.synchronize()
+    H.assert_close(H.host(grads)[:U], ref, ab, H.RTOL_F32, f"bwd seq dim={dim}")
+
+
+# ------------------------------------------------------------------------------------------ update
+
+@pytest.mark.parametrize("dim", [4, 16, 64, 128, 512, 1024])
+def test_adagrad(H, dim):
+    import torch
+    rng = np.random.default_rng(dim + 1)
+    R, U = 20000, 6000
+    t0 = (rng.standard_normal((R, dim)) * 0.01).astype(np.float32)
+    s0 = (rng.random(R) * 0.1).astype(np.float32)
+    s0[::3] = 0
+    keys = np.sort(rng.choice(R, size=U, replace=False)).astype(np.int64)
+    keys = keys[rng.permutation(U)]
+    grads = rng.standard_normal((U, dim)).astype(np.float32)
+    grads[5] = 0.0
+    s0[keys[5]] = 0.0
+    tr, sr = t0.copy(), s0.copy()
+    H.O.sparse_adagrad(tr, sr, keys, grads, 0.01, 1e-8)
+    tg, sg = H.dev(t0), H.dev(s0)
+    gbuf = np.zeros((U + 50, dim), np.float32)
+    gbuf[:U] = grads
+    kbuf = np.zeros(U + 50, np.int64)
+    kbuf[:U] = keys
+    H.B.np_sparse_adagrad(tg, sg, H.dev(kbuf), H.dev(gbuf), H.dev(np.array([U], np.int32)), U + 50, 0.01, 1e-8)
+    torch.cuda.synchronize()
+    tgot, sgot = H.host(tg), H.host(sg)
+    delta = np.abs(tr.astype(np.float64) - t0)
+    H.assert_close(tgot[keys], tr[keys], np.abs(t0[keys]) + delta[keys], H.RTOL_F32, "updated rows")
+    H.assert_close(sgot[keys], sr[keys], np.abs(sr[keys]), H.RTOL_F32, "updated state")
+    rest = np.setdiff1d(np.arange(R), keys)
+    assert tgot[rest].tobytes() == t0[rest].tobytes() and sgot[rest].tobytes() == s0[rest].tobytes()
+    assert tgot[keys[5]].tobytes() == t0[keys[5]].tobytes() and sgot[keys[5]] == 0.0   # zero gradient: no change, no NaN
+
+
+# ------------------------------------------------------------------------------------------ whole step
+
+def _dense_step_check(H, cfg, steps=2):
+    """Runs `steps` consecutive batches through the five calls on a dense table small enough for the oracle.
+    Every call is held against the oracle on the same inputs: the integer outputs bit for bit, the forward
+    against the table as the previous update left it (the staleness-free read of Proposition 1), the
+    gradients against the fp64 sums, and the update against the oracle's update of the same gradient rows."""
+    import torch
+    R, D = cfg.num_rows, cfg.dim
+    table_ref = H.wl.table_init_rows(np.arange(R), D, cfg.table_seed)
+    state_ref = np.zeros(R, np.float32)
+    table = torch.empty((R, D), dtype=torch.float32, device="cuda")
+    H.B.np_util_table_init(table, cfg.table_seed)
+    state = torch.zeros(R, dtype=torch.float32, device="cuda")
+    prev = None
+    seq = cfg.mode == H.wl.SEQ
+    dt = H.O.BF16 if seq else H.O.F32
+    for t in range(steps):
+        batch = H.wl.make_batch(cfg, t, prev=prev)
+        prev = batch
+        g = H.gpu_step(cfg, batch, table, state)
+        dy_ref = H.host(g["dY"]) if seq else batch.dY
+        unique, inverse, counts, occ_offsets, occ = H.O.dedup(batch.keys)
+        send_keys, splits, send_offsets, sfu, uts = H.O.route(unique, cfg.num_shards, cfg.shard_fn)
+        l2s = H.O.compose(inverse, uts)
+        ref = dict(unique=unique, inverse=inverse, counts=counts, occ_offsets=occ_offsets, occ=occ, send_keys=send_keys,
+                   splits=splits, send_offsets=send_offsets, send_from_unique=sfu, unique_to_send=uts, lookup_to_send=l2s)
+        U = H.assert_int_outputs_equal(g, ref, batch.n, cfg.num_shards)
+        out_ref, _, ab = H.O.lookup_fwd(table_ref, send_keys, l2s, batch.bag_offsets, cfg.mode, batch.max_len, dt, want_abs=True)
+        if seq:
+            assert H.host(g["out"]).tobytes() == out_ref.tobytes()
+        else:
+            H.assert_close(H.host(g["out"]), out_ref, ab, H.RTOL_F32, f"step {t} forward")
+        grads_ref, gab = H.O.lookup_bwd(dy_ref, dt, D, cfg.mode, batch.max_len, batch.bag_offsets, inverse, U, uts, want_abs=True)
+        grads_gpu = H.host(g["grads"])[:U]
+        H.assert_close(grads_gpu, grads_ref, gab, H.RTOL_F32, f"step {t} gradients")
+        before_t, before_s = table_ref.copy(), state_ref.copy()
+        H.O.sparse_adagrad(table_ref, state_ref, send_keys, grads_gpu, cfg.lr, cfg.eps)
+        tg, sg = H.host(table), H.host(state)
+        K = unique
+        delta = np.abs(table_ref[K].astype(np.float64) - before_t[K])
+        H.assert_close(tg[K], table_ref[K], np.abs(before_t[K]) + delta, H.RTOL_F32, f"step {t} updated rows")
+        H.assert_close(sg[K], state_ref[K], np.abs(state_ref[K]), H.RTOL_F32, f"step {t} state")
+        rest = np.ones(R, bool)
+        rest[K] = False
+        assert tg[rest].tobytes() == before_t[rest].tobytes()           # Eq. (2): keys outside the batch are untouched
+        assert sg[rest].tobytes() == before_s[rest].tobytes()
+        assert np.all(np.any(tg[K] != before_t[K], axis=1) | ~np.any(grads_gpu[uts] != 0, axis=1))
+        # continue from the GPU's own table so that rounding differences do not leak into the next step's checks
+        table_ref[:] = tg
+        state_ref[:] = sg
+
+
+def test_step_tiny_config_two_batches(H):
+    """Configuration 1 at full size, two consecutive batches with shared hot keys: lookup -> update -> lookup
+    equals the sequential oracle (Proposition 1)."""
+    _dense_step_check(H, H.wl.config("tiny"), steps=2)
+
+
+@pytest.mark.parametrize("name,row_div,batch_div", [("dlrm", 400, 64), ("seq", 4000, 128), ("skew", 4000, 64),
+                                                    ("large", 8000, 256)])
+def test_step_scaled_configs(H, name, row_div, batch_div):
+    _dense_step_check(H, H.wl.scaled(H.wl.config(name), row_div, batch_div), steps=2)
