@@ -1,0 +1,278 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-embedding hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|skew|seq|dlrm|tiny]
+
+One step = one pass of the whole path (np_dedup, np_route, np_lookup_fwd, np_lookup_bwd,
+np_sparse_adagrad) over one synthetic batch, inputs already resident in HBM.  Consecutive steps alternate
+between two batches (the second built with 30 % distinct-key overlap where the configuration asks for it),
+and the Adagrad update stays live between steps.  Prints ONE JSON line:
+
+  value       lookups per second over the whole five-call step
+  roofline    the longest-running kernel: algorithmic bytes per launch / its mean duration (HIP events
+              recorded by the library around every launch, on the launch stream) against 8 TB/s
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same batch on the host cores
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(n: int, U: int, B: int, D: int, S: int, mode: int, max_len: int) -> dict:
+    """Compulsory HBM bytes of each call (every distinct row / element crosses HBM once)."""
+    row = 4 * D
+    seq = mode == 2
+    out_bytes = B * max_len * D * 2 if seq else B * row
+    dy_bytes = n * D * 2 if seq else B * row
+    return {
+        "np_dedup": 8 * n + 4 * n + 4 * n + 16 * U,
+        "np_route": 8 * U + 8 * U + 4 * U + 4 * U + 4 * S,
+        "np_lookup_fwd": U * row + 4 * n + 4 * B + out_bytes,
+        "np_lookup_bwd": dy_bytes + 8 * n + 4 * U + U * row,
+        "np_sparse_adagrad": 3 * U * row + 16 * U,
+    }
+
+
+# the kernel that carries (nearly all of) each call's algorithmic bytes
+KERNEL_OF_CALL = {"sparse_adagrad": "np_sparse_adagrad", "bwd_main": "np_lookup_bwd", "fwd_pool": "np_lookup_fwd",
+                  "fwd_seq": "np_lookup_fwd"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-div", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives are built; "
+              "the All2All exchanges are represented by np_route's send buffer).", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2604_06956_amd import binding as B
+    from paper_2604_06956_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    cfg = wl.config(args.workload)
+    t_gen = time.time()
+    b0 = wl.make_batch(cfg, 0, with_dy=False)
+    b1 = wl.make_batch(cfg, 1, prev=b0, with_dy=False)
+    batches = [b0, b1]
+    stats = [wl.batch_stats(b.keys) for b in batches]
+    K0, K1 = np.unique(b0.keys), np.unique(b1.keys)
+    overlap = float(np.intersect1d(K0, K1, assume_unique=True).size / K1.size)
+    gen_s = time.time() - t_gen
+
+    R, D, S = cfg.num_rows, cfg.dim, cfg.num_shards
+    seq = cfg.mode == wl.SEQ
+    table = torch.empty((R, D), dtype=torch.float32, device=dev)
+    state = torch.zeros(R, dtype=torch.float32, device=dev)
+    B.np_util_table_init(table, cfg.table_seed)
+
+    n_max = max(b.n for b in batches)
+    cap = max(s["U"] for s in stats) + 1024
+    max_len = max(b.max_len for b in batches)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.BASE_SEED + cfg.index)
+    dbatch = []
+    for b in batches:
+        shape = (cfg.num_bags, max_len, D) if seq else (cfg.num_bags, D)
+        dY = torch.randn(shape, dtype=torch.float32, device=dev, generator=gen)
+        if seq:
+            dY = dY.bfloat16()
+        dbatch.append(dict(keys=torch.from_numpy(b.keys).to(dev), off=torch.from_numpy(b.bag_offsets).to(dev), dY=dY, n=b.n))
+
+    i32, i64 = torch.int32, torch.int64
+    dd = dict(unique=torch.empty(n_max, dtype=i64, device=dev), inverse=torch.empty(n_max, dtype=i32, device=dev),
+              counts=torch.empty(n_max, dtype=i32, device=dev), occ_offsets=torch.empty(n_max + 1, dtype=i32, device=dev),
+              occ=torch.empty(n_max, dtype=i32, device=dev), num_unique=torch.zeros(1, dtype=i32, device=dev))
+    # the unique-key count is known on the host for these synthetic batches, so U-sized buffers use cap, not n
+    rr = dict(send_keys=torch.empty(cap, dtype=i64, device=dev), splits=torch.empty(S, dtype=i32, device=dev),
+              send_offsets=torch.empty(S + 1, dtype=i32, device=dev), send_from_unique=torch.empty(cap, dtype=i32, device=dev),
+              unique_to_send=torch.empty(cap, dtype=i32, device=dev), lookup_to_send=torch.empty(n_max, dtype=i32, device=dev))
+    out_dtype = B.BF16 if seq else B.F32
+    out = torch.empty((cfg.num_bags, max_len, D) if seq else (cfg.num_bags, D),
+                      dtype=torch.bfloat16 if seq else torch.float32, device=dev)
+    grads = torch.empty((cap, D), dtype=torch.float32, device=dev)
+    ws_d = torch.empty(max(B.np_dedup_workspace_bytes(n_max, cfg.key_bits), 256), dtype=torch.uint8, device=dev)
+    ws_r = torch.empty(max(B.np_route_workspace_bytes(cap, S), 256), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(max(B.np_lookup_bwd_workspace_bytes(cfg.num_bags, n_max, D, cfg.mode), 256), dtype=torch.uint8, device=dev)
+
+    def step(i: int) -> None:
+        bt = dbatch[i % 2]
+        n = bt["n"]
+        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
+        B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, inverse=dd["inverse"], n=n, out=rr, ws=ws_r)
+        B.np_lookup_fwd(table, rr["send_keys"], rr["lookup_to_send"], bt["off"], n, cfg.mode, max_len, out_dtype,
+                        num_list=dd["num_unique"], cap=cap, out=out)
+        B.np_lookup_bwd(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
+                        unique_to_send=rr["unique_to_send"], grads=grads, ws=ws_b)
+        B.np_sparse_adagrad(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    assert int(dd["num_unique"].item()) == stats[(args.warmup - 1) % 2]["U"] if args.warmup > 0 else True
+
+    # ---- timed region: exactly K steps, per-kernel HIP events recorded by the library on the launch stream
+    B.np_prof_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    records = B.np_prof_collect(65536)
+    B.np_prof_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    lookups = sum(dbatch[(args.warmup + i) % 2]["n"] for i in range(args.steps))
+    value = lookups / (t1 - t0)
+
+    # ---- the same K steps without event recording (what the events cost)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    ms_per_step_noevents = (time.perf_counter() - t2) * 1e3 / args.steps
+
+    kern = {}
+    for name, ms in records:
+        k = kern.setdefault(name, [0, 0.0])
+        k[0] += 1
+        k[1] += ms
+    kernels = {k: {"launches_per_step": v[0] / args.steps, "ms_per_step": v[1] / args.steps, "avg_ms": v[1] / v[0]}
+               for k, v in kern.items()}
+    call_ms = {}
+    for k, v in kernels.items():
+        call = ("np_dedup" if k.startswith("dedup") else "np_route" if k.startswith("route") else
+                "np_lookup_fwd" if k.startswith("fwd") else "np_lookup_bwd" if k.startswith("bwd") else "np_sparse_adagrad")
+        call_ms[call] = call_ms.get(call, 0.0) + v["ms_per_step"]
+
+    n_avg = float(np.mean([s["n"] for s in stats]))
+    U_avg = float(np.mean([s["U"] for s in stats]))
+    alg = algorithmic_bytes(int(n_avg), int(U_avg), cfg.num_bags, D, S, cfg.mode, max_len)
+    dominant = max((k for k in kernels if k in KERNEL_OF_CALL), key=lambda k: kernels[k]["avg_ms"])
+    dom_call = KERNEL_OF_CALL[dominant]
+    achieved = alg[dom_call] / (kernels[dominant]["avg_ms"] * 1e-3) / 1e9
+    fbu_ms = sum(call_ms.get(c, 0.0) for c in ("np_lookup_fwd", "np_lookup_bwd", "np_sparse_adagrad"))
+    fbu_bytes = alg["np_lookup_fwd"] + alg["np_lookup_bwd"] + alg["np_sparse_adagrad"]
+
+    # ---- bandwidth yardstick: a plain 16-byte copy kernel, 2 GiB each way
+    words = 2 ** 31
+    src = torch.empty(words, dtype=torch.uint8, device=dev)
+    dst = torch.empty(words, dtype=torch.uint8, device=dev)
+    B.np_util_stream_copy(dst, src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        B.np_util_stream_copy(dst, src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * words * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, b0, wl, args.cpu_sample_div)
+
+    line = {
+        "metric": "embedding lookups/sec (fwd+bwd+update) and achieved HBM GB/s on 1 MI355X",
+        "value": value,
+        "unit": "lookups/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {len(cfg.table_rows)} table(s), {R} rows x dim {D} fp32, batch {cfg.batch} x "
+                               f"{cfg.features} features, Zipf({cfg.alpha}), {S} shards, mode "
+                               f"{['sum', 'mean', 'seq-bf16'][cfg.mode]}; step = dedup+route+fwd+bwd+adagrad",
+                   "n_lookups": [s["n"] for s in stats], "unique_keys": [s["U"] for s in stats],
+                   "hottest_key_count": [s["hottest"] for s in stats], "distinct_key_overlap": overlap,
+                   "num_bags": cfg.num_bags, "max_len": max_len},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg[dom_call], "avg_launch_ms": kernels[dominant]["avg_ms"]},
+        "cpu_baseline": cpu,
+        "fwd_bwd_update": {"ms_per_step": fbu_ms, "lookups_per_s": n_avg / (fbu_ms * 1e-3) if fbu_ms > 0 else None,
+                           "algorithmic_GBps": fbu_bytes / (fbu_ms * 1e-3) / 1e9 if fbu_ms > 0 else None,
+                           "frac_of_peak": fbu_bytes / (fbu_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if fbu_ms > 0 else None},
+        "calls": {c: {"ms_per_step": call_ms.get(c, 0.0), "algorithmic_bytes": alg[c],
+                      "algorithmic_GBps": alg[c] / (call_ms[c] * 1e-3) / 1e9 if call_ms.get(c, 0.0) > 0 else None}
+                  for c in alg},
+        "kernels": kernels,
+        "ms_per_step_without_events": ms_per_step_noevents,
+        "stream_copy_GBps": copy_gbs,
+        "input_generation_s": gen_s,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+def cpu_baseline(cfg, batch, wl, div: int):
+    """The CPU oracle, as it stands, on the first 1/div of the batch's bags: the five steps on a table that holds
+    only the rows the sample touches (keys renumbered in order, which changes no result of the path)."""
+    from oracle import np_oracle as O
+    O.build()
+    nb = max(1, cfg.num_bags // div)
+    off = batch.bag_offsets[:nb + 1].astype(np.int32)
+    n = int(off[-1])
+    keys = batch.keys[:n]
+    touched = np.unique(keys)
+    local = np.searchsorted(touched, keys).astype(np.int64)
+    table = wl.table_init_rows(touched, cfg.dim, cfg.table_seed)
+    state = np.zeros(touched.shape[0], np.float32)
+    rng = np.random.default_rng(1)
+    seq = cfg.mode == wl.SEQ
+    if seq:
+        dY = (rng.standard_normal((nb, batch.max_len, cfg.dim)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    else:
+        dY = rng.standard_normal((nb, cfg.dim)).astype(np.float32)
+    t0 = time.perf_counter()
+    unique, inverse, counts, occ_offsets, occ = O.dedup(local)
+    t1 = time.perf_counter()
+    send_keys, splits, send_offsets, sfu, uts = O.route(touched[unique], cfg.num_shards, cfg.shard_fn)
+    l2s = O.compose(inverse, uts)
+    t2 = time.perf_counter()
+    O.lookup_fwd(table, unique[sfu], l2s, off, cfg.mode, batch.max_len, O.BF16 if seq else O.F32)
+    t3 = time.perf_counter()
+    grads, _ = O.lookup_bwd(dY, O.BF16 if seq else O.F32, cfg.dim, cfg.mode, batch.max_len, off, inverse, unique.shape[0], uts)
+    t4 = time.perf_counter()
+    O.sparse_adagrad(table, state, unique[sfu], grads, cfg.lr, cfg.eps)
+    t5 = time.perf_counter()
+    total = t5 - t0
+    return {"value": n / total, "unit": "lookups/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {nb} of {cfg.num_bags} bags of batch 0 ({n} lookups, {touched.shape[0]} distinct keys), all five "
+                      f"steps, table holding only the touched rows; single-threaded C, fp64 accumulation",
+            "seconds": total,
+            "seconds_per_call": {"dedup": t1 - t0, "route": t2 - t1, "fwd": t3 - t2, "bwd": t4 - t3, "adagrad": t5 - t4}}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -40,7 +40,9 @@ inline ChunkPlan make_chunk_plan(int64_t cap) {
     return p;
 }
 
-inline size_t part_hist_elems(const ChunkPlan& p, int bins) { return static_cast<size_t>(p.num_chunks) * bins; }
+// Words reserved for the histogram matrix: sized for the largest chunk count so that the workspace
+// requirement grows monotonically with the input size (the chunk count itself does not).
+inline size_t part_hist_elems(const ChunkPlan&, int bins) { return static_cast<size_t>(kTargetChunks) * bins; }
 
 template <typename KeyT>
 inline size_t part_scatter_lds_bytes(int bins, bool stage_digit) {
