@@ -182,6 +182,14 @@ int np_sparse_adagrad(float* table, float* state, int64_t num_rows, int32_t dim,
  */
 int np_util_table_init(float* table, int64_t num_rows, int32_t dim, uint64_t seed, void* stream);
 
+/*
+ * Count the rows of `table` whose bits differ anywhere from what np_util_table_init(seed) wrote: the number
+ * of rows an update has touched.  *d_count (device, uint64) is overwritten.  Used by the tests to show at
+ * full table size that rows outside a batch keep their bits.
+ */
+int np_util_table_count_changed(const float* table, int64_t num_rows, int32_t dim, uint64_t seed,
+                                unsigned long long* d_count, void* stream);
+
 /* Plain device copy of `bytes` (multiple of 16) with 16-byte loads and stores: the bandwidth yardstick. */
 int np_util_stream_copy(void* dst, const void* src, size_t bytes, void* stream);
 

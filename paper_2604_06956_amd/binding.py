@@ -57,6 +57,8 @@ lib.np_sparse_adagrad.restype = ctypes.c_int
 lib.np_sparse_adagrad.argtypes = [_vp, _vp, _i64, _i32, _vp, _vp, _vp, _i32, _f32, _f32, _vp]
 lib.np_util_table_init.restype = ctypes.c_int
 lib.np_util_table_init.argtypes = [_vp, _i64, _i32, _u64, _vp]
+lib.np_util_table_count_changed.restype = ctypes.c_int
+lib.np_util_table_count_changed.argtypes = [_vp, _i64, _i32, _u64, _vp, _vp]
 lib.np_util_stream_copy.restype = ctypes.c_int
 lib.np_util_stream_copy.argtypes = [_vp, _vp, _sz, _vp]
 lib.np_prof_enable.restype = ctypes.c_int
@@ -209,6 +211,14 @@ def np_sparse_adagrad(table: torch.Tensor, state: torch.Tensor, list_keys: torch
 def np_util_table_init(table: torch.Tensor, seed: int) -> None:
     num_rows, dim = table.shape
     _chk("np_util_table_init", lib.np_util_table_init(_ptr(table), num_rows, dim, seed, _stream()))
+
+
+def np_util_table_count_changed(table: torch.Tensor, seed: int) -> int:
+    """Rows of ``table`` that differ from the initialiser (synchronises)."""
+    num_rows, dim = table.shape
+    cnt = torch.zeros(1, dtype=torch.int64, device=table.device)
+    _chk("np_util_table_count_changed", lib.np_util_table_count_changed(_ptr(table), num_rows, dim, seed, _ptr(cnt), _stream()))
+    return int(cnt.item())
 
 
 def np_util_stream_copy(dst: torch.Tensor, src: torch.Tensor) -> None:

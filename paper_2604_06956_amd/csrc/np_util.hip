@@ -59,6 +59,42 @@ __global__ void __launch_bounds__(256) table_init_kernel(float4* __restrict__ ta
     }
 }
 
+__global__ void zero_u64_kernel(unsigned long long* p) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0ull;
+}
+
+// One thread per row (test harness code: simplicity over speed); integer atomics only.
+__global__ void __launch_bounds__(256)
+table_count_changed_kernel(const float4* __restrict__ table, uint64_t num_rows, int words_per_row, uint64_t seed_term,
+                           unsigned long long* __restrict__ count) {
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+    unsigned long long local = 0;
+    for (uint64_t row = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; row < num_rows; row += stride) {
+        bool changed = false;
+        for (int wq = 0; wq < words_per_row && !changed; ++wq) {
+            const uint64_t w = row * words_per_row + wq;
+            const float4 t = table[w];
+            const float got[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                uint64_t h = w * 4 + c + seed_term;
+                h ^= h >> 31;
+                h *= 0xD6E8FEB86659FD93ull;
+                h ^= h >> 27;
+                h *= 0xA3B195354A39B70Dull;
+                h ^= h >> 33;
+                const int q = static_cast<int>(h >> 40) - 8388608;
+                const float v = static_cast<float>(q) * (0.01f / 8388608.0f);
+                changed |= __float_as_uint(v) != __float_as_uint(got[c]);
+            }
+        }
+        local += changed ? 1ull : 0ull;
+    }
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) local += __shfl_xor(local, d, kWave);
+    if (__lane_id() == 0 && local) atomicAdd(count, local);
+}
+
 __global__ void __launch_bounds__(256) stream_copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src, uint64_t num_words) {
     const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
     for (uint64_t w = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; w < num_words; w += stride)
@@ -90,6 +126,21 @@ int np_util_table_init(float* table, int64_t num_rows, int32_t dim, uint64_t see
     const unsigned grid = static_cast<unsigned>(want < 65536 ? want : 65536);
     NP_LAUNCH("table_init", np::table_init_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
               reinterpret_cast<float4*>(table), words, seed * 0x2545F4914F6CDD1Dull);
+    return np::launch_status();
+}
+
+int np_util_table_count_changed(const float* table, int64_t num_rows, int32_t dim, uint64_t seed,
+                                unsigned long long* d_count, void* stream) {
+    if (!table || !d_count || num_rows < 0 || dim < 4 || dim % 4 != 0 || !np::aligned(table, 16)) return NP_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    NP_LAUNCH("zero_u64", np::zero_u64_kernel, dim3(1), dim3(64), 0, s, d_count);
+    if (num_rows > 0) {
+        const uint64_t want = (static_cast<uint64_t>(num_rows) + 255) / 256;
+        const unsigned grid = static_cast<unsigned>(want < 65536 ? want : 65536);
+        NP_LAUNCH("table_count_changed", np::table_count_changed_kernel, dim3(grid), dim3(256), 0, s,
+                  reinterpret_cast<const float4*>(table), static_cast<uint64_t>(num_rows), dim / 4, seed * 0x2545F4914F6CDD1Dull,
+                  d_count);
+    }
     return np::launch_status();
 }
 

@@ -51,11 +51,15 @@ def table_init_rows(rows: np.ndarray, dim: int, seed: int) -> np.ndarray:
     """fp32 ``[len(rows), dim]`` initial values of the given table rows, uniform on [-0.01, 0.01)."""
     rows = np.asarray(rows, dtype=np.int64).astype(np.uint64)
     cols = np.arange(dim, dtype=np.uint64)
-    with np.errstate(over="ignore"):
-        counter = rows[:, None] * np.uint64(dim) + cols[None, :]
-    h = table_init_hash(counter, seed)
-    q = (h >> np.uint64(40)).astype(np.int64) - 8388608  # 24 bits -> [-2^23, 2^23)
-    return q.astype(np.float32) * TABLE_INIT_SCALE
+    out = np.empty((rows.shape[0], dim), dtype=np.float32)
+    step = max(1, (1 << 24) // max(dim, 1))          # bound the uint64 temporaries to ~128 MB each
+    for a in range(0, rows.shape[0], step):
+        with np.errstate(over="ignore"):
+            counter = rows[a:a + step, None] * np.uint64(dim) + cols[None, :]
+        h = table_init_hash(counter, seed)
+        q = (h >> np.uint64(40)).astype(np.int64) - 8388608  # 24 bits -> [-2^23, 2^23)
+        out[a:a + step] = q.astype(np.float32) * TABLE_INIT_SCALE
+    return out
 
 
 # ----------------------------------------------------------------------------------------

@@ -13,6 +13,21 @@ RTOL_F32 = 1e-5
 RTOL_BF16 = 1e-2
 
 
+def progress(msg: str) -> None:
+    """A line in gpurun_out/test_progress.log: long full-size tests stay visibly alive while pytest captures stdout."""
+    import os
+    import time
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    d = os.path.join(root, "gpurun_out")
+    try:
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "test_progress.log"), "a") as f:
+            f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+    except OSError:
+        pass
+    print(msg, flush=True)
+
+
 def dev(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
