@@ -17,12 +17,11 @@ from typing import Dict, Optional, Tuple
 import torch  # imported before the library so that the library binds to torch's HIP runtime
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libnestpipe_hip.so")
+LIB_PATH = os.environ.get("NESTPIPE_LIB") or os.path.join(_PKG, "libnestpipe_hip.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_06956_amd.build`")
 
-lib = ctypes.CDLL(LIB_PATH)
 
 NP_OK = 0
 SHARD_MOD, SHARD_HASH = 0, 1
@@ -33,38 +32,46 @@ MAX_SHARDS = 4096
 _vp, _i32, _i64, _sz, _f32, _u64 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float,
                                     ctypes.c_uint64)
 
-lib.np_version.restype = ctypes.c_int
-lib.np_status_string.restype = ctypes.c_char_p
-lib.np_status_string.argtypes = [ctypes.c_int]
-lib.np_dedup.restype = ctypes.c_int
-lib.np_dedup.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
-lib.np_dedup_workspace_bytes.restype = _sz
-lib.np_dedup_workspace_bytes.argtypes = [_i32, _i32]
-lib.np_route.restype = ctypes.c_int
-lib.np_route.argtypes = [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
-lib.np_route_workspace_bytes.restype = _sz
-lib.np_route_workspace_bytes.argtypes = [_i32, _i32]
-lib.np_lookup_fwd.restype = ctypes.c_int
-lib.np_lookup_fwd.argtypes = [_vp, _i64, _i32, _vp, _vp, _i32, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _sz,
-                              _vp]
-lib.np_lookup_fwd_workspace_bytes.restype = _sz
-lib.np_lookup_fwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
-lib.np_lookup_bwd.restype = ctypes.c_int
-lib.np_lookup_bwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
-lib.np_lookup_bwd_workspace_bytes.restype = _sz
-lib.np_lookup_bwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
-lib.np_sparse_adagrad.restype = ctypes.c_int
-lib.np_sparse_adagrad.argtypes = [_vp, _vp, _i64, _i32, _vp, _vp, _vp, _i32, _f32, _f32, _vp]
-lib.np_util_table_init.restype = ctypes.c_int
-lib.np_util_table_init.argtypes = [_vp, _i64, _i32, _u64, _vp]
-lib.np_util_table_count_changed.restype = ctypes.c_int
-lib.np_util_table_count_changed.argtypes = [_vp, _i64, _i32, _u64, _vp, _vp]
-lib.np_util_stream_copy.restype = ctypes.c_int
-lib.np_util_stream_copy.argtypes = [_vp, _vp, _sz, _vp]
-lib.np_prof_enable.restype = ctypes.c_int
-lib.np_prof_enable.argtypes = [ctypes.c_int]
-lib.np_prof_collect.restype = ctypes.c_int
-lib.np_prof_collect.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float), ctypes.c_int]
+
+
+def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
+    """Declare the prototypes of include/nestpipe.h on a loaded library handle."""
+    L.np_version.restype = ctypes.c_int
+    L.np_status_string.restype = ctypes.c_char_p
+    L.np_status_string.argtypes = [ctypes.c_int]
+    L.np_dedup.restype = ctypes.c_int
+    L.np_dedup.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.np_dedup_workspace_bytes.restype = _sz
+    L.np_dedup_workspace_bytes.argtypes = [_i32, _i32]
+    L.np_route.restype = ctypes.c_int
+    L.np_route.argtypes = [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
+    L.np_route_workspace_bytes.restype = _sz
+    L.np_route_workspace_bytes.argtypes = [_i32, _i32]
+    L.np_lookup_fwd.restype = ctypes.c_int
+    L.np_lookup_fwd.argtypes = [_vp, _i64, _i32, _vp, _vp, _i32, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _sz,
+                                  _vp]
+    L.np_lookup_fwd_workspace_bytes.restype = _sz
+    L.np_lookup_fwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
+    L.np_lookup_bwd.restype = ctypes.c_int
+    L.np_lookup_bwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
+    L.np_lookup_bwd_workspace_bytes.restype = _sz
+    L.np_lookup_bwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
+    L.np_sparse_adagrad.restype = ctypes.c_int
+    L.np_sparse_adagrad.argtypes = [_vp, _vp, _i64, _i32, _vp, _vp, _vp, _i32, _f32, _f32, _vp]
+    L.np_util_table_init.restype = ctypes.c_int
+    L.np_util_table_init.argtypes = [_vp, _i64, _i32, _u64, _vp]
+    L.np_util_table_count_changed.restype = ctypes.c_int
+    L.np_util_table_count_changed.argtypes = [_vp, _i64, _i32, _u64, _vp, _vp]
+    L.np_util_stream_copy.restype = ctypes.c_int
+    L.np_util_stream_copy.argtypes = [_vp, _vp, _sz, _vp]
+    L.np_prof_enable.restype = ctypes.c_int
+    L.np_prof_enable.argtypes = [ctypes.c_int]
+    L.np_prof_collect.restype = ctypes.c_int
+    L.np_prof_collect.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float), ctypes.c_int]
+    return L
+
+
+lib = _configure(ctypes.CDLL(LIB_PATH))
 
 
 class NestPipeError(RuntimeError):

@@ -29,9 +29,12 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+EXTRA = os.environ.get("NESTPIPE_EXTRA_FLAGS", "").split()
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
-    r = subprocess.run([HIPCC, *FLAGS, "-c", src, "-o", obj], capture_output=True, text=True)
+    r = subprocess.run([HIPCC, *FLAGS, *EXTRA, "-c", src, "-o", obj], capture_output=True, text=True)
     msgs = "\n".join(ln for ln in (r.stdout + r.stderr).splitlines() if "packed-fp32-ops" not in ln)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{msgs}")

@@ -9,7 +9,10 @@
 
 namespace np {
 
-constexpr int kMaxDigitBits = 11;
+#ifndef NP_MAX_DIGIT_BITS
+#define NP_MAX_DIGIT_BITS 11
+#endif
+constexpr int kMaxDigitBits = NP_MAX_DIGIT_BITS;
 
 struct PassPlan {
     int passes;

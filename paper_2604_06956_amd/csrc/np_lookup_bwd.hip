@@ -4,7 +4,7 @@
 //
 // A deterministic segmented reduction over np_dedup's occurrence lists, balanced under any skew:
 //
-//   bwd_expand     src_row[j] = the dY row lookup j reads (its bag, or its padded sequence position)
+//   bwd_bagmap     a bitmap of bag starts plus one bag index per 64 lookups: lookup -> bag in one 16-byte read
 //   bwd_tile_seg0  for every tile of 256 consecutive sorted positions, the key segment its first position is in
 //   bwd_main       one block per tile.  Every thread prepares one position (dY row, weight, head/tail flags
 //                  of its segment); then each LPR-lane group walks its LPR positions in order, several dY row
@@ -26,14 +26,57 @@ namespace np {
 constexpr int kBwdTile = 256;
 constexpr int kBwdUnroll = 8;
 
-template <int G>
+// One entry per 64 consecutive lookups: where bags start inside the block and which bag the block begins in.
+// 16 bytes per 64 lookups (n/4 bytes in all), so the random reads of bwd_main mostly stay in L2 / Infinity Cache.
+struct __align__(16) BagMapEntry {
+    uint64_t starts;  // bit k (1..63): a bag starts at lookup 64w + k
+    int32_t bag0;     // bag holding lookup 64w; sign bit: an empty bag also starts inside the block -> walk bag_offsets
+    int32_t start0;   // bag_offsets[bag0]
+};
+
 __global__ void __launch_bounds__(256)
-bwd_expand_kernel(const int32_t* __restrict__ bag_offsets, int num_bags, int seq, int max_len, int32_t* __restrict__ src_row) {
-    const int r = threadIdx.x % G;
-    const int64_t b = static_cast<int64_t>(blockIdx.x) * (256 / G) + threadIdx.x / G;
-    if (b >= num_bags) return;
-    const int lo = bag_offsets[b], hi = bag_offsets[b + 1];
-    for (int j = lo + r; j < hi; j += G) src_row[j] = seq ? static_cast<int32_t>(b * max_len + (j - lo)) : static_cast<int32_t>(b);
+bwd_bagmap_kernel(const int32_t* __restrict__ bag_offsets, int num_bags, int n, BagMapEntry* __restrict__ map) {
+    const int w = blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t base64 = static_cast<int64_t>(w) * 64;
+    if (base64 >= n) return;
+    const int base = static_cast<int>(base64);
+    int lo = 0, hi = num_bags;  // last bag in [lo, hi) that starts at or before base; it is non-empty and holds base
+    while (hi - lo > 1) {
+        const int mid = lo + (hi - lo) / 2;
+        if (bag_offsets[mid] <= base) lo = mid;
+        else hi = mid;
+    }
+    const int last = n - 1 - base < 63 ? n - 1 : base + 63;
+    uint64_t bits = 0;
+    bool twice = false;
+    for (int b = lo + 1; b < num_bags; ++b) {
+        const int o = bag_offsets[b];
+        if (o > last) break;
+        const uint64_t m = 1ull << (o - base);
+        twice |= (bits & m) != 0;
+        bits |= m;
+    }
+    BagMapEntry e;
+    e.starts = bits;
+    e.bag0 = twice ? (lo | static_cast<int32_t>(0x80000000u)) : lo;
+    e.start0 = bag_offsets[lo];
+    map[w] = e;
+}
+
+// Bag of lookup j and the first lookup of that bag.
+__device__ __forceinline__ void bag_of_lookup(const BagMapEntry* __restrict__ map, const int32_t* __restrict__ bag_offsets, int j,
+                                              int& bag, int& start) {
+    const BagMapEntry e = map[j >> 6];
+    const int k = j & 63;
+    const uint64_t m = e.starts & ((2ull << k) - 1ull);  // starts at or before j (bit 0 is never set)
+    bag = (e.bag0 & 0x7FFFFFFF) + __popcll(m);
+    start = m ? (j - k + 63 - __clzll(static_cast<long long>(m))) : e.start0;
+    if (e.bag0 < 0) {  // an empty bag starts in this block: the bit count misses it, walk the offsets instead
+        int b = e.bag0 & 0x7FFFFFFF;
+        while (bag_offsets[b + 1] <= j) ++b;
+        bag = b;
+        start = bag_offsets[b];
+    }
 }
 
 __global__ void __launch_bounds__(256)
@@ -68,9 +111,9 @@ __device__ __forceinline__ float4 load_dy(const uint16_t* dY, size_t row, int di
 
 template <int LPR, int NV, bool MEAN, typename DyT>
 __global__ void __launch_bounds__(256)
-bwd_main_kernel(const DyT* __restrict__ dY, int dim, const int32_t* __restrict__ bag_offsets, int n,
+bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const int32_t* __restrict__ bag_offsets, int n,
                 const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ occ, const int32_t* __restrict__ d_num_unique,
-                const int32_t* __restrict__ unique_to_send, const int32_t* __restrict__ src_row,
+                const int32_t* __restrict__ unique_to_send, const BagMapEntry* __restrict__ bagmap,
                 const int32_t* __restrict__ tile_seg0, float* __restrict__ grads, float* __restrict__ tile_left,
                 float* __restrict__ tile_right, int32_t* __restrict__ tile_rseg) {
     constexpr int GPB = 256 / LPR;
@@ -111,9 +154,12 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, const int32_t* __restrict__
     int sr = 0, dst = -1;
     float w = 1.f;
     if (valid) {
-        sr = src_row[occ[i]];
+        const int j = occ[i];
+        int bag, start;
+        bag_of_lookup(bagmap, bag_offsets, j, bag, start);
+        sr = seq ? bag * max_len + (j - start) : bag;
         if (MEAN) {
-            const int len = bag_offsets[sr + 1] - bag_offsets[sr];
+            const int len = bag_offsets[bag + 1] - start;
             w = 1.f / static_cast<float>(len);
         }
         if (is_tail) dst = unique_to_send ? unique_to_send[seg] : seg;
@@ -315,7 +361,7 @@ struct BwdWs {
 inline BwdWs bwd_ws_layout(int32_t n, int32_t dim) {
     BwdWs w;
     w.num_tiles = (n + kBwdTile - 1) / kBwdTile;
-    w.total = align_up(4 * static_cast<size_t>(n), 256)                              // src_row
+    w.total = align_up(sizeof(BagMapEntry) * ((static_cast<size_t>(n) + 63) / 64), 256)  // bag map
               + 2 * align_up(4 * static_cast<size_t>(w.num_tiles) * dim, 256)        // tile_left, tile_right
               + 2 * align_up(4 * static_cast<size_t>(w.num_tiles), 256);             // tile_seg0, tile_rseg
     return w;
@@ -339,23 +385,15 @@ template <int LPR, int NV>
 void bwd_launch(const BwdArgs& a) {
     const BwdWs L = bwd_ws_layout(a.n, a.dim);
     WsCursor cur(a.ws);
-    int32_t* src_row = cur.take<int32_t>(a.n);
+    const int map_entries = (a.n + 63) / 64;
+    BagMapEntry* bagmap = cur.take<BagMapEntry>(map_entries);
     float* tile_left = cur.take<float>(static_cast<size_t>(L.num_tiles) * a.dim);
     float* tile_right = cur.take<float>(static_cast<size_t>(L.num_tiles) * a.dim);
     int32_t* tile_seg0 = cur.take<int32_t>(L.num_tiles);
     int32_t* tile_rseg = cur.take<int32_t>(L.num_tiles);
     const int seq = a.mode == NP_SEQ ? 1 : 0;
-    const int64_t avg = a.n / (a.num_bags > 0 ? a.num_bags : 1);
-    if (avg <= 6) {
-        NP_LAUNCH("bwd_expand", bwd_expand_kernel<4>, dim3((a.num_bags + 63) / 64), dim3(256), 0, a.stream, a.bag_offsets,
-                  a.num_bags, seq, a.max_len, src_row);
-    } else if (avg <= 24) {
-        NP_LAUNCH("bwd_expand", bwd_expand_kernel<16>, dim3((a.num_bags + 15) / 16), dim3(256), 0, a.stream, a.bag_offsets,
-                  a.num_bags, seq, a.max_len, src_row);
-    } else {
-        NP_LAUNCH("bwd_expand", bwd_expand_kernel<64>, dim3((a.num_bags + 3) / 4), dim3(256), 0, a.stream, a.bag_offsets,
-                  a.num_bags, seq, a.max_len, src_row);
-    }
+    NP_LAUNCH("bwd_bagmap", bwd_bagmap_kernel, dim3((map_entries + 255) / 256), dim3(256), 0, a.stream, a.bag_offsets, a.num_bags,
+              a.n, bagmap);
     NP_LAUNCH("bwd_tile_seg0", bwd_tile_seg0_kernel, dim3((L.num_tiles + 255) / 256), dim3(256), 0, a.stream, a.occ_offsets,
               a.d_num_unique, L.num_tiles, tile_seg0);
     const bool mean = a.mode == NP_POOL_MEAN;
@@ -363,21 +401,21 @@ void bwd_launch(const BwdArgs& a) {
         const uint16_t* dy = static_cast<const uint16_t*>(a.dY);
         if (mean)
             NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, uint16_t>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
-                      a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, src_row, tile_seg0, a.grads,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, a.grads,
                       tile_left, tile_right, tile_rseg);
         else
             NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, uint16_t>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
-                      a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, src_row, tile_seg0, a.grads,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, a.grads,
                       tile_left, tile_right, tile_rseg);
     } else {
         const float* dy = static_cast<const float*>(a.dY);
         if (mean)
             NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, float>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
-                      a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, src_row, tile_seg0, a.grads,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, a.grads,
                       tile_left, tile_right, tile_rseg);
         else
             NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, float>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
-                      a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, src_row, tile_seg0, a.grads,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, a.grads,
                       tile_left, tile_right, tile_rseg);
     }
     NP_LAUNCH("bwd_fixup", (bwd_fixup_kernel<LPR, NV>), dim3(L.num_tiles), dim3(256), 0, a.stream, a.dim, a.occ_offsets,

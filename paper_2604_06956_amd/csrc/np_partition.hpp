@@ -17,10 +17,17 @@
 
 namespace np {
 
-constexpr int kPartThreads = 256;
+#ifndef NP_PART_THREADS
+#define NP_PART_THREADS 512
+#endif
+#ifndef NP_PART_IPT
+#define NP_PART_IPT 8
+#endif
+constexpr int kPartThreads = NP_PART_THREADS;
 constexpr int kPartWaves = kPartThreads / kWave;
-constexpr int kPartIPT = 16;
+constexpr int kPartIPT = NP_PART_IPT;
 constexpr int kPartTile = kPartThreads * kPartIPT;
+static_assert(kPartIPT * kWave <= 65535, "per-wave digit counters are 16 bits wide");
 constexpr int kPartMaxBins = 4096;
 constexpr int kTargetChunks = 1024;
 constexpr int kColscanThreads = 1024;
@@ -47,7 +54,7 @@ inline size_t part_hist_elems(const ChunkPlan&, int bins) { return static_cast<s
 template <typename KeyT>
 inline size_t part_scatter_lds_bytes(int bins, bool stage_digit) {
     const size_t fixed = 3 * sizeof(uint32_t) * bins + 64;  // gofs, binstart, btot, scan scratch
-    const size_t cnt = sizeof(uint32_t) * kPartWaves * bins;
+    const size_t cnt = align_up(sizeof(uint16_t) * kPartWaves * bins, 16);  // a wave ranks kPartIPT * 64 <= 65535 items
     size_t stage = (sizeof(KeyT) + sizeof(uint32_t)) * kPartTile;
     if (stage_digit) stage += sizeof(uint16_t) * kPartTile;
     return fixed + (cnt > stage ? cnt : stage);
@@ -135,7 +142,7 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
     uint32_t* btot = binstart + bins;
     int* scan_tmp = reinterpret_cast<int*>(btot + bins);  // 16 ints
     unsigned char* un = reinterpret_cast<unsigned char*>(scan_tmp + 16);
-    volatile uint32_t* cnt = reinterpret_cast<volatile uint32_t*>(un);  // [waves][bins], aliased with the staging area
+    volatile uint16_t* cnt = reinterpret_cast<volatile uint16_t*>(un);  // [waves][bins], aliased with the staging area
     KeyT* skey = reinterpret_cast<KeyT*>(un);
     uint32_t* sval = reinterpret_cast<uint32_t*>(skey + kPartTile);
     uint16_t* sdig = reinterpret_cast<uint16_t*>(sval + kPartTile);
@@ -171,7 +178,7 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
 
     for (int64_t tile_base = lo; tile_base < hi; tile_base += kPartTile) {
         const int tile_count = hi - tile_base < kPartTile ? static_cast<int>(hi - tile_base) : kPartTile;
-        for (int i = tid; i < kPartWaves * bins; i += kPartThreads) cnt[i] = 0;
+        for (int i = tid; i < kPartWaves * bins; i += kPartThreads) cnt[i] = 0;  // 16-bit stores
         __syncthreads();
 
         KeyT k[kPartIPT];
@@ -193,12 +200,12 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
             const bool valid = idx < tile_count;
             const uint64_t peers = match_any(d[i], nbits, valid);
-            volatile uint32_t* ctr = cnt + w * bins + d[i];
+            volatile uint16_t* ctr = cnt + w * bins + d[i];
             const uint32_t pre = *ctr;
             const uint64_t below = peers & lt;
             r[i] = pre + __popcll(below);
             __builtin_amdgcn_wave_barrier();
-            if (valid && below == 0) *ctr = pre + __popcll(peers);
+            if (valid && below == 0) *ctr = static_cast<uint16_t>(pre + __popcll(peers));
             __builtin_amdgcn_wave_barrier();
         }
         __syncthreads();
@@ -209,7 +216,7 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
 #pragma unroll
             for (int ww = 0; ww < kPartWaves; ++ww) {
                 const uint32_t t = cnt[ww * bins + b];
-                cnt[ww * bins + b] = s;
+                cnt[ww * bins + b] = static_cast<uint16_t>(s);
                 s += t;
             }
             btot[b] = s;
@@ -262,6 +269,9 @@ inline void run_partition_pass(const P& pol, int n_host, const int* d_n, int bin
     NP_LAUNCH(tag_scan, part_colscan_kernel<kColscanThreads>, dim3((bins + kWave - 1) / kWave), dim3(kColscanThreads), 0, stream, H,
               plan.num_chunks, bins, bin_total);
     const size_t lds = part_scatter_lds_bytes<typename P::KeyT>(bins, P::kStageDigit);
+    if (lds > 48 * 1024)  // above the default dynamic-LDS allowance: opt in (a failure shows up as a failed launch)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(part_scatter_kernel<P>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     NP_LAUNCH(tag_scatter, part_scatter_kernel<P>, dim3(plan.num_chunks), dim3(kPartThreads), lds, stream, pol, n_host,
               d_n, bins, nbits, plan, H, bin_total, totals_out, offsets_out);
 }
