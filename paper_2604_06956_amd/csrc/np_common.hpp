@@ -96,6 +96,10 @@ __device__ __forceinline__ uint32_t fastmod64(uint64_t x, const FastMod& f) {
     return fastmod32(hi * f.pow32 + lo, f);  // hi, pow32 < 2^16: the product fits in 32 bits
 }
 
+// Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS traffic, not for global loads
+// still in flight (a plain __syncthreads drains those too, which serialises every prefetch behind the barrier).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 __device__ __forceinline__ int wave_incl_scan(int v) {
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
@@ -106,14 +110,14 @@ __device__ __forceinline__ int wave_incl_scan(int v) {
 }
 
 // Exclusive scan of one int per thread over a block of NW waves.  `smem` holds NW + 1 ints.  Returns the
-// exclusive prefix; *total receives the block sum.  Contains two __syncthreads.
+// exclusive prefix; *total receives the block sum.  Contains two LDS barriers.
 template <int NW>
 __device__ __forceinline__ int block_excl_scan(int v, int* smem, int* total) {
     const int w = threadIdx.x / kWave;
     const int inc = wave_incl_scan(v);
-    __syncthreads();  // smem may still be read from a previous call
+    lds_barrier();  // smem may still be read from a previous call
     if (__lane_id() == kWave - 1) smem[w] = inc;
-    __syncthreads();
+    lds_barrier();
     int base = 0, tot = 0;
 #pragma unroll
     for (int i = 0; i < NW; ++i) {

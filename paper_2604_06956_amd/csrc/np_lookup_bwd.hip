@@ -6,6 +6,11 @@
 //
 //   bwd_bagmap     a bitmap of bag starts plus one bag index per 64 lookups: lookup -> bag in one 16-byte read
 //   bwd_tile_seg0  for every tile of 256 consecutive sorted positions, the key segment its first position is in
+//   bwd_order      execution order of the tiles (it changes no result, only which dY rows are in cache): the lookups
+//                  of one key are spread evenly over the bags, so the tiles of all long segments are run sorted by
+//                  their relative position inside their segment, one contiguous range of relative positions per
+//                  die; tiles running at the same time then read the same band of dY rows from L2 / Infinity
+//                  Cache instead of once per lookup from HBM.  One stable partition pass over the tile list.
 //   bwd_main       one block per tile.  Every thread prepares one position (dY row, weight, head/tail flags
 //                  of its segment); then each LPR-lane group walks its LPR positions in order, several dY row
 //                  loads in flight, and closes a running sum whenever a segment ends.  Sums of segments that
@@ -19,12 +24,20 @@
 // The order of every floating-point addition is a function of occ_offsets alone: no atomics, no dependence
 // on scheduling, so two runs give the same bits.  A hot key with millions of lookups costs the same per
 // lookup as a cold one.
-#include "np_common.hpp"
+#include "np_partition.hpp"
 
 namespace np {
 
 constexpr int kBwdTile = 256;
 constexpr int kBwdUnroll = 8;
+constexpr int kOrderBuckets = 1024;   // relative positions inside a long segment
+#ifndef NP_ORDER_MIN_COUNT
+#define NP_ORDER_MIN_COUNT 2048
+#endif
+#ifndef NP_ORDER_XCD_SPLIT
+#define NP_ORDER_XCD_SPLIT 1
+#endif
+constexpr int kOrderMinCount = NP_ORDER_MIN_COUNT;  // segments at least this long take part in the locality order
 
 // One entry per 64 consecutive lookups: where bags start inside the block and which bag the block begins in.
 // 16 bytes per 64 lookups (n/4 bytes in all), so the random reads of bwd_main mostly stay in L2 / Infinity Cache.
@@ -94,6 +107,32 @@ bwd_tile_seg0_kernel(const int32_t* __restrict__ occ_offsets, const int32_t* __r
     tile_seg0[t] = lo;
 }
 
+// Partition policy that sorts tiles by the bucket of their relative position inside a long segment; tiles that are
+// not wholly inside one long segment go to the last bucket.
+struct TileOrderPolicy {
+    using KeyT = uint32_t;
+    static constexpr bool kStageDigit = false;
+    const int32_t* tile_seg0;
+    const int32_t* occ_offsets;
+    int32_t* order;
+    int n;
+    __device__ __forceinline__ uint32_t load_key(int64_t i) const {
+        const int tile_start = static_cast<int>(i) * kBwdTile;
+        const int tile_end = n - tile_start < kBwdTile ? n : tile_start + kBwdTile;
+        const int u0 = tile_seg0[i];
+        const int s0 = occ_offsets[u0], e0 = occ_offsets[u0 + 1];
+        if (e0 < tile_end || e0 - s0 < kOrderMinCount) return kOrderBuckets;
+        return static_cast<uint32_t>((static_cast<uint64_t>(tile_start - s0) * kOrderBuckets) / static_cast<uint32_t>(e0 - s0));
+    }
+    __device__ __forceinline__ void load(int64_t i, uint32_t& k, uint32_t& v) const {
+        k = load_key(i);
+        v = static_cast<uint32_t>(i);
+    }
+    __device__ __forceinline__ uint32_t digit(uint32_t k) const { return k; }
+    __device__ __forceinline__ void store(uint32_t dst, uint32_t, uint32_t v) const { order[dst] = static_cast<int32_t>(v); }
+    __device__ __forceinline__ void placed(int64_t, uint32_t) const {}
+};
+
 template <int LPR>
 __device__ __forceinline__ int group_bcast(int v, int src_in_group) {
     return __shfl(v, (__lane_id() & ~(LPR - 1)) + src_in_group, kWave);
@@ -114,73 +153,99 @@ __global__ void __launch_bounds__(256)
 bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const int32_t* __restrict__ bag_offsets, int n,
                 const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ occ, const int32_t* __restrict__ d_num_unique,
                 const int32_t* __restrict__ unique_to_send, const BagMapEntry* __restrict__ bagmap,
-                const int32_t* __restrict__ tile_seg0, float* __restrict__ grads, float* __restrict__ tile_left,
-                float* __restrict__ tile_right, int32_t* __restrict__ tile_rseg) {
+                const int32_t* __restrict__ tile_seg0, const int32_t* __restrict__ order, const int32_t* __restrict__ order_offsets,
+                int num_tiles, float* __restrict__ grads, float* __restrict__ tile_left, float* __restrict__ tile_right,
+                int32_t* __restrict__ tile_rseg) {
     constexpr int GPB = 256 / LPR;
     constexpr int ROWW = LPR * NV;  // float4 words per (padded) row
     __shared__ int headmark[kBwdTile + 1];
-    __shared__ int scan_tmp[16];
+    __shared__ int wave_heads[4];
     __shared__ float4 lpart[GPB * ROWW];
     __shared__ float4 rpart[GPB * ROWW];
     __shared__ int l_exists[GPB], l_closed[GPB], l_dst[GPB], r_exists[GPB];
 
     const int t = threadIdx.x;
-    const int tile = blockIdx.x;
+    // block -> tile: die x (blocks x, x+8, ...) first runs its contiguous share of the locality-ordered tiles, then
+    // every 8th of the remaining ones
+    int tile;
+    {
+        const int nh = order_offsets[kOrderBuckets];
+        const int nc = num_tiles - nh;
+        const int hc = (nh + kNumXcd - 1) / kNumXcd;
+        const int x = blockIdx.x % kNumXcd, sl = blockIdx.x / kNumXcd;
+        int k;
+        if (!NP_ORDER_XCD_SPLIT) {
+            k = blockIdx.x;
+            if (k >= num_tiles) return;
+        } else if (sl < hc) {
+            k = x * hc + sl;
+            if (k >= nh) return;
+        } else {
+            const int kc = (sl - hc) * kNumXcd + x;
+            if (kc >= nc) return;
+            k = nh + kc;
+        }
+        tile = order[k];
+    }
     const int tile_start = tile * kBwdTile;
     const int i = tile_start + t;
     const bool valid = i < n;
     const int U = *d_num_unique;
     const int u0 = tile_seg0[tile];
     const int words = dim / 4;
+    const int g = t / LPR, r = t % LPR;
+    const int wv_id = t / kWave;
 
+    // loads that depend on nothing but the tile go out first
+    const int j = valid ? occ[i] : 0;
+    const int cand = u0 + 1 + t;
+    const int rel = cand <= U ? occ_offsets[cand] - tile_start : INT32_MAX;  // >= 1
+    const int seg0_start = occ_offsets[u0];
     headmark[t] = 0;
     if (t == 0) headmark[kBwdTile] = 0;
     __syncthreads();
-    {
-        const int cand = u0 + 1 + t;
-        if (cand <= U) {
-            const int rel = occ_offsets[cand] - tile_start;  // >= 1
-            if (rel <= kBwdTile) headmark[rel] = 1;
-        }
-    }
-    __syncthreads();
-    const int flag = t > 0 ? headmark[t] : 0;
-    int is_head = flag;
-    if (t == 0) is_head = occ_offsets[u0] == tile_start ? 1 : 0;
-    const int is_tail = headmark[t + 1];
-    int total;
-    const int seg = u0 + block_excl_scan<4>(flag, scan_tmp, &total) + flag;
-
-    int sr = 0, dst = -1;
+    if (rel <= kBwdTile) headmark[rel] = 1;
+    int sr = 0;
     float w = 1.f;
     if (valid) {
-        const int j = occ[i];
         int bag, start;
         bag_of_lookup(bagmap, bag_offsets, j, bag, start);
         sr = seq ? bag * max_len + (j - start) : bag;
-        if (MEAN) {
-            const int len = bag_offsets[bag + 1] - start;
-            w = 1.f / static_cast<float>(len);
-        }
-        if (is_tail) dst = unique_to_send ? unique_to_send[seg] : seg;
+        if (MEAN) w = 1.f / static_cast<float>(bag_offsets[bag + 1] - start);
     }
+    __syncthreads();
+    // segment of every position: heads strictly after the tile start, counted with one ballot per wave
+    const int flag = t > 0 ? headmark[t] : 0;
+    const int is_tail = headmark[t + 1];
+    const uint64_t fmask = __ballot(flag);
+    if (__lane_id() == 0) wave_heads[wv_id] = __popcll(fmask);
+    __syncthreads();
+    int seg = u0 + __popcll(fmask & lanemask_lt()) + flag;
+#pragma unroll
+    for (int ww = 0; ww < 3; ++ww)
+        if (ww < wv_id) seg += wave_heads[ww];
+    // a tail position knows where its segment's row goes; every other position carries -1
+    int dst = -1;
+    if (valid && is_tail) dst = unique_to_send ? unique_to_send[seg] : seg;
     if (valid && t == min(n - tile_start, kBwdTile) - 1) {
         // the tile owns the segment that runs past its end only if that segment starts inside the tile
-        const bool starts_here = seg > u0 || occ_offsets[u0] == tile_start;
+        const bool starts_here = seg > u0 || seg0_start == tile_start;
         tile_rseg[tile] = (!is_tail && starts_here) ? seg : -1;
     }
 
-    // ---- each group walks its strip of LPR positions -------------------------------------------------
-    const int g = t / LPR, r = t % LPR;
+    // ---- each group walks its strip of LPR positions ---------------------------------------------------
+    // Position k > 0 starts a segment exactly when position k - 1 ends one, so the walk needs the end marks
+    // (dst >= 0) and, for position 0 alone, whether the strip begins inside a segment that started earlier.
     int cnt = n - (tile_start + g * LPR);
     cnt = cnt < 0 ? 0 : (cnt > LPR ? LPR : cnt);
+    const int head_here = t == 0 ? (seg0_start == tile_start ? 1 : 0) : flag;
+    bool first_open = group_bcast<LPR>(head_here, 0) == 0;  // the strip's first run continues an earlier one
     const int wbits = __float_as_int(w);
     float4 acc[NV];
 #pragma unroll
     for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
-    bool open_left = false, le = false, lc = false, re = false;
-    int ld = -1;
-    bool last_tail = true;
+    bool le = false, lc = false, re = false;
+    int ld = -1, dlast = 0;
     for (int k0 = 0; k0 < cnt; k0 += kBwdUnroll) {
         float4 x[kBwdUnroll][NV];
 #pragma unroll
@@ -197,12 +262,8 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
         for (int q = 0; q < kBwdUnroll; ++q) {
             const int k = k0 + q;
             if (k < cnt) {
-                const int hk = group_bcast<LPR>(is_head, k);
-                const int tk = group_bcast<LPR>(is_tail, k);
                 const int dk = group_bcast<LPR>(dst, k);
                 const float wk = MEAN ? __int_as_float(group_bcast<LPR>(wbits, k)) : 1.f;
-                if (k == 0) open_left = !hk;
-                else if (hk) open_left = false;
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
                     if (MEAN) {
@@ -217,9 +278,9 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                         acc[v].w += x[q][v].w;
                     }
                 }
-                last_tail = tk != 0;
-                if (tk) {
-                    if (!open_left) {
+                dlast = dk;
+                if (dk >= 0) {  // a segment ends here
+                    if (!first_open) {
 #pragma unroll
                         for (int v = 0; v < NV; ++v) {
                             const int wv = r + v * LPR;
@@ -231,6 +292,7 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                         le = true;
                         lc = true;
                         ld = dk;
+                        first_open = false;
                     }
 #pragma unroll
                     for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -238,8 +300,8 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
             }
         }
     }
-    if (cnt > 0 && !last_tail) {
-        if (open_left) {  // one segment covers the whole strip and goes on
+    if (cnt > 0 && dlast < 0) {  // the last run goes on past the strip
+        if (first_open) {        // one segment covers the whole strip
 #pragma unroll
             for (int v = 0; v < NV; ++v) lpart[g * ROWW + r + v * LPR] = acc[v];
             le = true;
@@ -296,60 +358,77 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     }
 }
 
-// One block per tile whose last segment runs on into later tiles.
+// Blocks of 1024 threads stride over the tiles; a tile whose last segment runs on into later tiles adds its right
+// partial and the left partials of the following tiles.  A long chain (a key with millions of lookups spans
+// thousands of tiles) is cut into one contiguous run per group, four loads in flight per lane, and the runs
+// are combined in tile order: the shape of the sum depends on the chain length alone.
+constexpr int kFixupThreads = 1024;
+
 template <int LPR, int NV>
-__global__ void __launch_bounds__(256)
-bwd_fixup_kernel(int dim, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
+__global__ void __launch_bounds__(kFixupThreads)
+bwd_fixup_kernel(int dim, int num_tiles, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
                  const float* __restrict__ tile_left, const float* __restrict__ tile_right, const int32_t* __restrict__ tile_rseg,
                  float* __restrict__ grads) {
-    constexpr int GPB = 256 / LPR;
+    constexpr int GPB = kFixupThreads / LPR;
     constexpr int ROWW = LPR * NV;
     __shared__ float4 part[GPB * ROWW];
-    const int tile = blockIdx.x;
-    const int seg = tile_rseg[tile];
-    if (seg < 0) return;
-    const int end = occ_offsets[seg + 1];
-    const int last_tile = (end - 1) / kBwdTile;
-    const int count = last_tile - tile;  // left partials to add, >= 1
     const int g = threadIdx.x / LPR, r = threadIdx.x % LPR;
     const int words = dim / 4;
-    const int per = (count + GPB - 1) / GPB;
-    const int c0 = g * per;
-    const int c1 = c0 + per < count ? c0 + per : count;
-    float4 acc[NV];
+    for (int tile = blockIdx.x; tile < num_tiles; tile += gridDim.x) {
+        const int seg = tile_rseg[tile];
+        if (seg < 0) continue;  // uniform over the block
+        const int end = occ_offsets[seg + 1];
+        const int last_tile = (end - 1) / kBwdTile;
+        const int count = last_tile - tile;  // left partials to add, >= 1
+        const int per = (count + GPB - 1) / GPB;
+        const int c0 = g * per;
+        const int c1 = c0 + per < count ? c0 + per : count;
+        float4 acc[NV];
 #pragma unroll
-    for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int c = c0; c < c1; ++c) {
-        const float4* src = reinterpret_cast<const float4*>(tile_left + static_cast<size_t>(tile + 1 + c) * dim);
+        for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int c = c0; c < c1; c += 4) {
+            float4 p[4][NV];
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const int wv = r + v * LPR;
-            if (wv < words) {
-                const float4 p = src[wv];
-                acc[v].x += p.x;
-                acc[v].y += p.y;
-                acc[v].z += p.z;
-                acc[v].w += p.w;
+            for (int q = 0; q < 4; ++q) {
+                const float4* src = reinterpret_cast<const float4*>(tile_left + static_cast<size_t>(tile + 1 + (c + q < c1 ? c + q : c)) * dim);
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const int wv = r + v * LPR;
+                    p[q][v] = (c + q < c1 && wv < words) ? src[wv] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (c + q < c1) {
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) {
+                        acc[v].x += p[q][v].x;
+                        acc[v].y += p[q][v].y;
+                        acc[v].z += p[q][v].z;
+                        acc[v].w += p[q][v].w;
+                    }
+                }
             }
         }
-    }
+        __syncthreads();  // part may still be read by the previous tile of this block
 #pragma unroll
-    for (int v = 0; v < NV; ++v) part[g * ROWW + r + v * LPR] = acc[v];
-    __syncthreads();
-    const int t = threadIdx.x;
-    if (t < words) {
-        float4 s = reinterpret_cast<const float4*>(tile_right + static_cast<size_t>(tile) * dim)[t];
-        for (int gg = 0; gg < GPB; ++gg) {
-            if (gg * per < count) {
-                const float4 p = part[gg * ROWW + t];
-                s.x += p.x;
-                s.y += p.y;
-                s.z += p.z;
-                s.w += p.w;
+        for (int v = 0; v < NV; ++v) part[g * ROWW + r + v * LPR] = acc[v];
+        __syncthreads();
+        const int t = threadIdx.x;
+        if (t < words) {
+            float4 s = reinterpret_cast<const float4*>(tile_right + static_cast<size_t>(tile) * dim)[t];
+            for (int gg = 0; gg < GPB; ++gg) {
+                if (gg * per < count) {
+                    const float4 q = part[gg * ROWW + t];
+                    s.x += q.x;
+                    s.y += q.y;
+                    s.z += q.z;
+                    s.w += q.w;
+                }
             }
+            const int dst = unique_to_send ? unique_to_send[seg] : seg;
+            reinterpret_cast<float4*>(grads + static_cast<size_t>(dst) * dim)[t] = s;
         }
-        const int dst = unique_to_send ? unique_to_send[seg] : seg;
-        reinterpret_cast<float4*>(grads + static_cast<size_t>(dst) * dim)[t] = s;
     }
 }
 
@@ -363,7 +442,10 @@ inline BwdWs bwd_ws_layout(int32_t n, int32_t dim) {
     w.num_tiles = (n + kBwdTile - 1) / kBwdTile;
     w.total = align_up(sizeof(BagMapEntry) * ((static_cast<size_t>(n) + 63) / 64), 256)  // bag map
               + 2 * align_up(4 * static_cast<size_t>(w.num_tiles) * dim, 256)        // tile_left, tile_right
-              + 2 * align_up(4 * static_cast<size_t>(w.num_tiles), 256);             // tile_seg0, tile_rseg
+              + 3 * align_up(4 * static_cast<size_t>(w.num_tiles), 256)              // tile_seg0, tile_rseg, order
+              + align_up(4 * static_cast<size_t>(kOrderBuckets + 2), 256)             // bucket offsets of the order
+              + align_up(4 * part_hist_elems(make_chunk_plan(w.num_tiles), kOrderBuckets + 1), 256)
+              + align_up(4 * static_cast<size_t>(kOrderBuckets + 1), 256);
     return w;
 }
 
@@ -391,35 +473,46 @@ void bwd_launch(const BwdArgs& a) {
     float* tile_right = cur.take<float>(static_cast<size_t>(L.num_tiles) * a.dim);
     int32_t* tile_seg0 = cur.take<int32_t>(L.num_tiles);
     int32_t* tile_rseg = cur.take<int32_t>(L.num_tiles);
+    int32_t* order = cur.take<int32_t>(L.num_tiles);
+    int32_t* order_offsets = cur.take<int32_t>(kOrderBuckets + 2);
+    const ChunkPlan oplan = make_chunk_plan(L.num_tiles);
+    uint32_t* oH = cur.take<uint32_t>(part_hist_elems(oplan, kOrderBuckets + 1));
+    uint32_t* obin = cur.take<uint32_t>(kOrderBuckets + 1);
     const int seq = a.mode == NP_SEQ ? 1 : 0;
     NP_LAUNCH("bwd_bagmap", bwd_bagmap_kernel, dim3((map_entries + 255) / 256), dim3(256), 0, a.stream, a.bag_offsets, a.num_bags,
               a.n, bagmap);
     NP_LAUNCH("bwd_tile_seg0", bwd_tile_seg0_kernel, dim3((L.num_tiles + 255) / 256), dim3(256), 0, a.stream, a.occ_offsets,
               a.d_num_unique, L.num_tiles, tile_seg0);
+    {
+        TileOrderPolicy pol{tile_seg0, a.occ_offsets, order, a.n};
+        run_partition_pass(pol, L.num_tiles, nullptr, kOrderBuckets + 1, 11, oplan, oH, obin, nullptr, order_offsets, a.stream,
+                           "bwd_order_hist", "bwd_order_colscan", "bwd_order_scatter");
+    }
+    const unsigned main_grid = static_cast<unsigned>((L.num_tiles + 2 * kNumXcd + kNumXcd - 1) / kNumXcd * kNumXcd);
     const bool mean = a.mode == NP_POOL_MEAN;
     if (a.dy_dtype == NP_BF16) {
         const uint16_t* dy = static_cast<const uint16_t*>(a.dY);
         if (mean)
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, uint16_t>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, a.grads,
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, uint16_t>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.grads,
                       tile_left, tile_right, tile_rseg);
         else
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, uint16_t>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, a.grads,
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, uint16_t>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.grads,
                       tile_left, tile_right, tile_rseg);
     } else {
         const float* dy = static_cast<const float*>(a.dY);
         if (mean)
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, float>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, a.grads,
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, float>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.grads,
                       tile_left, tile_right, tile_rseg);
         else
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, float>), dim3(L.num_tiles), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, a.grads,
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, float>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.grads,
                       tile_left, tile_right, tile_rseg);
     }
-    NP_LAUNCH("bwd_fixup", (bwd_fixup_kernel<LPR, NV>), dim3(L.num_tiles), dim3(256), 0, a.stream, a.dim, a.occ_offsets,
-              a.unique_to_send, tile_left, tile_right, tile_rseg, a.grads);
+    NP_LAUNCH("bwd_fixup", (bwd_fixup_kernel<LPR, NV>), dim3(L.num_tiles < 2048 ? L.num_tiles : 2048), dim3(kFixupThreads), 0,
+              a.stream, a.dim, L.num_tiles, a.occ_offsets, a.unique_to_send, tile_left, tile_right, tile_rseg, a.grads);
 }
 
 }  // namespace np

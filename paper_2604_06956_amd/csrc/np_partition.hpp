@@ -176,23 +176,38 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
     if (hi > n) hi = n;
     const uint64_t lt = lanemask_lt();
 
+    // the items of the first tile; later tiles are fetched one iteration ahead and stay in flight across the LDS
+    // barriers of the tile being ranked
+    KeyT kn[kPartIPT];
+    uint32_t vn[kPartIPT];
+#pragma unroll
+    for (int i = 0; i < kPartIPT; ++i) {
+        const int64_t at = lo + w * (kWave * kPartIPT) + i * kWave + lane;
+        kn[i] = KeyT(0);
+        vn[i] = 0;
+        if (at < hi) pol.load(at, kn[i], vn[i]);
+    }
+
     for (int64_t tile_base = lo; tile_base < hi; tile_base += kPartTile) {
         const int tile_count = hi - tile_base < kPartTile ? static_cast<int>(hi - tile_base) : kPartTile;
         for (int i = tid; i < kPartWaves * bins; i += kPartThreads) cnt[i] = 0;  // 16-bit stores
-        __syncthreads();
+        lds_barrier();
 
         KeyT k[kPartIPT];
         uint32_t v[kPartIPT], d[kPartIPT], r[kPartIPT];
 #pragma unroll
         for (int i = 0; i < kPartIPT; ++i) {
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
-            k[i] = KeyT(0);
-            v[i] = 0;
-            d[i] = 0;
-            if (idx < tile_count) {
-                pol.load(tile_base + idx, k[i], v[i]);
-                d[i] = pol.digit(k[i]);
-            }
+            k[i] = kn[i];
+            v[i] = vn[i];
+            d[i] = idx < tile_count ? pol.digit(k[i]) : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < kPartIPT; ++i) {
+            const int64_t at = tile_base + kPartTile + w * (kWave * kPartIPT) + i * kWave + lane;
+            kn[i] = KeyT(0);
+            vn[i] = 0;
+            if (at < hi) pol.load(at, kn[i], vn[i]);
         }
         // stable rank of every item among the items of its wave with the same digit
 #pragma unroll
@@ -208,7 +223,7 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
             if (valid && below == 0) *ctr = static_cast<uint16_t>(pre + __popcll(peers));
             __builtin_amdgcn_wave_barrier();
         }
-        __syncthreads();
+        lds_barrier();
         // per bin: exclusive scan over the waves, total of the tile
         int local = 0;
         for (int b = b0; b < b1; ++b) {
@@ -228,32 +243,31 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
             binstart[b] = static_cast<uint32_t>(run);
             run += static_cast<int>(btot[b]);
         }
-        __syncthreads();
-        uint32_t pos[kPartIPT];
+        lds_barrier();
 #pragma unroll
         for (int i = 0; i < kPartIPT; ++i) {
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
             const uint32_t in_bin = cnt[w * bins + d[i]] + r[i];
-            pos[i] = binstart[d[i]] + in_bin;
+            r[i] = binstart[d[i]] + in_bin;  // position inside the reordered tile
             if (idx < tile_count) pol.placed(tile_base + idx, gofs[d[i]] + in_bin);
         }
-        __syncthreads();  // the counters are dead from here on: their storage becomes the staging area
+        lds_barrier();  // the counters are dead from here on: their storage becomes the staging area
 #pragma unroll
         for (int i = 0; i < kPartIPT; ++i) {
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
             if (idx < tile_count) {
-                skey[pos[i]] = k[i];
-                sval[pos[i]] = v[i];
-                if (P::kStageDigit) sdig[pos[i]] = static_cast<uint16_t>(d[i]);
+                skey[r[i]] = k[i];
+                sval[r[i]] = v[i];
+                if (P::kStageDigit) sdig[r[i]] = static_cast<uint16_t>(d[i]);
             }
         }
-        __syncthreads();
+        lds_barrier();
         for (int p = tid; p < tile_count; p += kPartThreads) {
             const KeyT key = skey[p];
             const uint32_t dd = P::kStageDigit ? static_cast<uint32_t>(sdig[p]) : pol.digit(key);
             pol.store(gofs[dd] + (static_cast<uint32_t>(p) - binstart[dd]), key, sval[p]);
         }
-        __syncthreads();
+        lds_barrier();
         for (int b = b0; b < b1; ++b) gofs[b] += btot[b];
         // the next iteration's first barrier orders these updates before any use
     }
