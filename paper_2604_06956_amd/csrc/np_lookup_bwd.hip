@@ -94,8 +94,9 @@ __device__ __forceinline__ void bag_of_lookup(const BagMapEntry* __restrict__ ma
 
 __global__ void __launch_bounds__(256)
 bwd_tile_seg0_kernel(const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ d_num_unique, int num_tiles,
-                     int32_t* __restrict__ tile_seg0) {
+                     int32_t* __restrict__ tile_seg0, int32_t* __restrict__ long_count) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t == 0) *long_count = 0;  // the list of long chains is rebuilt by every call
     if (t >= num_tiles) return;
     const int pos = t * kBwdTile;
     int lo = 0, hi = *d_num_unique;  // the answer is the last u in [lo, hi) with occ_offsets[u] <= pos
@@ -138,12 +139,15 @@ __device__ __forceinline__ int group_bcast(int v, int src_in_group) {
     return __shfl(v, (__lane_id() & ~(LPR - 1)) + src_in_group, kWave);
 }
 
-__device__ __forceinline__ float4 load_dy(const float* dY, size_t row, int dim, int word) {
-    return reinterpret_cast<const float4*>(dY + row * dim)[word];
+// Row `row` (non-negative, below 2^31) of dY: one 32x32->64 multiply for the byte offset.
+__device__ __forceinline__ float4 load_dy(const float* dY, int row, int dim, int word) {
+    const uint64_t off = static_cast<uint64_t>(static_cast<uint32_t>(row)) * static_cast<uint32_t>(dim * 4);
+    return reinterpret_cast<const float4*>(reinterpret_cast<const char*>(dY) + off)[word];
 }
 
-__device__ __forceinline__ float4 load_dy(const uint16_t* dY, size_t row, int dim, int word) {
-    const uint2 p = reinterpret_cast<const uint2*>(dY + row * dim)[word];
+__device__ __forceinline__ float4 load_dy(const uint16_t* dY, int row, int dim, int word) {
+    const uint64_t off = static_cast<uint64_t>(static_cast<uint32_t>(row)) * static_cast<uint32_t>(dim * 2);
+    const uint2 p = reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(dY) + off)[word];
     return make_float4(__uint_as_float(p.x << 16), __uint_as_float(p.x & 0xFFFF0000u), __uint_as_float(p.y << 16),
                        __uint_as_float(p.y & 0xFFFF0000u));
 }
@@ -251,11 +255,11 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
 #pragma unroll
         for (int q = 0; q < kBwdUnroll; ++q) {
             const bool on = k0 + q < cnt;
-            const int srk = group_bcast<LPR>(sr, on ? k0 + q : 0);
+            const int srk = group_bcast<LPR>(sr, (k0 + q) & (LPR - 1));
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 const int wv = r + v * LPR;
-                x[q][v] = (on && wv < words) ? load_dy(dY, static_cast<size_t>(srk), dim, wv) : make_float4(0.f, 0.f, 0.f, 0.f);
+                x[q][v] = (on && wv < words) ? load_dy(dY, srk, dim, wv) : make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
 #pragma unroll
@@ -358,28 +362,77 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     }
 }
 
-// Blocks of 1024 threads stride over the tiles; a tile whose last segment runs on into later tiles adds its right
-// partial and the left partials of the following tiles.  A long chain (a key with millions of lookups spans
-// thousands of tiles) is cut into one contiguous run per group, four loads in flight per lane, and the runs
-// are combined in tile order: the shape of the sum depends on the chain length alone.
+// A tile whose last segment runs on into later tiles owns that segment: it adds its right partial and the left
+// partials of the following tiles, in tile order.  Chains of up to kFixupShort partials (nearly all of them) are
+// summed by one LPR-lane group per tile; longer chains (a key with millions of lookups spans thousands of tiles)
+// are listed and summed by a whole block each, cut into one contiguous run per group with four loads in
+// flight per lane.  Either way the shape of the sum depends on the chain length alone.
+constexpr int kFixupShort = 8;
 constexpr int kFixupThreads = 1024;
 
 template <int LPR, int NV>
+__global__ void __launch_bounds__(256)
+bwd_fixup_short_kernel(int dim, int num_tiles, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
+                       const float* __restrict__ tile_left, const float* __restrict__ tile_right,
+                       const int32_t* __restrict__ tile_rseg, float* __restrict__ grads, int32_t* __restrict__ long_count,
+                       int32_t* __restrict__ long_tiles) {
+    constexpr int GPB = 256 / LPR;
+    const int r = threadIdx.x % LPR;
+    const int tile = blockIdx.x * GPB + threadIdx.x / LPR;
+    if (tile >= num_tiles) return;
+    const int seg = tile_rseg[tile];
+    if (seg < 0) return;
+    const int count = (occ_offsets[seg + 1] - 1) / kBwdTile - tile;  // left partials to add, >= 1
+    if (count > kFixupShort) {
+        if (r == 0) long_tiles[atomicAdd(long_count, 1)] = tile;  // list order is arbitrary; it decides no value
+        return;
+    }
+    const int words = dim / 4;
+    float4 acc[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int wv = r + v * LPR;
+        acc[v] = wv < words ? reinterpret_cast<const float4*>(tile_right + static_cast<size_t>(tile) * dim)[wv]
+                            : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    for (int c = 0; c < count; ++c) {
+        const float4* src = reinterpret_cast<const float4*>(tile_left + static_cast<size_t>(tile + 1 + c) * dim);
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int wv = r + v * LPR;
+            if (wv < words) {
+                const float4 p = src[wv];
+                acc[v].x += p.x;
+                acc[v].y += p.y;
+                acc[v].z += p.z;
+                acc[v].w += p.w;
+            }
+        }
+    }
+    const int dst = unique_to_send ? unique_to_send[seg] : seg;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int wv = r + v * LPR;
+        if (wv < words) reinterpret_cast<float4*>(grads + static_cast<size_t>(dst) * dim)[wv] = acc[v];
+    }
+}
+
+template <int LPR, int NV>
 __global__ void __launch_bounds__(kFixupThreads)
-bwd_fixup_kernel(int dim, int num_tiles, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
-                 const float* __restrict__ tile_left, const float* __restrict__ tile_right, const int32_t* __restrict__ tile_rseg,
-                 float* __restrict__ grads) {
+bwd_fixup_long_kernel(int dim, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
+                      const float* __restrict__ tile_left, const float* __restrict__ tile_right,
+                      const int32_t* __restrict__ tile_rseg, float* __restrict__ grads, const int32_t* __restrict__ long_count,
+                      const int32_t* __restrict__ long_tiles) {
     constexpr int GPB = kFixupThreads / LPR;
     constexpr int ROWW = LPR * NV;
     __shared__ float4 part[GPB * ROWW];
     const int g = threadIdx.x / LPR, r = threadIdx.x % LPR;
     const int words = dim / 4;
-    for (int tile = blockIdx.x; tile < num_tiles; tile += gridDim.x) {
+    const int num_long = *long_count;
+    for (int li = blockIdx.x; li < num_long; li += gridDim.x) {
+        const int tile = long_tiles[li];
         const int seg = tile_rseg[tile];
-        if (seg < 0) continue;  // uniform over the block
-        const int end = occ_offsets[seg + 1];
-        const int last_tile = (end - 1) / kBwdTile;
-        const int count = last_tile - tile;  // left partials to add, >= 1
+        const int count = (occ_offsets[seg + 1] - 1) / kBwdTile - tile;
         const int per = (count + GPB - 1) / GPB;
         const int c0 = g * per;
         const int c1 = c0 + per < count ? c0 + per : count;
@@ -410,7 +463,7 @@ bwd_fixup_kernel(int dim, int num_tiles, const int32_t* __restrict__ occ_offsets
                 }
             }
         }
-        __syncthreads();  // part may still be read by the previous tile of this block
+        __syncthreads();  // part may still be read for the previous chain of this block
 #pragma unroll
         for (int v = 0; v < NV; ++v) part[g * ROWW + r + v * LPR] = acc[v];
         __syncthreads();
@@ -442,7 +495,8 @@ inline BwdWs bwd_ws_layout(int32_t n, int32_t dim) {
     w.num_tiles = (n + kBwdTile - 1) / kBwdTile;
     w.total = align_up(sizeof(BagMapEntry) * ((static_cast<size_t>(n) + 63) / 64), 256)  // bag map
               + 2 * align_up(4 * static_cast<size_t>(w.num_tiles) * dim, 256)        // tile_left, tile_right
-              + 3 * align_up(4 * static_cast<size_t>(w.num_tiles), 256)              // tile_seg0, tile_rseg, order
+              + 4 * align_up(4 * static_cast<size_t>(w.num_tiles), 256)              // tile_seg0, tile_rseg, order, long chains
+              + 256                                                                   // number of long chains
               + align_up(4 * static_cast<size_t>(kOrderBuckets + 2), 256)             // bucket offsets of the order
               + align_up(4 * part_hist_elems(make_chunk_plan(w.num_tiles), kOrderBuckets + 1), 256)
               + align_up(4 * static_cast<size_t>(kOrderBuckets + 1), 256);
@@ -474,6 +528,8 @@ void bwd_launch(const BwdArgs& a) {
     int32_t* tile_seg0 = cur.take<int32_t>(L.num_tiles);
     int32_t* tile_rseg = cur.take<int32_t>(L.num_tiles);
     int32_t* order = cur.take<int32_t>(L.num_tiles);
+    int32_t* long_tiles = cur.take<int32_t>(L.num_tiles);
+    int32_t* long_count = cur.take<int32_t>(1);
     int32_t* order_offsets = cur.take<int32_t>(kOrderBuckets + 2);
     const ChunkPlan oplan = make_chunk_plan(L.num_tiles);
     uint32_t* oH = cur.take<uint32_t>(part_hist_elems(oplan, kOrderBuckets + 1));
@@ -482,7 +538,7 @@ void bwd_launch(const BwdArgs& a) {
     NP_LAUNCH("bwd_bagmap", bwd_bagmap_kernel, dim3((map_entries + 255) / 256), dim3(256), 0, a.stream, a.bag_offsets, a.num_bags,
               a.n, bagmap);
     NP_LAUNCH("bwd_tile_seg0", bwd_tile_seg0_kernel, dim3((L.num_tiles + 255) / 256), dim3(256), 0, a.stream, a.occ_offsets,
-              a.d_num_unique, L.num_tiles, tile_seg0);
+              a.d_num_unique, L.num_tiles, tile_seg0, long_count);
     {
         TileOrderPolicy pol{tile_seg0, a.occ_offsets, order, a.n};
         run_partition_pass(pol, L.num_tiles, nullptr, kOrderBuckets + 1, 11, oplan, oH, obin, nullptr, order_offsets, a.stream,
@@ -511,8 +567,11 @@ void bwd_launch(const BwdArgs& a) {
                       seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.grads,
                       tile_left, tile_right, tile_rseg);
     }
-    NP_LAUNCH("bwd_fixup", (bwd_fixup_kernel<LPR, NV>), dim3(L.num_tiles < 2048 ? L.num_tiles : 2048), dim3(kFixupThreads), 0,
-              a.stream, a.dim, L.num_tiles, a.occ_offsets, a.unique_to_send, tile_left, tile_right, tile_rseg, a.grads);
+    constexpr int GPB = 256 / LPR;
+    NP_LAUNCH("bwd_fixup_short", (bwd_fixup_short_kernel<LPR, NV>), dim3((L.num_tiles + GPB - 1) / GPB), dim3(256), 0, a.stream, a.dim,
+              L.num_tiles, a.occ_offsets, a.unique_to_send, tile_left, tile_right, tile_rseg, a.grads, long_count, long_tiles);
+    NP_LAUNCH("bwd_fixup_long", (bwd_fixup_long_kernel<LPR, NV>), dim3(512), dim3(kFixupThreads), 0, a.stream, a.dim, a.occ_offsets,
+              a.unique_to_send, tile_left, tile_right, tile_rseg, a.grads, long_count, long_tiles);
 }
 
 }  // namespace np

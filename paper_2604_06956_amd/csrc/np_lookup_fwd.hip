@@ -43,18 +43,24 @@ fwd_pool_kernel(const float* __restrict__ table, int dim, const int64_t* __restr
 #pragma unroll
     for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
 
+    const int gl = __lane_id() & ~(LPR - 1);  // first lane of this group
     for (int base = lo; base < hi; base += LPR) {
         const int j = base + r;
-        int64_t row = 0;
-        if (j < hi) row = list_keys[idx ? idx[j] : j];
+        // one lane per lookup: slot, key and the byte offset of the row (the 64-bit multiply happens here, once
+        // per lookup, instead of in every lane of the walk below)
+        int64_t row_off = 0;
+        if (j < hi) row_off = list_keys[idx ? idx[j] : j] * static_cast<int64_t>(dim) * static_cast<int64_t>(sizeof(float));
+        const int off_lo = static_cast<int>(row_off & 0xFFFFFFFFll), off_hi = static_cast<int>(row_off >> 32);
         const int cnt = hi - base < LPR ? hi - base : LPR;
         for (int k0 = 0; k0 < cnt; k0 += kFwdUnroll) {
             float4 x[kFwdUnroll][NV];
 #pragma unroll
             for (int q = 0; q < kFwdUnroll; ++q) {
-                const bool on = k0 + q < cnt;  // uniform inside the group
-                const int64_t rk = group_bcast64<LPR>(row, on ? k0 + q : 0);
-                const float4* src = reinterpret_cast<const float4*>(table + static_cast<size_t>(rk) * dim);
+                const bool on = k0 + q < cnt;  // uniform inside the group; k0 + q < LPR always
+                const uint32_t lo32 = static_cast<uint32_t>(__shfl(off_lo, gl + k0 + q, kWave));
+                const uint32_t hi32 = static_cast<uint32_t>(__shfl(off_hi, gl + k0 + q, kWave));
+                const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const char*>(table) +
+                                                                    ((static_cast<uint64_t>(hi32) << 32) | lo32));
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
                     const int wv = r + v * LPR;
@@ -63,14 +69,12 @@ fwd_pool_kernel(const float* __restrict__ table, int dim, const int64_t* __restr
             }
 #pragma unroll
             for (int q = 0; q < kFwdUnroll; ++q) {
-                if (k0 + q < cnt) {
 #pragma unroll
-                    for (int v = 0; v < NV; ++v) {
-                        acc[v].x += x[q][v].x;
-                        acc[v].y += x[q][v].y;
-                        acc[v].z += x[q][v].z;
-                        acc[v].w += x[q][v].w;
-                    }
+                for (int v = 0; v < NV; ++v) {  // rows that were not loaded are zeros
+                    acc[v].x += x[q][v].x;
+                    acc[v].y += x[q][v].y;
+                    acc[v].z += x[q][v].z;
+                    acc[v].w += x[q][v].w;
                 }
             }
         }

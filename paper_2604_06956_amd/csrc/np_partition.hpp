@@ -90,7 +90,21 @@ part_hist_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, Chunk
     const int64_t lo = static_cast<int64_t>(c) * plan.chunk_items;
     int64_t hi = lo + plan.chunk_items;
     if (hi > n) hi = n;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kPartThreads) atomicAdd(&lh[pol.digit(pol.load_key(i))], 1u);
+    constexpr int kBatch = 8;  // independent loads in flight per thread
+    for (int64_t base = lo; base < hi; base += static_cast<int64_t>(kPartThreads) * kBatch) {
+        typename P::KeyT k[kBatch];
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            const int64_t i = base + q * kPartThreads + threadIdx.x;
+            k[q] = typename P::KeyT(0);
+            if (i < hi) k[q] = pol.load_key(i);
+        }
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            const int64_t i = base + q * kPartThreads + threadIdx.x;
+            if (i < hi) atomicAdd(&lh[pol.digit(k[q])], 1u);
+        }
+    }
     __syncthreads();
     for (int b = threadIdx.x; b < bins; b += kPartThreads) H[static_cast<size_t>(c) * bins + b] = lh[b];
 }
