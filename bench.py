@@ -109,7 +109,7 @@ def main() -> int:
     # the unique-key count is known on the host for these synthetic batches, so U-sized buffers use cap, not n
     rr = dict(send_keys=torch.empty(cap, dtype=i64, device=dev), splits=torch.empty(S, dtype=i32, device=dev),
               send_offsets=torch.empty(S + 1, dtype=i32, device=dev), send_from_unique=torch.empty(cap, dtype=i32, device=dev),
-              unique_to_send=torch.empty(cap, dtype=i32, device=dev), lookup_to_send=torch.empty(n_max, dtype=i32, device=dev))
+              unique_to_send=torch.empty(cap, dtype=i32, device=dev))
     out_dtype = B.BF16 if seq else B.F32
     out = torch.empty((cfg.num_bags, max_len, D) if seq else (cfg.num_bags, D),
                       dtype=torch.bfloat16 if seq else torch.float32, device=dev)
@@ -122,8 +122,10 @@ def main() -> int:
         bt = dbatch[i % 2]
         n = bt["n"]
         B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
-        B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, inverse=dd["inverse"], n=n, out=rr, ws=ws_r)
-        B.np_lookup_fwd(table, rr["send_keys"], rr["lookup_to_send"], bt["off"], n, cfg.mode, max_len, out_dtype,
+        B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
+        # the table is local, so the forward reads it through the requester-side list (unique keys, inverse map);
+        # gradients are produced in send order and applied with the send-ordered keys
+        B.np_lookup_fwd(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
                         num_list=dd["num_unique"], cap=cap, out=out)
         B.np_lookup_bwd(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
                         unique_to_send=rr["unique_to_send"], grads=grads, ws=ws_b)

@@ -97,35 +97,50 @@ fwd_pool_kernel(const float* __restrict__ table, int dim, const int64_t* __restr
     }
 }
 
+constexpr int kSeqPerGroup = 4;  // output positions per group, their slot -> key -> row chains in flight together
+
 template <int LPR, int NV, typename OutT>
 __global__ void __launch_bounds__(256)
 fwd_seq_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx,
                const int32_t* __restrict__ bag_offsets, int num_bags, int max_len, OutT* __restrict__ out) {
     constexpr int GPB = 256 / LPR;
     const int r = threadIdx.x % LPR;
-    const int64_t q = static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR;  // output position
     const int64_t total = static_cast<int64_t>(num_bags) * max_len;
-    if (q >= total) return;
-    int b;
-    if (total <= 0xFFFFFFFFll)
-        b = static_cast<int>(static_cast<uint32_t>(q) / static_cast<uint32_t>(max_len));
-    else
-        b = static_cast<int>(q / max_len);
-    const int p = static_cast<int>(q - static_cast<int64_t>(b) * max_len);
-    const int lo = bag_offsets[b], len = bag_offsets[b + 1] - lo;
+    const int64_t q0 = (static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR) * kSeqPerGroup;  // first output position
     const int words = dim / 4;
-    const float4* src = nullptr;
-    if (p < len) {
-        const int j = lo + p;
-        const int64_t row = list_keys[idx ? idx[j] : j];
-        src = reinterpret_cast<const float4*>(table + static_cast<size_t>(row) * dim);
+    const float4* src[kSeqPerGroup];
+#pragma unroll
+    for (int k = 0; k < kSeqPerGroup; ++k) {
+        const int64_t q = q0 + k;
+        src[k] = nullptr;
+        if (q < total) {
+            const int b = static_cast<int>(static_cast<uint32_t>(q) / static_cast<uint32_t>(max_len));  // total < 2^31
+            const int p = static_cast<int>(q - static_cast<int64_t>(b) * max_len);
+            const int lo = bag_offsets[b];
+            if (p < bag_offsets[b + 1] - lo) {
+                const int j = lo + p;
+                src[k] = reinterpret_cast<const float4*>(table + static_cast<size_t>(list_keys[idx ? idx[j] : j]) * dim);
+            }
+        }
+    }
+    float4 x[kSeqPerGroup][NV];
+#pragma unroll
+    for (int k = 0; k < kSeqPerGroup; ++k) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int wv = r + v * LPR;
+            x[k][v] = (src[k] && wv < words) ? src[k][wv] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
     }
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-        const int wv = r + v * LPR;
-        if (wv < words) {
-            const float4 a = src ? src[wv] : make_float4(0.f, 0.f, 0.f, 0.f);
-            store_words(out + static_cast<size_t>(q) * dim + wv * 4, a);
+    for (int k = 0; k < kSeqPerGroup; ++k) {
+        const int64_t q = q0 + k;
+        if (q < total) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int wv = r + v * LPR;
+                if (wv < words) store_words(out + static_cast<size_t>(q) * dim + wv * 4, x[k][v]);
+            }
         }
     }
 }
@@ -168,7 +183,8 @@ void fwd_launch(const FwdArgs& a) {
     if (a.num_bags > 0) {
         if (a.mode == NP_SEQ) {
             const int64_t total = static_cast<int64_t>(a.num_bags) * a.max_len;
-            const unsigned grid = static_cast<unsigned>((total + GPB - 1) / GPB);
+            const int64_t per_block = static_cast<int64_t>(GPB) * kSeqPerGroup;
+            const unsigned grid = static_cast<unsigned>((total + per_block - 1) / per_block);
             if (a.out_dtype == NP_BF16)
                 NP_LAUNCH("fwd_seq", (fwd_seq_kernel<LPR, NV, uint16_t>), dim3(grid), dim3(256), 0, a.stream, a.table, a.dim,
                           a.list_keys, a.idx, a.bag_offsets, a.num_bags, a.max_len, static_cast<uint16_t*>(a.out));
@@ -224,7 +240,7 @@ int np_lookup_fwd(const float* table, int64_t num_rows, int32_t dim, const int64
     if (rows_out && (!d_num_list || !list_keys)) return NP_ERR_INVALID_ARG;
     if (!np::aligned(table, 16) || !np::aligned(out, out_dtype == NP_BF16 ? 8 : 16) || !np::aligned(rows_out, 16))
         return NP_ERR_INVALID_ARG;
-    if (mode == NP_SEQ && static_cast<int64_t>(num_bags) * max_len > (int64_t(1) << 40)) return NP_ERR_UNSUPPORTED;
+    if (mode == NP_SEQ && static_cast<int64_t>(num_bags) * max_len > INT32_MAX) return NP_ERR_UNSUPPORTED;
     np::FwdArgs a{table, dim, list_keys, d_num_list, cap, idx, bag_offsets, num_bags, mode, max_len, out_dtype, out, rows_out,
                   static_cast<hipStream_t>(stream)};
     const int words = dim / 4;

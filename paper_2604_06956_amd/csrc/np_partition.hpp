@@ -121,8 +121,15 @@ part_colscan_kernel(uint32_t* __restrict__ H, int num_chunks, int bins, uint32_t
     const int c0 = y * per;
     const int c1 = c0 + per < num_chunks ? c0 + per : num_chunks;
     uint32_t sum = 0;
-    if (bin < bins)
-        for (int c = c0; c < c1; ++c) sum += H[static_cast<size_t>(c) * bins + bin];
+    if (bin < bins) {
+        for (int c = c0; c < c1; c += 8) {
+            uint32_t t[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) t[q] = c + q < c1 ? H[static_cast<size_t>(c + q) * bins + bin] : 0u;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) sum += t[q];
+        }
+    }
     part[y][lane] = sum;
     __syncthreads();
     uint32_t base = 0, total = 0;
@@ -134,11 +141,15 @@ part_colscan_kernel(uint32_t* __restrict__ H, int num_chunks, int bins, uint32_t
     }
     if (bin < bins) {
         uint32_t run = base;
-        for (int c = c0; c < c1; ++c) {
-            const size_t a = static_cast<size_t>(c) * bins + bin;
-            const uint32_t t = H[a];
-            H[a] = run;
-            run += t;
+        for (int c = c0; c < c1; c += 8) {
+            uint32_t t[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) t[q] = c + q < c1 ? H[static_cast<size_t>(c + q) * bins + bin] : 0u;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (c + q < c1) H[static_cast<size_t>(c + q) * bins + bin] = run;
+                run += t[q];
+            }
         }
         if (y == 0) bin_total[bin] = total;
     }
