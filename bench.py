@@ -44,6 +44,11 @@ def algorithmic_bytes(n: int, U: int, B: int, D: int, S: int, mode: int, max_len
     }
 
 
+# HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the copy-kernel
+# calibration; see profiles/large_step_kernels.txt), keyed by (workload, kernel).  Static: bench.py cannot run
+# the profiler on itself.
+MEASURED_TRAFFIC = {("large", "bwd_main"): 14.66e9, ("large", "fwd_pool"): 9.64e9, ("large", "sparse_adagrad"): 8.39e9}
+
 # the kernel that carries (nearly all of) each call's algorithmic bytes
 KERNEL_OF_CALL = {"sparse_adagrad": "np_sparse_adagrad", "bwd_main": "np_lookup_bwd", "fwd_pool": "np_lookup_fwd",
                   "fwd_seq": "np_lookup_fwd"}
@@ -219,7 +224,7 @@ def main() -> int:
                    "hottest_key_count": [s["hottest"] for s in stats], "distinct_key_overlap": overlap,
                    "num_bags": cfg.num_bags, "max_len": max_len},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((cfg.name, dominant)),
                      "algorithmic_bytes_per_launch": alg[dom_call], "avg_launch_ms": kernels[dominant]["avg_ms"]},
         "cpu_baseline": cpu,
         "fwd_bwd_update": {"ms_per_step": fbu_ms, "lookups_per_s": n_avg / (fbu_ms * 1e-3) if fbu_ms > 0 else None,
