@@ -337,3 +337,45 @@ int np_ref_sparse_adagrad(float* table, float* state, int64_t num_rows, int32_t 
     }
     return 0;
 }
+
+/* ------------------------------------------------- dual-buffer synchronisation (Section IV-B) -------- */
+
+/*
+ * Section IV-B: before batch B_t starts its forward pass, the intersection of the compact key sets of the two
+ * consecutive batches is taken (on keys, not on vectors).  keys_a and keys_b are ascending and distinct.
+ * Output, in ascending key order: pairs (idx_a[i], idx_b[i]) with keys_a[idx_a[i]] == keys_b[idx_b[i]].
+ * A plain two-pointer merge.
+ */
+int np_ref_intersect(const int64_t* keys_a, int32_t na, const int64_t* keys_b, int32_t nb, int32_t* idx_a,
+                     int32_t* idx_b, int32_t* num_common) {
+    if (na < 0 || nb < 0 || !num_common) return -1;
+    int32_t i = 0, j = 0, c = 0;
+    while (i < na && j < nb) {
+        if (keys_a[i] < keys_b[j]) {
+            ++i;
+        } else if (keys_b[j] < keys_a[i]) {
+            ++j;
+        } else {
+            idx_a[c] = i;
+            idx_b[c] = j;
+            ++c;
+            ++i;
+            ++j;
+        }
+    }
+    *num_common = c;
+    return 0;
+}
+
+/*
+ * Section IV-B: the vectors of the intersecting keys are copied from the active buffer (which holds the
+ * updates of B_{t-1}) into the prefetch buffer (which was filled for B_t before those updates): Eq. (2),
+ * second case.  dst[dst_idx[i], :] = src[src_idx[i], :] for i < count, a bit copy.
+ */
+int np_ref_sync_rows(const float* src, const int32_t* src_idx, float* dst, const int32_t* dst_idx, int32_t count,
+                     int32_t dim) {
+    if (count < 0 || dim < 1) return -1;
+    for (int32_t i = 0; i < count; ++i)
+        memcpy(dst + (size_t)dst_idx[i] * (size_t)dim, src + (size_t)src_idx[i] * (size_t)dim, sizeof(float) * (size_t)dim);
+    return 0;
+}

@@ -51,7 +51,7 @@ def _load():
         _lib.np_ref_bf16_to_f32.restype = ctypes.c_float
         _lib.np_ref_bf16_to_f32.argtypes = [ctypes.c_uint16]
         for name in ("np_ref_dedup", "np_ref_route", "np_ref_compose", "np_ref_lookup_fwd", "np_ref_lookup_bwd",
-                     "np_ref_sparse_adagrad"):
+                     "np_ref_sparse_adagrad", "np_ref_intersect", "np_ref_sync_rows"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -181,6 +181,30 @@ def sparse_adagrad(table: np.ndarray, state: np.ndarray, list_keys, grads, lr: f
                                        _p(grads), ctypes.c_int32(list_keys.shape[0]), ctypes.c_float(lr),
                                        ctypes.c_float(eps))
     _chk(rc, "sparse_adagrad")
+
+
+def intersect(keys_a, keys_b) -> Tuple[np.ndarray, np.ndarray]:
+    """-> idx_a, idx_b (int32): positions of the common keys of two ascending distinct key lists, ascending."""
+    a = _as(keys_a, np.int64)
+    b = _as(keys_b, np.int64)
+    m = max(1, min(a.shape[0], b.shape[0]))
+    ia = np.empty(m, np.int32)
+    ib = np.empty(m, np.int32)
+    c = ctypes.c_int32(-1)
+    rc = _load().np_ref_intersect(_p(a), ctypes.c_int32(a.shape[0]), _p(b), ctypes.c_int32(b.shape[0]), _p(ia), _p(ib),
+                                  ctypes.byref(c))
+    _chk(rc, "intersect")
+    return ia[:c.value].copy(), ib[:c.value].copy()
+
+
+def sync_rows(src: np.ndarray, src_idx, dst: np.ndarray, dst_idx) -> None:
+    """dst[dst_idx[i]] = src[src_idx[i]] in place on ``dst`` (both [*, D] fp32, C-contiguous)."""
+    assert src.dtype == np.float32 and dst.dtype == np.float32 and src.shape[1] == dst.shape[1]
+    assert src.flags["C_CONTIGUOUS"] and dst.flags["C_CONTIGUOUS"]
+    si = _as(src_idx, np.int32)
+    di = _as(dst_idx, np.int32)
+    rc = _load().np_ref_sync_rows(_p(src), _p(si), _p(dst), _p(di), ctypes.c_int32(si.shape[0]), ctypes.c_int32(src.shape[1]))
+    _chk(rc, "sync_rows")
 
 
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
