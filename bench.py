@@ -200,6 +200,33 @@ def main() -> int:
     copy_gbs = 2 * words * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del src, dst
 
+    # ---- dual-buffer synchronisation of the two batches (Section IV-B), timed on its own: key-set intersection
+    # plus the copy of the common rows from an active to a prefetch row buffer
+    B.np_dedup(dbatch[0]["keys"], cfg.key_bits, out=dd, ws=ws_d)
+    ua, na_ = dd["unique"][:cap].clone(), dd["num_unique"].clone()
+    B.np_dedup(dbatch[1]["keys"], cfg.key_bits, out=dd, ws=ws_d)
+    ub, nb_ = dd["unique"][:cap], dd["num_unique"]
+    active = torch.empty((cap, D), dtype=torch.float32, device=dev)
+    prefetch = torch.empty((cap, D), dtype=torch.float32, device=dev)
+    isec = B.np_intersect(ua, na_, cap, ub, nb_, cap)
+    B.np_sync_rows(active, isec["idx_a"], prefetch, isec["idx_b"], isec["num_common"], cap)
+    torch.cuda.synchronize()
+    B.np_prof_enable(True)
+    reps = 5
+    for _ in range(reps):
+        B.np_intersect(ua, na_, cap, ub, nb_, cap, out=isec)
+        B.np_sync_rows(active, isec["idx_a"], prefetch, isec["idx_b"], isec["num_common"], cap)
+    torch.cuda.synchronize()
+    sync_rec = B.np_prof_collect(1024)
+    B.np_prof_enable(False)
+    common = int(isec["num_common"].item())
+    sync_k = {}
+    for name, ms in sync_rec:
+        sync_k[name] = sync_k.get(name, 0.0) + ms / reps
+    dbsync = {"common_keys": common, "ms": sum(sync_k.values()), "kernels_ms": sync_k,
+              "row_copy_GBps": 2 * common * 4 * D / (sync_k.get("sync_rows", 1e9) * 1e-3) / 1e9}
+    del active, prefetch, ua
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(cfg, b0, wl, args.cpu_sample_div)
@@ -234,6 +261,7 @@ def main() -> int:
                       "algorithmic_GBps": alg[c] / (call_ms[c] * 1e-3) / 1e9 if call_ms.get(c, 0.0) > 0 else None}
                   for c in alg},
         "kernels": kernels,
+        "dual_buffer_sync": dbsync,
         "ms_per_step_without_events": ms_per_step_noevents,
         "stream_copy_GBps": copy_gbs,
         "input_generation_s": gen_s,

@@ -172,6 +172,34 @@ int np_sparse_adagrad(float* table, float* state, int64_t num_rows, int32_t dim,
                       const float* grads, const int32_t* d_num_list, int32_t cap, float lr, float eps,
                       void* stream);
 
+/* ---- dual-buffer synchronisation (Section IV-B) --------------------------------------------------- */
+
+/*
+ * np_intersect - Section IV-B: "a dedicated kernel computes the intersection of compact key sets between
+ * consecutive batches, rather than full embedding vectors".
+ *
+ *   keys_a [cap_a] in  ascending distinct keys of B_{t-1} (np_dedup's unique), *d_num_a valid
+ *   keys_b [cap_b] in  ascending distinct keys of B_t, *d_num_b valid
+ *   idx_a, idx_b [min(cap_a, cap_b)] out  keys_a[idx_a[i]] == keys_b[idx_b[i]] for i < *d_num_common, in
+ *                      ascending key order; every common key appears exactly once
+ *   d_num_common [1]   out
+ * Bit-exact function of the inputs.  Either list may be empty.
+ */
+int np_intersect(const int64_t* keys_a, const int32_t* d_num_a, int32_t cap_a, const int64_t* keys_b,
+                 const int32_t* d_num_b, int32_t cap_b, int32_t* idx_a, int32_t* idx_b, int32_t* d_num_common, void* ws,
+                 size_t ws_bytes, void* stream);
+size_t np_intersect_workspace_bytes(int32_t cap_b);
+
+/*
+ * np_sync_rows - Section IV-B: the vectors of the common keys are copied from the active buffer to the prefetch
+ * buffer with device-to-device copies (Eq. (2), second case: a key of B_{t-1} carries its updated vector).
+ *
+ *   dst_rows[dst_idx[i], :] = src_rows[src_idx[i], :]  for i < *d_count (device), a bit copy of fp32 rows of
+ *   width dim.  dst_idx entries are pairwise distinct; rows of dst that are not named keep their bits.
+ */
+int np_sync_rows(const float* src_rows, const int32_t* src_idx, float* dst_rows, const int32_t* dst_idx,
+                 const int32_t* d_count, int32_t cap, int32_t dim, void* stream);
+
 /* ---- harness utilities (not on the hot path) ------------------------------------------------------ */
 
 /*

@@ -58,6 +58,12 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.np_lookup_bwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
     L.np_sparse_adagrad.restype = ctypes.c_int
     L.np_sparse_adagrad.argtypes = [_vp, _vp, _i64, _i32, _vp, _vp, _vp, _i32, _f32, _f32, _vp]
+    L.np_intersect.restype = ctypes.c_int
+    L.np_intersect.argtypes = [_vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.np_intersect_workspace_bytes.restype = _sz
+    L.np_intersect_workspace_bytes.argtypes = [_i32]
+    L.np_sync_rows.restype = ctypes.c_int
+    L.np_sync_rows.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]
     L.np_util_table_init.restype = ctypes.c_int
     L.np_util_table_init.argtypes = [_vp, _i64, _i32, _u64, _vp]
     L.np_util_table_count_changed.restype = ctypes.c_int
@@ -213,6 +219,28 @@ def np_sparse_adagrad(table: torch.Tensor, state: torch.Tensor, list_keys: torch
     rc = lib.np_sparse_adagrad(_ptr(table), _ptr(state), num_rows, dim, _ptr(list_keys), _ptr(grads), _ptr(num_list), cap,
                                lr, eps, _stream())
     _chk("np_sparse_adagrad", rc)
+
+
+def np_intersect(keys_a: torch.Tensor, num_a: torch.Tensor, cap_a: int, keys_b: torch.Tensor, num_b: torch.Tensor, cap_b: int,
+                 out: Optional[Dict[str, torch.Tensor]] = None, ws: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """-> dict(idx_a, idx_b [min(cap_a, cap_b)] i32, num_common[1] i32)."""
+    dev = keys_a.device
+    if out is None:
+        m = max(1, min(cap_a, cap_b))
+        out = dict(idx_a=torch.empty(m, dtype=torch.int32, device=dev), idx_b=torch.empty(m, dtype=torch.int32, device=dev),
+                   num_common=torch.empty(1, dtype=torch.int32, device=dev))
+    ws, ws_bytes = _ws(int(lib.np_intersect_workspace_bytes(cap_b)), ws, dev)
+    rc = lib.np_intersect(_ptr(keys_a), _ptr(num_a), cap_a, _ptr(keys_b), _ptr(num_b), cap_b, _ptr(out["idx_a"]),
+                          _ptr(out["idx_b"]), _ptr(out["num_common"]), _ptr(ws), ws_bytes, _stream())
+    _chk("np_intersect", rc)
+    return out
+
+
+def np_sync_rows(src_rows: torch.Tensor, src_idx: torch.Tensor, dst_rows: torch.Tensor, dst_idx: torch.Tensor,
+                 count: torch.Tensor, cap: int) -> None:
+    dim = src_rows.shape[1]
+    rc = lib.np_sync_rows(_ptr(src_rows), _ptr(src_idx), _ptr(dst_rows), _ptr(dst_idx), _ptr(count), cap, dim, _stream())
+    _chk("np_sync_rows", rc)
 
 
 def np_util_table_init(table: torch.Tensor, seed: int) -> None:
