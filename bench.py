@@ -62,6 +62,8 @@ def main() -> int:
     ap.add_argument("--workload", default="large")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-div", type=int, default=4)
+    ap.add_argument("--fwp-report", action="store_true",
+                    help="also dedup batch 0 split into N micro-batches of consecutive samples and report sum(U_i)/U")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives are built; "
@@ -227,6 +229,29 @@ def main() -> int:
               "row_copy_GBps": 2 * common * 4 * D / (sync_k.get("sync_rows", 1e9) * 1e-3) / 1e9}
     del active, prefetch, ua
 
+    fwp = None
+    if args.fwp_report:
+        # frozen-window micro-batching (Section V): keys are deduplicated inside each micro-batch only, so the
+        # vectors crossing the All2All inflate from U to sum(U_i)
+        fwp = {}
+        keys0, off0 = dbatch[0]["keys"], batches[0].bag_offsets
+        for N in (1, 2, 4, 8, 16, 32):
+            tot, ms = 0, 0.0
+            for i in range(N):
+                s0, s1 = cfg.batch * i // N, cfg.batch * (i + 1) // N
+                sl = [keys0[int(off0[f * cfg.batch + s0]):int(off0[f * cfg.batch + s1])] for f in range(cfg.features)]
+                mk = torch.cat(sl).contiguous()
+                if mk.numel() == 0:
+                    continue
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                B.np_dedup(mk, cfg.key_bits, out=dd, ws=ws_d)
+                e1.record()
+                torch.cuda.synchronize()
+                tot += int(dd["num_unique"].item())
+                ms += e0.elapsed_time(e1)
+            fwp[str(N)] = {"sum_unique": tot, "inflation": tot / stats[0]["U"], "dedup_ms_total": ms}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(cfg, b0, wl, args.cpu_sample_div)
@@ -262,6 +287,7 @@ def main() -> int:
                   for c in alg},
         "kernels": kernels,
         "dual_buffer_sync": dbsync,
+        "frozen_window_dedup": fwp,
         "ms_per_step_without_events": ms_per_step_noevents,
         "stream_copy_GBps": copy_gbs,
         "input_generation_s": gen_s,
