@@ -157,6 +157,36 @@ def main() -> int:
     lookups = sum(dbatch[(args.warmup + i) % 2]["n"] for i in range(args.steps))
     value = lookups / (t1 - t0)
 
+    # ---- the variant with backward and update fused (np_lookup_bwd_adagrad): not the headline, reported beside it
+    def step_fused(i: int) -> None:
+        bt = dbatch[i % 2]
+        n = bt["n"]
+        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
+        B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
+        B.np_lookup_fwd(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
+                        num_list=dd["num_unique"], cap=cap, out=out)
+        B.np_lookup_bwd_adagrad(bt["dY"], cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["unique"],
+                                dd["num_unique"], cap, table, state, cfg.lr, cfg.eps, ws=ws_b)
+
+    fused = None
+    if D <= 256:
+        step_fused(0)
+        B.np_prof_enable(True)
+        torch.cuda.synchronize()
+        tf0 = time.perf_counter()
+        for i in range(args.steps):
+            step_fused(args.warmup + i)
+        torch.cuda.synchronize()
+        fused_ms = (time.perf_counter() - tf0) * 1e3 / args.steps
+        frec = B.np_prof_collect(65536)
+        B.np_prof_enable(False)
+        fk = {}
+        for name, ms in frec:
+            fk[name] = fk.get(name, 0.0) + ms / args.steps
+        fused = {"ms_per_step": fused_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (fused_ms * 1e-3 * args.steps),
+                 "bwd_update_ms": sum(v for k, v in fk.items() if k.startswith("bwd")),
+                 "kernels_ms": {k: v for k, v in fk.items() if k.startswith("bwd")}}
+
     # ---- the same K steps without event recording (what the events cost)
     torch.cuda.synchronize()
     t2 = time.perf_counter()
@@ -286,6 +316,7 @@ def main() -> int:
                       "algorithmic_GBps": alg[c] / (call_ms[c] * 1e-3) / 1e9 if call_ms.get(c, 0.0) > 0 else None}
                   for c in alg},
         "kernels": kernels,
+        "fused_bwd_update_step": fused,
         "dual_buffer_sync": dbsync,
         "frozen_window_dedup": fwp,
         "ms_per_step_without_events": ms_per_step_noevents,
@@ -294,6 +325,10 @@ def main() -> int:
     }
     print(json.dumps(line))
     return 0
+
+
+def n_steps_lookups(dbatch, args) -> int:
+    return sum(dbatch[(args.warmup + i) % 2]["n"] for i in range(args.steps))
 
 
 def cpu_baseline(cfg, batch, wl, div: int):

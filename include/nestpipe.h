@@ -172,6 +172,21 @@ int np_sparse_adagrad(float* table, float* state, int64_t num_rows, int32_t dim,
                       const float* grads, const int32_t* d_num_list, int32_t cap, float lr, float eps,
                       void* stream);
 
+/*
+ * np_lookup_bwd_adagrad - np_lookup_bwd and np_sparse_adagrad in one pass for a worker that owns the rows it
+ * reduces (no gradient All2All in between): every finished gradient row is applied on the spot to
+ * table[unique[u], :] with the row-wise Adagrad rule above and is never written to HBM (Section IV-B: gradients
+ * are applied directly to the vectors of the active buffer).  Same sums, same order, same update arithmetic as
+ * the two separate calls: the table and state come out bit-identical.  dim <= 256.
+ *
+ *   unique [cap] in  np_dedup's distinct keys (pairwise distinct, so every row is updated exactly once)
+ *   other arguments as in np_lookup_bwd / np_sparse_adagrad; workspace as np_lookup_bwd_workspace_bytes.
+ */
+int np_lookup_bwd_adagrad(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
+                          const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
+                          const int32_t* occ, const int64_t* unique, const int32_t* d_num_unique, int32_t cap, float* table,
+                          float* state, int64_t num_rows, float lr, float eps, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- dual-buffer synchronisation (Section IV-B) --------------------------------------------------- */
 
 /*

@@ -30,22 +30,19 @@ adagrad_kernel(float* __restrict__ table, float* __restrict__ state, int dim, co
                 g[v] = gsrc[wv];
                 w[v] = wrow[wv];
             }
-            ss += g[v].x * g[v].x + g[v].y * g[v].y + g[v].z * g[v].z + g[v].w * g[v].w;
+            ss += sumsq4(g[v]);
         }
         const float s_old = state[key];
 #pragma unroll
         for (int d = LPR / 2; d > 0; d >>= 1) ss += __shfl_xor(ss, d, kWave);
-        const float G = s_old + ss * inv_dim;
+        const float G = adagrad_state(s_old, ss, inv_dim);
         const float denom = sqrtf(G) + eps;
         if (r == 0) state[key] = G;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int wv = r + v * LPR;
             if (wv < words) {
-                w[v].x -= lr * g[v].x / denom;
-                w[v].y -= lr * g[v].y / denom;
-                w[v].z -= lr * g[v].z / denom;
-                w[v].w -= lr * g[v].w / denom;
+                adagrad_step4(w[v], g[v], lr, denom);
                 wrow[wv] = w[v];
             }
         }

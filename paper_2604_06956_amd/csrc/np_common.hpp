@@ -139,6 +139,19 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float x) {
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(static_cast<uint32_t>(h) << 16); }
 
+// Row-wise Adagrad pieces shared by np_sparse_adagrad and the fused backward: written with explicit fused
+// multiply-adds so that both kernels round identically whatever the compiler would contract on its own.
+__device__ __forceinline__ float sumsq4(const float4& g) { return fmaf(g.w, g.w, fmaf(g.z, g.z, fmaf(g.y, g.y, g.x * g.x))); }
+
+__device__ __forceinline__ float adagrad_state(float s_old, float sumsq, float inv_dim) { return fmaf(sumsq, inv_dim, s_old); }
+
+__device__ __forceinline__ void adagrad_step4(float4& w, const float4& g, float lr, float denom) {
+    w.x -= (lr * g.x) / denom;
+    w.y -= (lr * g.y) / denom;
+    w.z -= (lr * g.z) / denom;
+    w.w -= (lr * g.w) / denom;
+}
+
 // Row geometry shared by the row kernels: a row of `dim` floats is dim/4 float4 words, handled by LPR
 // lanes holding NV words each (word index = lane_in_group + v * LPR).
 template <int LPR, int NV>

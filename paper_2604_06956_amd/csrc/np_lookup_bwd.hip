@@ -152,13 +152,51 @@ __device__ __forceinline__ float4 load_dy(const uint16_t* dY, int row, int dim, 
                        __uint_as_float(p.y & 0xFFFF0000u));
 }
 
-template <int LPR, int NV, bool MEAN, typename DyT>
+// Where a finished gradient row goes.  Plain: grads[dst, :].  Fused (np_lookup_bwd_adagrad): the row is consumed on
+// the spot by the row-wise Adagrad step on table[keys[dst], :] and never reaches HBM; the arithmetic is the one
+// of np_sparse_adagrad (same butterfly over the LPR lanes of a row), so both routes give the same bits.
+struct RowSink {
+    float* grads;
+    float* table;
+    float* state;
+    const int64_t* keys;
+    float lr, eps, inv_dim;
+};
+
+// Called by all LPR lanes that hold a row (lane r holds float4 word r; NV == 1 on the fused route).
+template <int LPR, bool FUSED>
+__device__ __forceinline__ void sink_row(const RowSink& sk, int dst, int dim, int r, int words, const float4& g) {
+    if (!FUSED) {
+        if (r < words) reinterpret_cast<float4*>(sk.grads + static_cast<size_t>(dst) * dim)[r] = g;
+        return;
+    }
+    const int64_t key = sk.keys[dst];
+    float4* wrow = reinterpret_cast<float4*>(sk.table + static_cast<size_t>(key) * dim);
+    float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
+    float ss = 0.f;
+    if (r < words) {
+        w = wrow[r];
+        ss += sumsq4(g);
+    }
+    const float s_old = sk.state[key];
+#pragma unroll
+    for (int d = LPR / 2; d > 0; d >>= 1) ss += __shfl_xor(ss, d, kWave);
+    const float G = adagrad_state(s_old, ss, sk.inv_dim);
+    const float denom = sqrtf(G) + sk.eps;
+    if (r == 0) sk.state[key] = G;
+    if (r < words) {
+        adagrad_step4(w, g, sk.lr, denom);
+        wrow[r] = w;
+    }
+}
+
+template <int LPR, int NV, bool MEAN, typename DyT, bool FUSED>
 __global__ void __launch_bounds__(256)
 bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const int32_t* __restrict__ bag_offsets, int n,
                 const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ occ, const int32_t* __restrict__ d_num_unique,
                 const int32_t* __restrict__ unique_to_send, const BagMapEntry* __restrict__ bagmap,
                 const int32_t* __restrict__ tile_seg0, const int32_t* __restrict__ order, const int32_t* __restrict__ order_offsets,
-                int num_tiles, float* __restrict__ grads, float* __restrict__ tile_left, float* __restrict__ tile_right,
+                int num_tiles, RowSink sink, float* __restrict__ tile_left, float* __restrict__ tile_right,
                 int32_t* __restrict__ tile_rseg) {
     constexpr int GPB = 256 / LPR;
     constexpr int ROWW = LPR * NV;  // float4 words per (padded) row
@@ -285,10 +323,14 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                 dlast = dk;
                 if (dk >= 0) {  // a segment ends here
                     if (!first_open) {
+                        if (FUSED) {
+                            sink_row<LPR, FUSED>(sink, dk, dim, r, words, acc[0]);
+                        } else {
 #pragma unroll
-                        for (int v = 0; v < NV; ++v) {
-                            const int wv = r + v * LPR;
-                            if (wv < words) reinterpret_cast<float4*>(grads + static_cast<size_t>(dk) * dim)[wv] = acc[v];
+                            for (int v = 0; v < NV; ++v) {
+                                const int wv = r + v * LPR;
+                                if (wv < words) reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dk) * dim)[wv] = acc[v];
+                            }
                         }
                     } else {
 #pragma unroll
@@ -342,9 +384,11 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                     open = true;
                 }
                 if (l_closed[gg]) {
-                    if (t < words) {
-                        if (started_here) reinterpret_cast<float4*>(grads + static_cast<size_t>(l_dst[gg]) * dim)[t] = carry;
-                        else reinterpret_cast<float4*>(tile_left + static_cast<size_t>(tile) * dim)[t] = carry;
+                    if (started_here) {
+                        if (FUSED) sink_row<LPR, FUSED>(sink, l_dst[gg], dim, t, words, carry);  // ROWW == LPR here
+                        else if (t < words) reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(l_dst[gg]) * dim)[t] = carry;
+                    } else if (t < words) {
+                        reinterpret_cast<float4*>(tile_left + static_cast<size_t>(tile) * dim)[t] = carry;
                     }
                     open = false;
                 }
@@ -370,11 +414,11 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
 constexpr int kFixupShort = 8;
 constexpr int kFixupThreads = 1024;
 
-template <int LPR, int NV>
+template <int LPR, int NV, bool FUSED>
 __global__ void __launch_bounds__(256)
 bwd_fixup_short_kernel(int dim, int num_tiles, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
                        const float* __restrict__ tile_left, const float* __restrict__ tile_right,
-                       const int32_t* __restrict__ tile_rseg, float* __restrict__ grads, int32_t* __restrict__ long_count,
+                       const int32_t* __restrict__ tile_rseg, RowSink sink, int32_t* __restrict__ long_count,
                        int32_t* __restrict__ long_tiles) {
     constexpr int GPB = 256 / LPR;
     const int r = threadIdx.x % LPR;
@@ -410,18 +454,22 @@ bwd_fixup_short_kernel(int dim, int num_tiles, const int32_t* __restrict__ occ_o
         }
     }
     const int dst = unique_to_send ? unique_to_send[seg] : seg;
+    if (FUSED) {
+        sink_row<LPR, FUSED>(sink, dst, dim, r, words, acc[0]);
+    } else {
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-        const int wv = r + v * LPR;
-        if (wv < words) reinterpret_cast<float4*>(grads + static_cast<size_t>(dst) * dim)[wv] = acc[v];
+        for (int v = 0; v < NV; ++v) {
+            const int wv = r + v * LPR;
+            if (wv < words) reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dst) * dim)[wv] = acc[v];
+        }
     }
 }
 
-template <int LPR, int NV>
+template <int LPR, int NV, bool FUSED>
 __global__ void __launch_bounds__(kFixupThreads)
 bwd_fixup_long_kernel(int dim, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
                       const float* __restrict__ tile_left, const float* __restrict__ tile_right,
-                      const int32_t* __restrict__ tile_rseg, float* __restrict__ grads, const int32_t* __restrict__ long_count,
+                      const int32_t* __restrict__ tile_rseg, RowSink sink, const int32_t* __restrict__ long_count,
                       const int32_t* __restrict__ long_tiles) {
     constexpr int GPB = kFixupThreads / LPR;
     constexpr int ROWW = LPR * NV;
@@ -468,8 +516,9 @@ bwd_fixup_long_kernel(int dim, const int32_t* __restrict__ occ_offsets, const in
         for (int v = 0; v < NV; ++v) part[g * ROWW + r + v * LPR] = acc[v];
         __syncthreads();
         const int t = threadIdx.x;
-        if (t < words) {
-            float4 s = reinterpret_cast<const float4*>(tile_right + static_cast<size_t>(tile) * dim)[t];
+        if (t < ROWW) {  // the first ROWW threads hold one word of the row each (words past the row are zeros)
+            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t < words) s = reinterpret_cast<const float4*>(tile_right + static_cast<size_t>(tile) * dim)[t];
             for (int gg = 0; gg < GPB; ++gg) {
                 if (gg * per < count) {
                     const float4 q = part[gg * ROWW + t];
@@ -480,7 +529,8 @@ bwd_fixup_long_kernel(int dim, const int32_t* __restrict__ occ_offsets, const in
                 }
             }
             const int dst = unique_to_send ? unique_to_send[seg] : seg;
-            reinterpret_cast<float4*>(grads + static_cast<size_t>(dst) * dim)[t] = s;
+            if (FUSED) sink_row<LPR, FUSED>(sink, dst, dim, t, words, s);
+            else if (t < words) reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dst) * dim)[t] = s;
         }
     }
 }
@@ -512,12 +562,12 @@ struct BwdArgs {
     const int32_t* occ;
     const int32_t* d_num_unique;
     const int32_t* unique_to_send;
-    float* grads;
+    RowSink sink;
     void* ws;
     hipStream_t stream;
 };
 
-template <int LPR, int NV>
+template <int LPR, int NV, bool FUSED>
 void bwd_launch(const BwdArgs& a) {
     const BwdWs L = bwd_ws_layout(a.n, a.dim);
     WsCursor cur(a.ws);
@@ -549,29 +599,29 @@ void bwd_launch(const BwdArgs& a) {
     if (a.dy_dtype == NP_BF16) {
         const uint16_t* dy = static_cast<const uint16_t*>(a.dY);
         if (mean)
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, uint16_t>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.grads,
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, uint16_t, FUSED>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.sink,
                       tile_left, tile_right, tile_rseg);
         else
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, uint16_t>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.grads,
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, uint16_t, FUSED>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.sink,
                       tile_left, tile_right, tile_rseg);
     } else {
         const float* dy = static_cast<const float*>(a.dY);
         if (mean)
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, float>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.grads,
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, float, FUSED>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.sink,
                       tile_left, tile_right, tile_rseg);
         else
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, float>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.grads,
+            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, float, FUSED>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
+                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.sink,
                       tile_left, tile_right, tile_rseg);
     }
     constexpr int GPB = 256 / LPR;
-    NP_LAUNCH("bwd_fixup_short", (bwd_fixup_short_kernel<LPR, NV>), dim3((L.num_tiles + GPB - 1) / GPB), dim3(256), 0, a.stream, a.dim,
-              L.num_tiles, a.occ_offsets, a.unique_to_send, tile_left, tile_right, tile_rseg, a.grads, long_count, long_tiles);
-    NP_LAUNCH("bwd_fixup_long", (bwd_fixup_long_kernel<LPR, NV>), dim3(512), dim3(kFixupThreads), 0, a.stream, a.dim, a.occ_offsets,
-              a.unique_to_send, tile_left, tile_right, tile_rseg, a.grads, long_count, long_tiles);
+    NP_LAUNCH("bwd_fixup_short", (bwd_fixup_short_kernel<LPR, NV, FUSED>), dim3((L.num_tiles + GPB - 1) / GPB), dim3(256), 0, a.stream, a.dim,
+              L.num_tiles, a.occ_offsets, a.unique_to_send, tile_left, tile_right, tile_rseg, a.sink, long_count, long_tiles);
+    NP_LAUNCH("bwd_fixup_long", (bwd_fixup_long_kernel<LPR, NV, FUSED>), dim3(512), dim3(kFixupThreads), 0, a.stream, a.dim, a.occ_offsets,
+              a.unique_to_send, tile_left, tile_right, tile_rseg, a.sink, long_count, long_tiles);
 }
 
 }  // namespace np
@@ -600,15 +650,41 @@ int np_lookup_bwd(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, i
     if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(grads, 16)) return NP_ERR_INVALID_ARG;
     if (!ws || !np::aligned(ws, 256) || ws_bytes < np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode)) return NP_ERR_WORKSPACE;
     np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, unique_to_send,
-                  grads, ws, static_cast<hipStream_t>(stream)};
+                  np::RowSink{grads, nullptr, nullptr, nullptr, 0.f, 0.f, 0.f}, ws, static_cast<hipStream_t>(stream)};
     const int words = dim / 4;
-    if (words <= 4) np::bwd_launch<4, 1>(a);
-    else if (words <= 8) np::bwd_launch<8, 1>(a);
-    else if (words <= 16) np::bwd_launch<16, 1>(a);
-    else if (words <= 32) np::bwd_launch<32, 1>(a);
-    else if (words <= 64) np::bwd_launch<64, 1>(a);
-    else if (words <= 128) np::bwd_launch<64, 2>(a);
-    else np::bwd_launch<64, 4>(a);
+    if (words <= 4) np::bwd_launch<4, 1, false>(a);
+    else if (words <= 8) np::bwd_launch<8, 1, false>(a);
+    else if (words <= 16) np::bwd_launch<16, 1, false>(a);
+    else if (words <= 32) np::bwd_launch<32, 1, false>(a);
+    else if (words <= 64) np::bwd_launch<64, 1, false>(a);
+    else if (words <= 128) np::bwd_launch<64, 2, false>(a);
+    else np::bwd_launch<64, 4, false>(a);
+    return np::launch_status();
+}
+
+int np_lookup_bwd_adagrad(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
+                          const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
+                          const int32_t* occ, const int64_t* unique, const int32_t* d_num_unique, int32_t cap, float* table,
+                          float* state, int64_t num_rows, float lr, float eps, void* ws, size_t ws_bytes, void* stream) {
+    if (num_bags < 0 || n < 0 || cap < 0 || !d_num_unique || !table || !state || num_rows < 1) return NP_ERR_INVALID_ARG;
+    if (mode != NP_POOL_SUM && mode != NP_POOL_MEAN && mode != NP_SEQ) return NP_ERR_INVALID_ARG;
+    if (dy_dtype != NP_F32 && dy_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
+    if (mode == NP_SEQ && max_len < 1) return NP_ERR_INVALID_ARG;
+    if (dim < 4 || dim % 4 != 0 || dim > 256) return NP_ERR_UNSUPPORTED;  // a row must fit one wave of float4 words
+    if (mode == NP_SEQ && static_cast<int64_t>(num_bags) * max_len > INT32_MAX) return NP_ERR_UNSUPPORTED;
+    if (n == 0) return NP_OK;
+    if (!dY || !bag_offsets || !occ_offsets || !occ || !unique || num_bags < 1) return NP_ERR_INVALID_ARG;
+    if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(table, 16)) return NP_ERR_INVALID_ARG;
+    if (!ws || !np::aligned(ws, 256) || ws_bytes < np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode)) return NP_ERR_WORKSPACE;
+    np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, nullptr,
+                  np::RowSink{nullptr, table, state, unique, lr, eps, 1.0f / static_cast<float>(dim)}, ws,
+                  static_cast<hipStream_t>(stream)};
+    const int words = dim / 4;
+    if (words <= 4) np::bwd_launch<4, 1, true>(a);
+    else if (words <= 8) np::bwd_launch<8, 1, true>(a);
+    else if (words <= 16) np::bwd_launch<16, 1, true>(a);
+    else if (words <= 32) np::bwd_launch<32, 1, true>(a);
+    else np::bwd_launch<64, 1, true>(a);
     return np::launch_status();
 }
 
