@@ -18,8 +18,9 @@
 //                  across the groups of the block in strip order; sums cut by a tile edge are parked in the
 //                  workspace as the tile's "left" (continues from an earlier tile) and "right" (continues
 //                  into later tiles) partials.
-//   bwd_fixup      the tile where a cut segment starts adds its right partial and the left partials of the
-//                  following tiles in tile order, with a fixed split of long chains over the block.
+//   bwd_fixup_*    the tile where a cut segment starts adds its right partial and the left partials of the
+//                  following tiles in tile order: one group per tile for short chains, one block per listed
+//                  long chain with a fixed split of the chain over the block.
 //
 // The order of every floating-point addition is a function of occ_offsets alone: no atomics, no dependence
 // on scheduling, so two runs give the same bits.  A hot key with millions of lookups costs the same per
