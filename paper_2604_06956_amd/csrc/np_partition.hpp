@@ -91,6 +91,7 @@ part_hist_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, Chunk
     int64_t hi = lo + plan.chunk_items;
     if (hi > n) hi = n;
     constexpr int kBatch = 8;  // independent loads in flight per thread
+    const int lane = threadIdx.x % kWave;
     for (int64_t base = lo; base < hi; base += static_cast<int64_t>(kPartThreads) * kBatch) {
         typename P::KeyT k[kBatch];
 #pragma unroll
@@ -101,8 +102,21 @@ part_hist_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, Chunk
         }
 #pragma unroll
         for (int q = 0; q < kBatch; ++q) {
+            // The lanes of a wave hold consecutive items, so the valid lanes are a prefix of the wave.  After the
+            // first pass equal digits arrive in runs (a popular key fills whole waves): one add per run of equal
+            // digits instead of one per lane keeps such waves from serialising on a single LDS address.
             const int64_t i = base + q * kPartThreads + threadIdx.x;
-            if (i < hi) atomicAdd(&lh[pol.digit(k[q])], 1u);
+            const bool valid = i < hi;
+            const uint32_t d = valid ? pol.digit(k[q]) : 0xFFFFFFFFu;
+            const uint32_t dprev = __shfl_up(d, 1, kWave);
+            const bool head = valid && (lane == 0 || d != dprev);
+            const uint64_t heads = __ballot(head);
+            const int num_valid = __popcll(__ballot(valid));
+            if (head) {
+                const uint64_t above = lane == kWave - 1 ? 0ull : (heads >> (lane + 1));
+                const int run = above ? __builtin_ctzll(above) + 1 : num_valid - lane;
+                atomicAdd(&lh[d], static_cast<uint32_t>(run));
+            }
         }
     }
     __syncthreads();
@@ -274,7 +288,7 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
             const uint32_t in_bin = cnt[w * bins + d[i]] + r[i];
             r[i] = binstart[d[i]] + in_bin;  // position inside the reordered tile
-            if (idx < tile_count) pol.placed(tile_base + idx, gofs[d[i]] + in_bin);
+            if (idx < tile_count && gofs[d[i]] + in_bin < static_cast<uint32_t>(n)) pol.placed(tile_base + idx, gofs[d[i]] + in_bin);
         }
         lds_barrier();  // the counters are dead from here on: their storage becomes the staging area
 #pragma unroll
@@ -290,7 +304,8 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
         for (int p = tid; p < tile_count; p += kPartThreads) {
             const KeyT key = skey[p];
             const uint32_t dd = P::kStageDigit ? static_cast<uint32_t>(sdig[p]) : pol.digit(key);
-            pol.store(gofs[dd] + (static_cast<uint32_t>(p) - binstart[dd]), key, sval[p]);
+            const uint32_t dst = gofs[dd] + (static_cast<uint32_t>(p) - binstart[dd]);
+            if (dst < static_cast<uint32_t>(n)) pol.store(dst, key, sval[p]);  // always true; keeps a broken histogram from writing out of bounds
         }
         lds_barrier();
         for (int b = b0; b < b1; ++b) gofs[b] += btot[b];
