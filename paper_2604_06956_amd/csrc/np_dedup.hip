@@ -95,7 +95,24 @@ dedup_count_heads_kernel(const K* __restrict__ sorted, int n, int chunk_items, i
     int64_t hi = lo + chunk_items;
     if (hi > n) hi = n;
     int cnt = 0;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kHeadThreads) cnt += (i == 0 || sorted[i] != sorted[i - 1]) ? 1 : 0;
+    for (int64_t base = lo; base < hi; base += static_cast<int64_t>(kHeadThreads) * 8) {
+        K cur[8], prv[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {  // sixteen independent loads in flight per thread
+            const int64_t i = base + q * kHeadThreads + threadIdx.x;
+            cur[q] = K(0);
+            prv[q] = K(0);
+            if (i < hi) {
+                cur[q] = sorted[i];
+                if (i > 0) prv[q] = sorted[i - 1];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int64_t i = base + q * kHeadThreads + threadIdx.x;
+            if (i < hi) cnt += (i == 0 || cur[q] != prv[q]) ? 1 : 0;
+        }
+    }
 #pragma unroll
     for (int d = kWave / 2; d > 0; d >>= 1) cnt += __shfl_xor(cnt, d, kWave);
     if (__lane_id() == 0) wsum[threadIdx.x / kWave] = cnt;

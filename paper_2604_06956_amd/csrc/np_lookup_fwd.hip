@@ -145,6 +145,76 @@ fwd_seq_kernel(const float* __restrict__ table, int dim, const int64_t* __restri
     }
 }
 
+// Sequence output in bf16 for rows whose width is a multiple of 8: a lane owns 8 consecutive floats (two
+// 16-byte loads) and writes them as 8 bf16 with one 16-byte store, so loads and stores are both full width.
+// L8 lanes share a row (dim / 8 rounded up to a power of two, at most 64), NV8 chunks of 8 floats per lane.
+template <int L8, int NV8>
+__global__ void __launch_bounds__(256)
+fwd_seq_bf16x8_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx,
+                      const int32_t* __restrict__ bag_offsets, int num_bags, int max_len, uint16_t* __restrict__ out) {
+    constexpr int GPB = 256 / L8;
+    const int r = threadIdx.x % L8;
+    const int64_t total = static_cast<int64_t>(num_bags) * max_len;
+    const int64_t q0 = (static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / L8) * kSeqPerGroup;
+    const int chunks = dim / 8;
+    const float4* src[kSeqPerGroup];
+#pragma unroll
+    for (int k = 0; k < kSeqPerGroup; ++k) {
+        const int64_t q = q0 + k;
+        src[k] = nullptr;
+        if (q < total) {
+            const int b = static_cast<int>(static_cast<uint32_t>(q) / static_cast<uint32_t>(max_len));  // total < 2^31
+            const int p = static_cast<int>(q - static_cast<int64_t>(b) * max_len);
+            const int lo = bag_offsets[b];
+            if (p < bag_offsets[b + 1] - lo) {
+                const int j = lo + p;
+                src[k] = reinterpret_cast<const float4*>(table + static_cast<size_t>(list_keys[idx ? idx[j] : j]) * dim);
+            }
+        }
+    }
+    float4 x[kSeqPerGroup][NV8][2];
+#pragma unroll
+    for (int k = 0; k < kSeqPerGroup; ++k) {
+#pragma unroll
+        for (int v = 0; v < NV8; ++v) {
+            const int c = r + v * L8;
+            const bool on = src[k] && c < chunks;
+            x[k][v][0] = on ? src[k][2 * c] : make_float4(0.f, 0.f, 0.f, 0.f);
+            x[k][v][1] = on ? src[k][2 * c + 1] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kSeqPerGroup; ++k) {
+        const int64_t q = q0 + k;
+        if (q < total) {
+#pragma unroll
+            for (int v = 0; v < NV8; ++v) {
+                const int c = r + v * L8;
+                if (c < chunks) {
+                    const float4 a = x[k][v][0], b = x[k][v][1];
+                    uint4 o;
+                    o.x = static_cast<uint32_t>(f32_to_bf16(a.x)) | (static_cast<uint32_t>(f32_to_bf16(a.y)) << 16);
+                    o.y = static_cast<uint32_t>(f32_to_bf16(a.z)) | (static_cast<uint32_t>(f32_to_bf16(a.w)) << 16);
+                    o.z = static_cast<uint32_t>(f32_to_bf16(b.x)) | (static_cast<uint32_t>(f32_to_bf16(b.y)) << 16);
+                    o.w = static_cast<uint32_t>(f32_to_bf16(b.z)) | (static_cast<uint32_t>(f32_to_bf16(b.w)) << 16);
+                    *reinterpret_cast<uint4*>(out + static_cast<size_t>(q) * dim + c * 8) = o;
+                }
+            }
+        }
+    }
+}
+
+template <int L8, int NV8>
+void fwd_seq_bf16x8_launch(const float* table, int dim, const int64_t* list_keys, const int32_t* idx, const int32_t* bag_offsets,
+                           int num_bags, int max_len, uint16_t* out, hipStream_t stream) {
+    constexpr int GPB = 256 / L8;
+    const int64_t total = static_cast<int64_t>(num_bags) * max_len;
+    const int64_t per_block = static_cast<int64_t>(GPB) * kSeqPerGroup;
+    const unsigned grid = static_cast<unsigned>((total + per_block - 1) / per_block);
+    NP_LAUNCH("fwd_seq", (fwd_seq_bf16x8_kernel<L8, NV8>), dim3(grid), dim3(256), 0, stream, table, dim, list_keys, idx, bag_offsets,
+              num_bags, max_len, out);
+}
+
 template <int LPR, int NV>
 __global__ void __launch_bounds__(256)
 fwd_rows_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys,
@@ -244,6 +314,19 @@ int np_lookup_fwd(const float* table, int64_t num_rows, int32_t dim, const int64
     np::FwdArgs a{table, dim, list_keys, d_num_list, cap, idx, bag_offsets, num_bags, mode, max_len, out_dtype, out, rows_out,
                   static_cast<hipStream_t>(stream)};
     const int words = dim / 4;
+    if (mode == NP_SEQ && out_dtype == NP_BF16 && dim % 8 == 0 && num_bags > 0 && np::aligned(out, 16)) {
+        // full-width route for bf16 sequences; the optional rows_out copy still goes through the generic launcher
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        uint16_t* o = static_cast<uint16_t*>(out);
+        const int chunks = dim / 8;
+        if (chunks <= 4) np::fwd_seq_bf16x8_launch<4, 1>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        else if (chunks <= 8) np::fwd_seq_bf16x8_launch<8, 1>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        else if (chunks <= 16) np::fwd_seq_bf16x8_launch<16, 1>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        else if (chunks <= 32) np::fwd_seq_bf16x8_launch<32, 1>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        else if (chunks <= 64) np::fwd_seq_bf16x8_launch<64, 1>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        else np::fwd_seq_bf16x8_launch<64, 2>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        a.num_bags = 0;  // pooled / sequence part done; what remains for the generic launcher is rows_out
+    }
     if (words <= 4) np::fwd_launch<4, 1>(a);
     else if (words <= 8) np::fwd_launch<8, 1>(a);
     else if (words <= 16) np::fwd_launch<16, 1>(a);
