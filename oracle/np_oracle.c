@@ -197,22 +197,22 @@ int np_ref_lookup_fwd(const float* table, int64_t num_rows, int32_t dim, const i
     if (mode == REF_SEQ && max_len < 1) return -1;
     double* acc = (double*)malloc(sizeof(double) * (size_t)dim);
     double* aab = (double*)malloc(sizeof(double) * (size_t)dim);
-    if (!acc || !aab) return -2;
+    if (!acc || !aab) { free(acc); free(aab); return -2; }
     size_t per_bag = (mode == REF_SEQ) ? (size_t)max_len * (size_t)dim : (size_t)dim;
     for (int32_t b = 0; b < num_bags; ++b) {
         int32_t lo = bag_offsets[b], hi = bag_offsets[b + 1];
         int32_t len = hi - lo;
         if (mode == REF_SEQ) {
-            if (len > max_len) return -3;
+            if (len > max_len) { free(acc); free(aab); return -3; }
             for (int32_t p = 0; p < max_len; ++p) {
                 for (int32_t d = 0; d < dim; ++d) {
                     double v = 0.0;
                     if (p < len) {
                         int32_t j = lo + p;
                         int32_t slot = idx ? idx[j] : j;
-                        if (slot < 0 || slot >= num_list) return -3;
+                        if (slot < 0 || slot >= num_list) { free(acc); free(aab); return -3; }
                         int64_t row = list_keys[slot];
-                        if (row < 0 || row >= num_rows) return -3;
+                        if (row < 0 || row >= num_rows) { free(acc); free(aab); return -3; }
                         v = (double)table[(size_t)row * (size_t)dim + (size_t)d];
                     }
                     size_t o = (size_t)b * per_bag + (size_t)p * (size_t)dim + (size_t)d;
@@ -228,9 +228,9 @@ int np_ref_lookup_fwd(const float* table, int64_t num_rows, int32_t dim, const i
         for (int32_t d = 0; d < dim; ++d) acc[d] = aab[d] = 0.0;
         for (int32_t j = lo; j < hi; ++j) {
             int32_t slot = idx ? idx[j] : j;
-            if (slot < 0 || slot >= num_list) return -3;
+            if (slot < 0 || slot >= num_list) { free(acc); free(aab); return -3; }
             int64_t row = list_keys[slot];
-            if (row < 0 || row >= num_rows) return -3;
+            if (row < 0 || row >= num_rows) { free(acc); free(aab); return -3; }
             for (int32_t d = 0; d < dim; ++d) {
                 double v = (double)table[(size_t)row * (size_t)dim + (size_t)d];
                 acc[d] += v;
@@ -254,7 +254,7 @@ int np_ref_lookup_fwd(const float* table, int64_t num_rows, int32_t dim, const i
     if (rows_out) {
         for (int32_t p = 0; p < num_list; ++p) {
             int64_t row = list_keys[p];
-            if (row < 0 || row >= num_rows) return -3;
+            if (row < 0 || row >= num_rows) { free(acc); free(aab); return -3; }
             memcpy(rows_out + (size_t)p * (size_t)dim, table + (size_t)row * (size_t)dim, sizeof(float) * (size_t)dim);
         }
     }
@@ -292,7 +292,7 @@ int np_ref_lookup_bwd(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mod
         double w = (mode == REF_POOL_MEAN && len > 0) ? 1.0 / (double)len : 1.0;
         for (int32_t j = lo; j < hi; ++j) {
             int32_t u = inverse[j];
-            if (u < 0 || u >= num_unique) return -3;
+            if (u < 0 || u >= num_unique) { free(acc); return -3; }
             size_t dst = (size_t)(unique_to_send ? unique_to_send[u] : u) * (size_t)dim;
             size_t src = (mode == REF_SEQ) ? ((size_t)b * (size_t)max_len + (size_t)(j - lo)) * (size_t)dim
                                            : (size_t)b * (size_t)dim;

@@ -38,6 +38,13 @@ def build(force: bool = False, sanitize: bool = False) -> str:
     return out
 
 
+def build_selftest(out: Optional[str] = None) -> str:
+    """Compile the stand-alone self-check (oracle/selftest.c + np_oracle.c); the tests build it with sanitizers."""
+    out = out or os.path.join(_HERE, "selftest.bin")
+    subprocess.run(["gcc", "-std=c11", "-O1", "-Wall", "-o", out, _SRC, os.path.join(_HERE, "selftest.c"), "-lm"], check=True)
+    return out
+
+
 def _load():
     global _lib
     if _lib is None:

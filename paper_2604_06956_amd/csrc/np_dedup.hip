@@ -304,6 +304,7 @@ int np_dedup(const int64_t* keys, int32_t n, int32_t key_bits, int64_t* unique, 
         return np::launch_status();
     }
     if (!keys || !unique || !inverse || !counts || !occ) return NP_ERR_INVALID_ARG;
+    if (n > INT32_MAX - (1 << 20)) return NP_ERR_UNSUPPORTED;  // tile-rounded indices must stay below 2^31
     if (!np::aligned(keys, 8) || !np::aligned(unique, 8) || !np::aligned(inverse, 4) || !np::aligned(counts, 4) ||
         !np::aligned(occ_offsets, 4) || !np::aligned(occ, 4))
         return NP_ERR_INVALID_ARG;

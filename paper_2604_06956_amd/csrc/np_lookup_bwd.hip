@@ -647,6 +647,7 @@ int np_lookup_bwd(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, i
     if (dim < 4 || dim % 4 != 0 || dim > NP_MAX_DIM) return NP_ERR_UNSUPPORTED;
     if (mode == NP_SEQ && static_cast<int64_t>(num_bags) * max_len > INT32_MAX) return NP_ERR_UNSUPPORTED;
     if (n == 0) return NP_OK;  // no lookups: no key receives a gradient, nothing to write
+    if (n > INT32_MAX - (1 << 20)) return NP_ERR_UNSUPPORTED;  // tile-rounded positions must stay below 2^31
     if (!dY || !bag_offsets || !occ_offsets || !occ || !grads || num_bags < 1) return NP_ERR_INVALID_ARG;
     if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(grads, 16)) return NP_ERR_INVALID_ARG;
     if (!ws || !np::aligned(ws, 256) || ws_bytes < np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode)) return NP_ERR_WORKSPACE;
@@ -674,6 +675,7 @@ int np_lookup_bwd_adagrad(const void* dY, int32_t dy_dtype, int32_t dim, int32_t
     if (dim < 4 || dim % 4 != 0 || dim > 256) return NP_ERR_UNSUPPORTED;  // a row must fit one wave of float4 words
     if (mode == NP_SEQ && static_cast<int64_t>(num_bags) * max_len > INT32_MAX) return NP_ERR_UNSUPPORTED;
     if (n == 0) return NP_OK;
+    if (n > INT32_MAX - (1 << 20)) return NP_ERR_UNSUPPORTED;
     if (!dY || !bag_offsets || !occ_offsets || !occ || !unique || num_bags < 1) return NP_ERR_INVALID_ARG;
     if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(table, 16)) return NP_ERR_INVALID_ARG;
     if (!ws || !np::aligned(ws, 256) || ws_bytes < np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode)) return NP_ERR_WORKSPACE;

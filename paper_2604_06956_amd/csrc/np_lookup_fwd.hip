@@ -97,7 +97,10 @@ fwd_pool_kernel(const float* __restrict__ table, int dim, const int64_t* __restr
     }
 }
 
-constexpr int kSeqPerGroup = 4;  // output positions per group, their slot -> key -> row chains in flight together
+#ifndef NP_SEQ_PER_GROUP
+#define NP_SEQ_PER_GROUP 4
+#endif
+constexpr int kSeqPerGroup = NP_SEQ_PER_GROUP;  // output positions per group, their slot -> key -> row chains in flight together
 
 template <int LPR, int NV, typename OutT>
 __global__ void __launch_bounds__(256)
