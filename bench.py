@@ -125,15 +125,27 @@ def main() -> int:
     ws_r = torch.empty(max(B.np_route_workspace_bytes(cap, S), 256), dtype=torch.uint8, device=dev)
     ws_b = torch.empty(max(B.np_lookup_bwd_workspace_bytes(cfg.num_bags, n_max, D, cfg.mode), 256), dtype=torch.uint8, device=dev)
 
+    # np_route needs only np_dedup's output and nothing before np_lookup_bwd needs np_route's, so it runs on a second
+    # stream (default priority) beside np_lookup_fwd; events order the two streams around it
+    main_stream = torch.cuda.current_stream()
+    side_stream = torch.cuda.Stream()
+    ev_dedup = torch.cuda.Event()
+    ev_route = torch.cuda.Event()
+
     def step(i: int) -> None:
         bt = dbatch[i % 2]
         n = bt["n"]
         B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
-        B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
+        ev_dedup.record(main_stream)
+        side_stream.wait_event(ev_dedup)
+        with torch.cuda.stream(side_stream):
+            B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
+            ev_route.record(side_stream)
         # the table is local, so the forward reads it through the requester-side list (unique keys, inverse map);
         # gradients are produced in send order and applied with the send-ordered keys
         B.np_lookup_fwd(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
                         num_list=dd["num_unique"], cap=cap, out=out)
+        main_stream.wait_event(ev_route)
         B.np_lookup_bwd(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
                         unique_to_send=rr["unique_to_send"], grads=grads, ws=ws_b)
         B.np_sparse_adagrad(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
@@ -316,6 +328,7 @@ def main() -> int:
                       "algorithmic_GBps": alg[c] / (call_ms[c] * 1e-3) / 1e9 if call_ms.get(c, 0.0) > 0 else None}
                   for c in alg},
         "kernels": kernels,
+        "streams": "np_route runs on a second stream beside np_lookup_fwd; its event times include that sharing",
         "fused_bwd_update_step": fused,
         "dual_buffer_sync": dbsync,
         "frozen_window_dedup": fwp,
