@@ -27,7 +27,7 @@ adagrad_kernel(float* __restrict__ table, float* __restrict__ state, int dim, co
             g[v] = make_float4(0.f, 0.f, 0.f, 0.f);
             w[v] = g[v];
             if (wv < words) {
-                g[v] = gsrc[wv];
+                g[v] = load_stream(gsrc + wv);
                 w[v] = wrow[wv];
             }
             ss += sumsq4(g[v]);
@@ -43,7 +43,7 @@ adagrad_kernel(float* __restrict__ table, float* __restrict__ state, int dim, co
             const int wv = r + v * LPR;
             if (wv < words) {
                 adagrad_step4(w[v], g[v], lr, denom);
-                wrow[wv] = w[v];
+                store_stream(wrow + wv, w[v]);
             }
         }
     }

@@ -129,6 +129,62 @@ __device__ __forceinline__ int block_excl_scan(int v, int* smem, int* total) {
     return base + inc - v;
 }
 
+// Accesses to data that is touched once per launch (index streams, output rows): marked non-temporal so that
+// they leave L2 first and the rows that are gathered again and again stay.  Only for whole rows and coalesced
+// streams: scattered 4- and 8-byte stores rely on L2 to merge partial lines and get much slower with the hint.
+#ifndef NP_STREAM_HINTS
+#define NP_STREAM_HINTS 1
+#endif
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void store_stream(float4* p, const float4& a) {
+#if NP_STREAM_HINTS
+    f32x4_t v = {a.x, a.y, a.z, a.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(p));
+#else
+    *p = a;
+#endif
+}
+
+__device__ __forceinline__ void store_stream(uint2* p, const uint2& a) {
+#if NP_STREAM_HINTS
+    u32x2_t v = {a.x, a.y};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x2_t*>(p));
+#else
+    *p = a;
+#endif
+}
+
+__device__ __forceinline__ float4 load_stream(const float4* p) {
+#if NP_STREAM_HINTS
+    const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+#else
+    return *p;
+#endif
+}
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void store_stream(uint4* p, const uint4& a) {
+#if NP_STREAM_HINTS
+    u32x4_t v = {a.x, a.y, a.z, a.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(p));
+#else
+    *p = a;
+#endif
+}
+
+template <typename T>
+__device__ __forceinline__ T load_stream(const T* p) {
+#if NP_STREAM_HINTS
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+
 // fp32 -> bf16, round to nearest even; NaN becomes a quiet NaN.
 __device__ __forceinline__ uint16_t f32_to_bf16(float x) {
     uint32_t b = __float_as_uint(x);

@@ -196,7 +196,7 @@ dedup_emit_kernel(const K* __restrict__ sorted, const int32_t* __restrict__ occ,
                     unique[u] = static_cast<int64_t>(k[i]);
                     occ_offsets[u] = static_cast<int32_t>(p);
                 }
-                inverse[occ[p]] = u;
+                inverse[occ[p]] = u;  // a plain store: L2 merges the partial lines (a non-temporal one doubles the kernel's time)
             }
         }
         running += total;

@@ -168,7 +168,7 @@ struct RowSink {
 template <int LPR, bool FUSED>
 __device__ __forceinline__ void sink_row(const RowSink& sk, int dst, int dim, int r, int words, const float4& g) {
     if (!FUSED) {
-        if (r < words) reinterpret_cast<float4*>(sk.grads + static_cast<size_t>(dst) * dim)[r] = g;
+        if (r < words) store_stream(reinterpret_cast<float4*>(sk.grads + static_cast<size_t>(dst) * dim) + r, g);
         return;
     }
     const int64_t key = sk.keys[dst];
@@ -240,7 +240,7 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     const int wv_id = t / kWave;
 
     // loads that depend on nothing but the tile go out first
-    const int j = valid ? occ[i] : 0;
+    const int j = valid ? load_stream(occ + i) : 0;
     const int cand = u0 + 1 + t;
     const int rel = cand <= U ? occ_offsets[cand] - tile_start : INT32_MAX;  // >= 1
     const int seg0_start = occ_offsets[u0];
@@ -330,7 +330,7 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
 #pragma unroll
                             for (int v = 0; v < NV; ++v) {
                                 const int wv = r + v * LPR;
-                                if (wv < words) reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dk) * dim)[wv] = acc[v];
+                                if (wv < words) store_stream(reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dk) * dim) + wv, acc[v]);
                             }
                         }
                     } else {
@@ -387,7 +387,7 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                 if (l_closed[gg]) {
                     if (started_here) {
                         if (FUSED) sink_row<LPR, FUSED>(sink, l_dst[gg], dim, t, words, carry);  // ROWW == LPR here
-                        else if (t < words) reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(l_dst[gg]) * dim)[t] = carry;
+                        else if (t < words) store_stream(reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(l_dst[gg]) * dim) + t, carry);
                     } else if (t < words) {
                         reinterpret_cast<float4*>(tile_left + static_cast<size_t>(tile) * dim)[t] = carry;
                     }
@@ -461,7 +461,7 @@ bwd_fixup_short_kernel(int dim, int num_tiles, const int32_t* __restrict__ occ_o
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int wv = r + v * LPR;
-            if (wv < words) reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dst) * dim)[wv] = acc[v];
+            if (wv < words) store_stream(reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dst) * dim) + wv, acc[v]);
         }
     }
 }
@@ -531,7 +531,7 @@ bwd_fixup_long_kernel(int dim, const int32_t* __restrict__ occ_offsets, const in
             }
             const int dst = unique_to_send ? unique_to_send[seg] : seg;
             if (FUSED) sink_row<LPR, FUSED>(sink, dst, dim, t, words, s);
-            else if (t < words) reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dst) * dim)[t] = s;
+            else if (t < words) store_stream(reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dst) * dim) + t, s);
         }
     }
 }

@@ -18,13 +18,13 @@ __device__ __forceinline__ int64_t group_bcast64(int64_t v, int src_in_group) {
     return (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
 }
 
-__device__ __forceinline__ void store_words(float* p, const float4& a) { *reinterpret_cast<float4*>(p) = a; }
+__device__ __forceinline__ void store_words(float* p, const float4& a) { store_stream(reinterpret_cast<float4*>(p), a); }
 
 __device__ __forceinline__ void store_words(uint16_t* p, const float4& a) {
     uint2 o;
     o.x = static_cast<uint32_t>(f32_to_bf16(a.x)) | (static_cast<uint32_t>(f32_to_bf16(a.y)) << 16);
     o.y = static_cast<uint32_t>(f32_to_bf16(a.z)) | (static_cast<uint32_t>(f32_to_bf16(a.w)) << 16);
-    *reinterpret_cast<uint2*>(p) = o;
+    store_stream(reinterpret_cast<uint2*>(p), o);
 }
 
 constexpr int kFwdUnroll = 4;
@@ -49,7 +49,7 @@ fwd_pool_kernel(const float* __restrict__ table, int dim, const int64_t* __restr
         // one lane per lookup: slot, key and the byte offset of the row (the 64-bit multiply happens here, once
         // per lookup, instead of in every lane of the walk below)
         int64_t row_off = 0;
-        if (j < hi) row_off = list_keys[idx ? idx[j] : j] * static_cast<int64_t>(dim) * static_cast<int64_t>(sizeof(float));
+        if (j < hi) row_off = list_keys[idx ? load_stream(idx + j) : j] * static_cast<int64_t>(dim) * static_cast<int64_t>(sizeof(float));
         const int off_lo = static_cast<int>(row_off & 0xFFFFFFFFll), off_hi = static_cast<int>(row_off >> 32);
         const int cnt = hi - base < LPR ? hi - base : LPR;
         for (int k0 = 0; k0 < cnt; k0 += kFwdUnroll) {
@@ -122,7 +122,7 @@ fwd_seq_kernel(const float* __restrict__ table, int dim, const int64_t* __restri
             const int lo = bag_offsets[b];
             if (p < bag_offsets[b + 1] - lo) {
                 const int j = lo + p;
-                src[k] = reinterpret_cast<const float4*>(table + static_cast<size_t>(list_keys[idx ? idx[j] : j]) * dim);
+                src[k] = reinterpret_cast<const float4*>(table + static_cast<size_t>(list_keys[idx ? load_stream(idx + j) : j]) * dim);
             }
         }
     }
@@ -156,28 +156,42 @@ __global__ void __launch_bounds__(256)
 fwd_seq_bf16x8_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx,
                       const int32_t* __restrict__ bag_offsets, int num_bags, int max_len, uint16_t* __restrict__ out) {
     constexpr int GPB = 256 / L8;
+    constexpr int SPG = kSeqPerGroup < L8 ? kSeqPerGroup : L8;  // positions per group; at most 64 per wave
     const int r = threadIdx.x % L8;
     const int64_t total = static_cast<int64_t>(num_bags) * max_len;
-    const int64_t q0 = (static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / L8) * kSeqPerGroup;
+    const int64_t q0 = (static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / L8) * SPG;
     const int chunks = dim / 8;
-    const float4* src[kSeqPerGroup];
-#pragma unroll
-    for (int k = 0; k < kSeqPerGroup; ++k) {
-        const int64_t q = q0 + k;
-        src[k] = nullptr;
-        if (q < total) {
-            const int b = static_cast<int>(static_cast<uint32_t>(q) / static_cast<uint32_t>(max_len));  // total < 2^31
-            const int p = static_cast<int>(q - static_cast<int64_t>(b) * max_len);
-            const int lo = bag_offsets[b];
-            if (p < bag_offsets[b + 1] - lo) {
-                const int j = lo + p;
-                src[k] = reinterpret_cast<const float4*>(table + static_cast<size_t>(list_keys[idx ? idx[j] : j]) * dim);
-            }
+    // The position -> bag -> slot -> key chain runs once per output position, on one lane each: lane l of the wave
+    // resolves the wave's l-th position, the groups then pick their row offsets up by shuffle.
+    constexpr int PW = (kWave / L8) * SPG;  // positions per wave, <= 64
+    static_assert(PW <= kWave, "one lane per position");
+    const int lane = __lane_id();
+    const int64_t wq0 = (static_cast<int64_t>(blockIdx.x) * GPB + (threadIdx.x / kWave) * (kWave / L8)) * SPG;
+    int64_t my_off = -1;  // byte offset of the row of position wq0 + lane; -1: padding or past the end
+    if (lane < PW && wq0 + lane < total) {
+        const int64_t q = wq0 + lane;
+        const int b = static_cast<int>(static_cast<uint32_t>(q) / static_cast<uint32_t>(max_len));  // total < 2^31
+        const int p = static_cast<int>(q - static_cast<int64_t>(b) * max_len);
+        const int lo = bag_offsets[b];
+        if (p < bag_offsets[b + 1] - lo) {
+            const int j = lo + p;
+            my_off = list_keys[idx ? load_stream(idx + j) : j] * static_cast<int64_t>(dim) * static_cast<int64_t>(sizeof(float));
         }
     }
-    float4 x[kSeqPerGroup][NV8][2];
+    const int off_lo = static_cast<int>(my_off & 0xFFFFFFFFll), off_hi = static_cast<int>(my_off >> 32);
+    const float4* src[SPG];
 #pragma unroll
-    for (int k = 0; k < kSeqPerGroup; ++k) {
+    for (int k = 0; k < SPG; ++k) {
+        const int from = (lane / L8) * SPG + k;
+        const uint32_t lo32 = static_cast<uint32_t>(__shfl(off_lo, from, kWave));
+        const int32_t hi32 = __shfl(off_hi, from, kWave);
+        src[k] = hi32 < 0 ? nullptr
+                          : reinterpret_cast<const float4*>(reinterpret_cast<const char*>(table) +
+                                                            ((static_cast<uint64_t>(static_cast<uint32_t>(hi32)) << 32) | lo32));
+    }
+    float4 x[SPG][NV8][2];
+#pragma unroll
+    for (int k = 0; k < SPG; ++k) {
 #pragma unroll
         for (int v = 0; v < NV8; ++v) {
             const int c = r + v * L8;
@@ -187,7 +201,7 @@ fwd_seq_bf16x8_kernel(const float* __restrict__ table, int dim, const int64_t* _
         }
     }
 #pragma unroll
-    for (int k = 0; k < kSeqPerGroup; ++k) {
+    for (int k = 0; k < SPG; ++k) {
         const int64_t q = q0 + k;
         if (q < total) {
 #pragma unroll
@@ -200,7 +214,7 @@ fwd_seq_bf16x8_kernel(const float* __restrict__ table, int dim, const int64_t* _
                     o.y = static_cast<uint32_t>(f32_to_bf16(a.z)) | (static_cast<uint32_t>(f32_to_bf16(a.w)) << 16);
                     o.z = static_cast<uint32_t>(f32_to_bf16(b.x)) | (static_cast<uint32_t>(f32_to_bf16(b.y)) << 16);
                     o.w = static_cast<uint32_t>(f32_to_bf16(b.z)) | (static_cast<uint32_t>(f32_to_bf16(b.w)) << 16);
-                    *reinterpret_cast<uint4*>(out + static_cast<size_t>(q) * dim + c * 8) = o;
+                    store_stream(reinterpret_cast<uint4*>(out + static_cast<size_t>(q) * dim + c * 8), o);
                 }
             }
         }
@@ -211,8 +225,9 @@ template <int L8, int NV8>
 void fwd_seq_bf16x8_launch(const float* table, int dim, const int64_t* list_keys, const int32_t* idx, const int32_t* bag_offsets,
                            int num_bags, int max_len, uint16_t* out, hipStream_t stream) {
     constexpr int GPB = 256 / L8;
+    constexpr int SPG = kSeqPerGroup < L8 ? kSeqPerGroup : L8;
     const int64_t total = static_cast<int64_t>(num_bags) * max_len;
-    const int64_t per_block = static_cast<int64_t>(GPB) * kSeqPerGroup;
+    const int64_t per_block = static_cast<int64_t>(GPB) * SPG;
     const unsigned grid = static_cast<unsigned>((total + per_block - 1) / per_block);
     NP_LAUNCH("fwd_seq", (fwd_seq_bf16x8_kernel<L8, NV8>), dim3(grid), dim3(256), 0, stream, table, dim, list_keys, idx, bag_offsets,
               num_bags, max_len, out);
@@ -231,7 +246,7 @@ fwd_rows_kernel(const float* __restrict__ table, int dim, const int64_t* __restr
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int wv = r + v * LPR;
-            if (wv < words) *reinterpret_cast<float4*>(rows_out + static_cast<size_t>(p) * dim + wv * 4) = src[wv];
+            if (wv < words) store_stream(reinterpret_cast<float4*>(rows_out + static_cast<size_t>(p) * dim + wv * 4), src[wv]);
         }
     }
 }
