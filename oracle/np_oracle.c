@@ -24,7 +24,9 @@
  *     and eps outside the square root (the paper's Eq. (2) is plain SGD; the benchmark
  *     definition asks for row-wise Adagrad);
  *   - an empty bag pools to zeros and sends no gradient;
- *   - sequence output is bf16 (round to nearest even), zero padded to max_len.
+ *   - sequence output is bf16 (round to nearest even), zero padded to max_len;
+ *   - a table kept in bf16 is read exactly (every bf16 value is an fp32 value) and an updated row is the
+ *     fp64 result rounded once to bf16, nearest, ties to even (no stochastic rounding, no fp32 shadow copy).
  *
  * All functions return 0 on success, a negative value on a bad argument.
  */
@@ -58,6 +60,28 @@ float np_ref_bf16_to_f32(uint16_t h) {
     float x;
     memcpy(&x, &b, 4);
     return x;
+}
+
+/*
+ * Round an fp64 value to bf16 in one step, nearest, ties to even (going through fp32 first would round twice).
+ * bf16 has 8 significant bits, exponents like fp32, subnormals that are multiples of 2^-133.
+ */
+uint16_t np_ref_f64_to_bf16(double x) {
+    if (isnan(x)) return 0x7FC0u;
+    uint16_t sign = signbit(x) ? 0x8000u : 0u;
+    double a = fabs(x);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return (uint16_t)(sign | 0x7F80u);
+    int e;
+    (void)frexp(a, &e);           /* a = m * 2^e with m in [0.5, 1) */
+    int q = e - 8;                /* keep 8 significant bits: the result is an integer times 2^q */
+    if (q < -133) q = -133;       /* subnormal range: fixed spacing */
+    double r = ldexp(rint(ldexp(a, -q)), q); /* rint: the default rounding mode is nearest-even; both scalings are exact */
+    if (r >= ldexp(1.0, 128)) return (uint16_t)(sign | 0x7F80u);
+    float f = (float)r;           /* exact: r has at most 8 significant bits in fp32's range */
+    uint32_t b;
+    memcpy(&b, &f, 4);
+    return (uint16_t)(sign | (uint16_t)(b >> 16));
 }
 
 /* ---------------------------------------------------------------- step 1: dedup ---- */
@@ -334,6 +358,29 @@ int np_ref_sparse_adagrad(float* table, float* state, int64_t num_rows, int32_t 
         double denom = sqrt(G) + (double)eps;
         float* w = table + (size_t)k * (size_t)dim;
         for (int32_t d = 0; d < dim; ++d) w[d] = (float)((double)w[d] - (double)lr * (double)g[d] / denom);
+    }
+    return 0;
+}
+
+/*
+ * The same update on a table stored in bf16 (bit patterns, [num_rows, dim]); the state stays fp32.  The old row is
+ * widened exactly, the step is taken in fp64 with the fp64 state sum, and the new row is rounded once to bf16.
+ */
+int np_ref_sparse_adagrad_bf16(uint16_t* table, float* state, int64_t num_rows, int32_t dim, const int64_t* list_keys,
+                               const float* grads, int32_t num_list, float lr, float eps) {
+    if (!table || !state || dim < 1 || num_list < 0) return -1;
+    for (int32_t p = 0; p < num_list; ++p) {
+        int64_t k = list_keys[p];
+        if (k < 0 || k >= num_rows) return -3;
+        const float* g = grads + (size_t)p * (size_t)dim;
+        double ss = 0.0;
+        for (int32_t d = 0; d < dim; ++d) ss += (double)g[d] * (double)g[d];
+        double G = (double)state[k] + ss / (double)dim;
+        state[k] = (float)G;
+        double denom = sqrt(G) + (double)eps;
+        uint16_t* w = table + (size_t)k * (size_t)dim;
+        for (int32_t d = 0; d < dim; ++d)
+            w[d] = np_ref_f64_to_bf16((double)np_ref_bf16_to_f32(w[d]) - (double)lr * (double)g[d] / denom);
     }
     return 0;
 }

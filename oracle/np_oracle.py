@@ -57,8 +57,10 @@ def _load():
         _lib.np_ref_f32_to_bf16.argtypes = [ctypes.c_float]
         _lib.np_ref_bf16_to_f32.restype = ctypes.c_float
         _lib.np_ref_bf16_to_f32.argtypes = [ctypes.c_uint16]
+        _lib.np_ref_f64_to_bf16.restype = ctypes.c_uint16
+        _lib.np_ref_f64_to_bf16.argtypes = [ctypes.c_double]
         for name in ("np_ref_dedup", "np_ref_route", "np_ref_compose", "np_ref_lookup_fwd", "np_ref_lookup_bwd",
-                     "np_ref_sparse_adagrad", "np_ref_intersect", "np_ref_sync_rows"):
+                     "np_ref_sparse_adagrad", "np_ref_sparse_adagrad_bf16", "np_ref_intersect", "np_ref_sync_rows"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -85,6 +87,10 @@ def mix(k: int) -> int:
 
 def shard(key: int, num_shards: int, shard_fn: int) -> int:
     return int(_load().np_ref_shard(int(key), int(num_shards), int(shard_fn)))
+
+
+def f64_to_bf16(x: float) -> int:
+    return int(_load().np_ref_f64_to_bf16(ctypes.c_double(x)))
 
 
 def f32_to_bf16(x: float) -> int:
@@ -138,7 +144,12 @@ def compose(inverse, unique_to_send) -> np.ndarray:
 
 def lookup_fwd(table, list_keys, idx, bag_offsets, mode: int, max_len: int = 1, out_dtype: int = F32,
                want_rows: bool = False, want_abs: bool = False):
-    """-> out (fp32 array, or uint16 array of bf16 bit patterns), rows_out or None, abs_out or None."""
+    """-> out (fp32 array, or uint16 array of bf16 bit patterns), rows_out or None, abs_out or None.
+
+    ``table`` is fp32, or uint16 bf16 bit patterns (widened exactly before use; rows_out then holds the widened rows).
+    """
+    if isinstance(table, np.ndarray) and table.dtype == np.uint16:
+        table = bf16_bits_to_f32(table)
     table = _as(table, np.float32)
     R, D = table.shape
     list_keys = _as(list_keys, np.int64)
@@ -188,6 +199,19 @@ def sparse_adagrad(table: np.ndarray, state: np.ndarray, list_keys, grads, lr: f
                                        _p(grads), ctypes.c_int32(list_keys.shape[0]), ctypes.c_float(lr),
                                        ctypes.c_float(eps))
     _chk(rc, "sparse_adagrad")
+
+
+def sparse_adagrad_bf16(table_bits: np.ndarray, state: np.ndarray, list_keys, grads, lr: float, eps: float) -> None:
+    """In place on ``table_bits`` [R, D] uint16 (bf16 bit patterns) and ``state`` [R] fp32."""
+    assert table_bits.dtype == np.uint16 and state.dtype == np.float32
+    assert table_bits.flags["C_CONTIGUOUS"] and state.flags["C_CONTIGUOUS"]
+    R, D = table_bits.shape
+    list_keys = _as(list_keys, np.int64)
+    grads = _as(grads, np.float32)
+    rc = _load().np_ref_sparse_adagrad_bf16(_p(table_bits), _p(state), ctypes.c_int64(R), ctypes.c_int32(D), _p(list_keys),
+                                            _p(grads), ctypes.c_int32(list_keys.shape[0]), ctypes.c_float(lr),
+                                            ctypes.c_float(eps))
+    _chk(rc, "sparse_adagrad_bf16")
 
 
 def intersect(keys_a, keys_b) -> Tuple[np.ndarray, np.ndarray]:
