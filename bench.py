@@ -29,18 +29,19 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(n: int, U: int, B: int, D: int, S: int, mode: int, max_len: int) -> dict:
+def algorithmic_bytes(n: int, U: int, B: int, D: int, S: int, mode: int, max_len: int, table_elem: int = 4) -> dict:
     """Compulsory HBM bytes of each call (every distinct row / element crosses HBM once)."""
     row = 4 * D
+    trow = table_elem * D   # a table row as stored
     seq = mode == 2
     out_bytes = B * max_len * D * 2 if seq else B * row
     dy_bytes = n * D * 2 if seq else B * row
     return {
         "np_dedup": 8 * n + 4 * n + 4 * n + 16 * U,
         "np_route": 8 * U + 8 * U + 4 * U + 4 * U + 4 * S,
-        "np_lookup_fwd": U * row + 4 * n + 4 * B + out_bytes,
+        "np_lookup_fwd": U * trow + 4 * n + 4 * B + out_bytes,
         "np_lookup_bwd": dy_bytes + 8 * n + 4 * U + U * row,
-        "np_sparse_adagrad": 3 * U * row + 16 * U,
+        "np_sparse_adagrad": U * row + 2 * U * trow + 16 * U,
     }
 
 
@@ -60,6 +61,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large")
+    ap.add_argument("--table-dtype", choices=("f32", "bf16"), default="f32",
+                    help="storage type of the table; bf16 runs np_lookup_fwd_t / np_sparse_adagrad_t (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-div", type=int, default=4)
     ap.add_argument("--fwp-report", action="store_true",
@@ -92,9 +95,15 @@ def main() -> int:
 
     R, D, S = cfg.num_rows, cfg.dim, cfg.num_shards
     seq = cfg.mode == wl.SEQ
-    table = torch.empty((R, D), dtype=torch.float32, device=dev)
+    bf16_table = args.table_dtype == "bf16"
+    table = torch.empty((R, D), dtype=torch.bfloat16 if bf16_table else torch.float32, device=dev)
     state = torch.zeros(R, dtype=torch.float32, device=dev)
-    B.np_util_table_init(table, cfg.table_seed)
+    if bf16_table:
+        B.np_util_table_init_t(table, cfg.table_seed)
+        fwd_call, adagrad_call = B.np_lookup_fwd_t, B.np_sparse_adagrad_t
+    else:
+        B.np_util_table_init(table, cfg.table_seed)
+        fwd_call, adagrad_call = B.np_lookup_fwd, B.np_sparse_adagrad
 
     n_max = max(b.n for b in batches)
     cap = max(s["U"] for s in stats) + 1024
@@ -143,12 +152,12 @@ def main() -> int:
             ev_route.record(side_stream)
         # the table is local, so the forward reads it through the requester-side list (unique keys, inverse map);
         # gradients are produced in send order and applied with the send-ordered keys
-        B.np_lookup_fwd(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
-                        num_list=dd["num_unique"], cap=cap, out=out)
+        fwd_call(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
+                 num_list=dd["num_unique"], cap=cap, out=out)
         main_stream.wait_event(ev_route)
         B.np_lookup_bwd(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
                         unique_to_send=rr["unique_to_send"], grads=grads, ws=ws_b)
-        B.np_sparse_adagrad(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
+        adagrad_call(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
 
     for i in range(args.warmup):
         step(i)
@@ -181,7 +190,7 @@ def main() -> int:
                                 dd["num_unique"], cap, table, state, cfg.lr, cfg.eps, ws=ws_b)
 
     fused = None
-    if D <= 256:
+    if D <= 256 and not bf16_table:   # the fused call takes fp32 tables only
         step_fused(0)
         B.np_prof_enable(True)
         torch.cuda.synchronize()
@@ -222,7 +231,7 @@ def main() -> int:
 
     n_avg = float(np.mean([s["n"] for s in stats]))
     U_avg = float(np.mean([s["U"] for s in stats]))
-    alg = algorithmic_bytes(int(n_avg), int(U_avg), cfg.num_bags, D, S, cfg.mode, max_len)
+    alg = algorithmic_bytes(int(n_avg), int(U_avg), cfg.num_bags, D, S, cfg.mode, max_len, 2 if bf16_table else 4)
     dominant = max((k for k in kernels if k in KERNEL_OF_CALL), key=lambda k: kernels[k]["avg_ms"])
     dom_call = KERNEL_OF_CALL[dominant]
     achieved = alg[dom_call] / (kernels[dominant]["avg_ms"] * 1e-3) / 1e9
@@ -296,7 +305,7 @@ def main() -> int:
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, b0, wl, args.cpu_sample_div)
+        cpu = cpu_baseline(cfg, b0, wl, args.cpu_sample_div, bf16_table)
 
     line = {
         "metric": "embedding lookups/sec (fwd+bwd+update) and achieved HBM GB/s on 1 MI355X",
@@ -311,14 +320,15 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {len(cfg.table_rows)} table(s), {R} rows x dim {D} fp32, batch {cfg.batch} x "
+        "config": {"workload": f"{cfg.name}: {len(cfg.table_rows)} table(s), {R} rows x dim {D} {'bf16' if bf16_table else 'fp32'}, batch {cfg.batch} x "
                                f"{cfg.features} features, Zipf({cfg.alpha}), {S} shards, mode "
                                f"{['sum', 'mean', 'seq-bf16'][cfg.mode]}; step = dedup+route+fwd+bwd+adagrad",
                    "n_lookups": [s["n"] for s in stats], "unique_keys": [s["U"] for s in stats],
                    "hottest_key_count": [s["hottest"] for s in stats], "distinct_key_overlap": overlap,
                    "num_bags": cfg.num_bags, "max_len": max_len},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((cfg.name, dominant)),
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None if bf16_table else MEASURED_TRAFFIC.get((cfg.name, dominant)),
                      "algorithmic_bytes_per_launch": alg[dom_call], "avg_launch_ms": kernels[dominant]["avg_ms"]},
         "cpu_baseline": cpu,
         "fwd_bwd_update": {"ms_per_step": fbu_ms, "lookups_per_s": n_avg / (fbu_ms * 1e-3) if fbu_ms > 0 else None,
@@ -344,7 +354,7 @@ def n_steps_lookups(dbatch, args) -> int:
     return sum(dbatch[(args.warmup + i) % 2]["n"] for i in range(args.steps))
 
 
-def cpu_baseline(cfg, batch, wl, div: int):
+def cpu_baseline(cfg, batch, wl, div: int, bf16_table: bool = False):
     """The CPU oracle, as it stands, on the first 1/div of the batch's bags: the five steps on a table that holds
     only the rows the sample touches (keys renumbered in order, which changes no result of the path)."""
     from oracle import np_oracle as O
@@ -356,6 +366,9 @@ def cpu_baseline(cfg, batch, wl, div: int):
     touched = np.unique(keys)
     local = np.searchsorted(touched, keys).astype(np.int64)
     table = wl.table_init_rows(touched, cfg.dim, cfg.table_seed)
+    if bf16_table:
+        import torch
+        table = torch.from_numpy(table).bfloat16().view(torch.int16).numpy().view(np.uint16).copy()
     state = np.zeros(touched.shape[0], np.float32)
     rng = np.random.default_rng(1)
     seq = cfg.mode == wl.SEQ
@@ -373,7 +386,7 @@ def cpu_baseline(cfg, batch, wl, div: int):
     t3 = time.perf_counter()
     grads, _ = O.lookup_bwd(dY, O.BF16 if seq else O.F32, cfg.dim, cfg.mode, batch.max_len, off, inverse, unique.shape[0], uts)
     t4 = time.perf_counter()
-    O.sparse_adagrad(table, state, unique[sfu], grads, cfg.lr, cfg.eps)
+    (O.sparse_adagrad_bf16 if bf16_table else O.sparse_adagrad)(table, state, unique[sfu], grads, cfg.lr, cfg.eps)
     t5 = time.perf_counter()
     total = t5 - t0
     return {"value": n / total, "unit": "lookups/s", "cores": 1, "kind": "oracle",

@@ -173,6 +173,26 @@ int np_sparse_adagrad(float* table, float* state, int64_t num_rows, int32_t dim,
                       void* stream);
 
 /*
+ * Tables stored in bf16 (a storage variant of this build; the paper stores fp32 vectors, Section IV-B).
+ * table_dtype is NP_F32 or NP_BF16; with NP_F32 the two calls below are np_lookup_fwd and np_sparse_adagrad.
+ *
+ * np_lookup_fwd_t: a bf16 row is widened exactly to fp32, then everything is as in np_lookup_fwd (fp32 sums in
+ *   ascending lookup order).  rows_out has the table's dtype and is a bit copy.  table and rows_out need 8-byte
+ *   alignment for bf16 (16 for fp32).
+ * np_sparse_adagrad_t: the row is widened, the fp32 step of np_sparse_adagrad is taken, and the new row is rounded
+ *   to bf16, nearest, ties to even (no stochastic rounding, no fp32 shadow copy); the state stays fp32.  A zero
+ *   gradient leaves the row's bits as they are.
+ * Errors as for the fp32 calls, plus NP_ERR_INVALID_ARG for an unknown table_dtype.
+ */
+int np_lookup_fwd_t(const void* table, int32_t table_dtype, int64_t num_rows, int32_t dim, const int64_t* list_keys,
+                    const int32_t* d_num_list, int32_t cap, const int32_t* idx, const int32_t* bag_offsets,
+                    int32_t num_bags, int32_t n, int32_t mode, int32_t max_len, int32_t out_dtype, void* out,
+                    void* rows_out, void* ws, size_t ws_bytes, void* stream);
+int np_sparse_adagrad_t(void* table, int32_t table_dtype, float* state, int64_t num_rows, int32_t dim,
+                        const int64_t* list_keys, const float* grads, const int32_t* d_num_list, int32_t cap, float lr,
+                        float eps, void* stream);
+
+/*
  * np_lookup_bwd_adagrad - np_lookup_bwd and np_sparse_adagrad in one pass for a worker that owns the rows it
  * reduces (no gradient All2All in between): every finished gradient row is applied on the spot to
  * table[unique[u], :] with the row-wise Adagrad rule above and is never written to HBM (Section IV-B: gradients
@@ -224,6 +244,8 @@ int np_sync_rows(const float* src_rows, const int32_t* src_idx, float* dst_rows,
  * uniform on [-0.01, 0.01), one rounding, identical on every platform.
  */
 int np_util_table_init(float* table, int64_t num_rows, int32_t dim, uint64_t seed, void* stream);
+/* The same for a table of dtype NP_F32 or NP_BF16 (the value above rounded to bf16, nearest even). */
+int np_util_table_init_t(void* table, int32_t table_dtype, int64_t num_rows, int32_t dim, uint64_t seed, void* stream);
 
 /*
  * Count the rows of `table` whose bits differ anywhere from what np_util_table_init(seed) wrote: the number
@@ -232,6 +254,8 @@ int np_util_table_init(float* table, int64_t num_rows, int32_t dim, uint64_t see
  */
 int np_util_table_count_changed(const float* table, int64_t num_rows, int32_t dim, uint64_t seed,
                                 unsigned long long* d_count, void* stream);
+int np_util_table_count_changed_t(const void* table, int32_t table_dtype, int64_t num_rows, int32_t dim, uint64_t seed,
+                                  unsigned long long* d_count, void* stream);
 
 /* Plain device copy of `bytes` (multiple of 16) with 16-byte loads and stores: the bandwidth yardstick. */
 int np_util_stream_copy(void* dst, const void* src, size_t bytes, void* stream);

@@ -61,6 +61,15 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
                                         _f32, _f32, _vp, _sz, _vp]
     L.np_sparse_adagrad.restype = ctypes.c_int
     L.np_sparse_adagrad.argtypes = [_vp, _vp, _i64, _i32, _vp, _vp, _vp, _i32, _f32, _f32, _vp]
+    L.np_lookup_fwd_t.restype = ctypes.c_int
+    L.np_lookup_fwd_t.argtypes = [_vp, _i32, _i64, _i32, _vp, _vp, _i32, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp,
+                                  _sz, _vp]
+    L.np_sparse_adagrad_t.restype = ctypes.c_int
+    L.np_sparse_adagrad_t.argtypes = [_vp, _i32, _vp, _i64, _i32, _vp, _vp, _vp, _i32, _f32, _f32, _vp]
+    L.np_util_table_init_t.restype = ctypes.c_int
+    L.np_util_table_init_t.argtypes = [_vp, _i32, _i64, _i32, _u64, _vp]
+    L.np_util_table_count_changed_t.restype = ctypes.c_int
+    L.np_util_table_count_changed_t.argtypes = [_vp, _i32, _i64, _i32, _u64, _vp, _vp]
     L.np_intersect.restype = ctypes.c_int
     L.np_intersect.argtypes = [_vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _sz, _vp]
     L.np_intersect_workspace_bytes.restype = _sz
@@ -192,6 +201,33 @@ def np_lookup_fwd(table: torch.Tensor, list_keys: torch.Tensor, idx: Optional[to
     return out, rows_out
 
 
+def _table_dtype(table: torch.Tensor) -> int:
+    if table.dtype == torch.float32:
+        return F32
+    if table.dtype == torch.bfloat16:
+        return BF16
+    raise NestPipeError(f"table dtype {table.dtype} is not supported (float32 or bfloat16)")
+
+
+def np_lookup_fwd_t(table: torch.Tensor, list_keys: torch.Tensor, idx: Optional[torch.Tensor], bag_offsets: torch.Tensor,
+                    n: int, mode: int, max_len: int = 1, out_dtype: int = F32, num_list: Optional[torch.Tensor] = None,
+                    cap: int = 0, want_rows: bool = False, out: Optional[torch.Tensor] = None,
+                    rows_out: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    """np_lookup_fwd for a float32 or bfloat16 table (the dtype of ``table`` is passed on); rows_out has the table's dtype."""
+    num_rows, dim = table.shape
+    num_bags = bag_offsets.numel() - 1
+    dev = table.device
+    if out is None:
+        shape = (num_bags, max_len, dim) if mode == SEQ else (num_bags, dim)
+        out = torch.empty(shape, dtype=_dt(out_dtype), device=dev)
+    if want_rows and rows_out is None:
+        rows_out = torch.empty((max(cap, 1), dim), dtype=table.dtype, device=dev)
+    rc = lib.np_lookup_fwd_t(_ptr(table), _table_dtype(table), num_rows, dim, _ptr(list_keys), _ptr(num_list), cap, _ptr(idx),
+                             _ptr(bag_offsets), num_bags, n, mode, max_len, out_dtype, _ptr(out), _ptr(rows_out), 0, 0, _stream())
+    _chk("np_lookup_fwd_t", rc)
+    return out, rows_out
+
+
 def np_lookup_bwd_workspace_bytes(num_bags: int, n: int, dim: int, mode: int) -> int:
     return int(lib.np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode))
 
@@ -240,6 +276,14 @@ def np_sparse_adagrad(table: torch.Tensor, state: torch.Tensor, list_keys: torch
     _chk("np_sparse_adagrad", rc)
 
 
+def np_sparse_adagrad_t(table: torch.Tensor, state: torch.Tensor, list_keys: torch.Tensor, grads: torch.Tensor,
+                        num_list: torch.Tensor, cap: int, lr: float, eps: float) -> None:
+    num_rows, dim = table.shape
+    rc = lib.np_sparse_adagrad_t(_ptr(table), _table_dtype(table), _ptr(state), num_rows, dim, _ptr(list_keys), _ptr(grads),
+                                 _ptr(num_list), cap, lr, eps, _stream())
+    _chk("np_sparse_adagrad_t", rc)
+
+
 def np_intersect(keys_a: torch.Tensor, num_a: torch.Tensor, cap_a: int, keys_b: torch.Tensor, num_b: torch.Tensor, cap_b: int,
                  out: Optional[Dict[str, torch.Tensor]] = None, ws: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
     """-> dict(idx_a, idx_b [min(cap_a, cap_b)] i32, num_common[1] i32)."""
@@ -272,6 +316,20 @@ def np_util_table_count_changed(table: torch.Tensor, seed: int) -> int:
     num_rows, dim = table.shape
     cnt = torch.zeros(1, dtype=torch.int64, device=table.device)
     _chk("np_util_table_count_changed", lib.np_util_table_count_changed(_ptr(table), num_rows, dim, seed, _ptr(cnt), _stream()))
+    return int(cnt.item())
+
+
+def np_util_table_init_t(table: torch.Tensor, seed: int) -> None:
+    num_rows, dim = table.shape
+    _chk("np_util_table_init_t", lib.np_util_table_init_t(_ptr(table), _table_dtype(table), num_rows, dim, seed, _stream()))
+
+
+def np_util_table_count_changed_t(table: torch.Tensor, seed: int) -> int:
+    """Rows of ``table`` (float32 or bfloat16) that differ from the initialiser (synchronises)."""
+    num_rows, dim = table.shape
+    cnt = torch.zeros(1, dtype=torch.int64, device=table.device)
+    _chk("np_util_table_count_changed_t",
+         lib.np_util_table_count_changed_t(_ptr(table), _table_dtype(table), num_rows, dim, seed, _ptr(cnt), _stream()))
     return int(cnt.item())
 
 

@@ -195,6 +195,40 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float x) {
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(static_cast<uint32_t>(h) << 16); }
 
+// A row "word" is four consecutive elements: 16 bytes of an fp32 row, 8 bytes of a bf16 row.  Reading a bf16 word
+// widens exactly; writing one rounds to nearest even.
+__device__ __forceinline__ float4 load_word(const float* row, int w) { return reinterpret_cast<const float4*>(row)[w]; }
+
+__device__ __forceinline__ float4 load_word(const uint16_t* row, int w) {
+    const uint2 u = reinterpret_cast<const uint2*>(row)[w];
+    return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
+                       __uint_as_float(u.y & 0xFFFF0000u));
+}
+
+__device__ __forceinline__ uint2 pack_bf16x4(const float4& a) {
+    uint2 o;
+    o.x = static_cast<uint32_t>(f32_to_bf16(a.x)) | (static_cast<uint32_t>(f32_to_bf16(a.y)) << 16);
+    o.y = static_cast<uint32_t>(f32_to_bf16(a.z)) | (static_cast<uint32_t>(f32_to_bf16(a.w)) << 16);
+    return o;
+}
+
+__device__ __forceinline__ void store_word_stream(float* row, int w, const float4& a) {
+    store_stream(reinterpret_cast<float4*>(row) + w, a);
+}
+
+__device__ __forceinline__ void store_word_stream(uint16_t* row, int w, const float4& a) {
+    store_stream(reinterpret_cast<uint2*>(row) + w, pack_bf16x4(a));
+}
+
+// Bit copy of one word (no conversion, so NaN payloads survive).
+__device__ __forceinline__ void copy_word_stream(const float* src, float* dst, int w) {
+    store_stream(reinterpret_cast<float4*>(dst) + w, reinterpret_cast<const float4*>(src)[w]);
+}
+
+__device__ __forceinline__ void copy_word_stream(const uint16_t* src, uint16_t* dst, int w) {
+    store_stream(reinterpret_cast<uint2*>(dst) + w, reinterpret_cast<const uint2*>(src)[w]);
+}
+
 // Row-wise Adagrad pieces shared by np_sparse_adagrad and the fused backward: written with explicit fused
 // multiply-adds so that both kernels round identically whatever the compiler would contract on its own.
 __device__ __forceinline__ float sumsq4(const float4& g) { return fmaf(g.w, g.w, fmaf(g.z, g.z, fmaf(g.y, g.y, g.x * g.x))); }

@@ -18,20 +18,15 @@ __device__ __forceinline__ int64_t group_bcast64(int64_t v, int src_in_group) {
     return (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
 }
 
-__device__ __forceinline__ void store_words(float* p, const float4& a) { store_stream(reinterpret_cast<float4*>(p), a); }
+__device__ __forceinline__ void store_words(float* p, const float4& a) { store_word_stream(p, 0, a); }
 
-__device__ __forceinline__ void store_words(uint16_t* p, const float4& a) {
-    uint2 o;
-    o.x = static_cast<uint32_t>(f32_to_bf16(a.x)) | (static_cast<uint32_t>(f32_to_bf16(a.y)) << 16);
-    o.y = static_cast<uint32_t>(f32_to_bf16(a.z)) | (static_cast<uint32_t>(f32_to_bf16(a.w)) << 16);
-    store_stream(reinterpret_cast<uint2*>(p), o);
-}
+__device__ __forceinline__ void store_words(uint16_t* p, const float4& a) { store_word_stream(p, 0, a); }
 
 constexpr int kFwdUnroll = 4;
 
-template <int LPR, int NV, bool MEAN, typename OutT>
+template <int LPR, int NV, bool MEAN, typename OutT, typename TabT>
 __global__ void __launch_bounds__(256)
-fwd_pool_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx,
+fwd_pool_kernel(const TabT* __restrict__ table, int dim, const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx,
                 const int32_t* __restrict__ bag_offsets, int num_bags, OutT* __restrict__ out) {
     constexpr int GPB = 256 / LPR;
     const int r = threadIdx.x % LPR;
@@ -49,7 +44,7 @@ fwd_pool_kernel(const float* __restrict__ table, int dim, const int64_t* __restr
         // one lane per lookup: slot, key and the byte offset of the row (the 64-bit multiply happens here, once
         // per lookup, instead of in every lane of the walk below)
         int64_t row_off = 0;
-        if (j < hi) row_off = list_keys[idx ? load_stream(idx + j) : j] * static_cast<int64_t>(dim) * static_cast<int64_t>(sizeof(float));
+        if (j < hi) row_off = list_keys[idx ? load_stream(idx + j) : j] * static_cast<int64_t>(dim) * static_cast<int64_t>(sizeof(TabT));
         const int off_lo = static_cast<int>(row_off & 0xFFFFFFFFll), off_hi = static_cast<int>(row_off >> 32);
         const int cnt = hi - base < LPR ? hi - base : LPR;
         for (int k0 = 0; k0 < cnt; k0 += kFwdUnroll) {
@@ -59,12 +54,12 @@ fwd_pool_kernel(const float* __restrict__ table, int dim, const int64_t* __restr
                 const bool on = k0 + q < cnt;  // uniform inside the group; k0 + q < LPR always
                 const uint32_t lo32 = static_cast<uint32_t>(__shfl(off_lo, gl + k0 + q, kWave));
                 const uint32_t hi32 = static_cast<uint32_t>(__shfl(off_hi, gl + k0 + q, kWave));
-                const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const char*>(table) +
-                                                                    ((static_cast<uint64_t>(hi32) << 32) | lo32));
+                const TabT* src = reinterpret_cast<const TabT*>(reinterpret_cast<const char*>(table) +
+                                                                ((static_cast<uint64_t>(hi32) << 32) | lo32));
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
                     const int wv = r + v * LPR;
-                    x[q][v] = (on && wv < words) ? src[wv] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    x[q][v] = (on && wv < words) ? load_word(src, wv) : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
             }
 #pragma unroll
@@ -97,46 +92,174 @@ fwd_pool_kernel(const float* __restrict__ table, int dim, const int64_t* __restr
     }
 }
 
+// Pooling over a bf16 table whose rows are a multiple of 8 elements wide: a lane owns 8 consecutive elements (one
+// 16-byte load per row, as wide as an fp32 lane's), L8 lanes share a row, so a wave keeps twice as many rows in
+// flight as with 8-byte lanes.  Same walk and same order of additions as fwd_pool_kernel.
+__device__ __forceinline__ void widen8(const uint4& u, float4& a, float4& b) {
+    a = make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
+                    __uint_as_float(u.y & 0xFFFF0000u));
+    b = make_float4(__uint_as_float(u.z << 16), __uint_as_float(u.z & 0xFFFF0000u), __uint_as_float(u.w << 16),
+                    __uint_as_float(u.w & 0xFFFF0000u));
+}
+
+template <int L8, int NV8, bool MEAN, typename OutT>
+__global__ void __launch_bounds__(256)
+fwd_pool_bf16x8_kernel(const uint16_t* __restrict__ table, int dim, const int64_t* __restrict__ list_keys,
+                       const int32_t* __restrict__ idx, const int32_t* __restrict__ bag_offsets, int num_bags, OutT* __restrict__ out) {
+    constexpr int GPB = 256 / L8;
+    const int r = threadIdx.x % L8;
+    const int64_t b = static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / L8;
+    if (b >= num_bags) return;  // whole groups leave together
+    const int lo = bag_offsets[b], hi = bag_offsets[b + 1];
+    const int chunks = dim / 8;
+    float4 acc[NV8][2];
+#pragma unroll
+    for (int v = 0; v < NV8; ++v) acc[v][0] = acc[v][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int gl = __lane_id() & ~(L8 - 1);
+    for (int base = lo; base < hi; base += L8) {
+        const int j = base + r;
+        int64_t row_off = 0;
+        if (j < hi) row_off = list_keys[idx ? load_stream(idx + j) : j] * static_cast<int64_t>(dim) * 2;
+        const int off_lo = static_cast<int>(row_off & 0xFFFFFFFFll), off_hi = static_cast<int>(row_off >> 32);
+        const int cnt = hi - base < L8 ? hi - base : L8;
+        for (int k0 = 0; k0 < cnt; k0 += kFwdUnroll) {
+            uint4 x[kFwdUnroll][NV8];
+#pragma unroll
+            for (int q = 0; q < kFwdUnroll; ++q) {
+                const bool on = k0 + q < cnt;  // uniform inside the group; k0 + q < L8 always (L8 >= kFwdUnroll)
+                const uint32_t lo32 = static_cast<uint32_t>(__shfl(off_lo, gl + k0 + q, kWave));
+                const uint32_t hi32 = static_cast<uint32_t>(__shfl(off_hi, gl + k0 + q, kWave));
+                const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(table) +
+                                                                  ((static_cast<uint64_t>(hi32) << 32) | lo32));
+#pragma unroll
+                for (int v = 0; v < NV8; ++v) {
+                    const int c = r + v * L8;
+                    x[q][v] = (on && c < chunks) ? src[c] : make_uint4(0u, 0u, 0u, 0u);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kFwdUnroll; ++q) {
+#pragma unroll
+                for (int v = 0; v < NV8; ++v) {  // rows that were not loaded are zeros
+                    float4 a, c;
+                    widen8(x[q][v], a, c);
+                    acc[v][0].x += a.x;
+                    acc[v][0].y += a.y;
+                    acc[v][0].z += a.z;
+                    acc[v][0].w += a.w;
+                    acc[v][1].x += c.x;
+                    acc[v][1].y += c.y;
+                    acc[v][1].z += c.z;
+                    acc[v][1].w += c.w;
+                }
+            }
+        }
+    }
+    float scale = 1.f;
+    if (MEAN && hi > lo) scale = 1.f / static_cast<float>(hi - lo);
+#pragma unroll
+    for (int v = 0; v < NV8; ++v) {
+        const int c = r + v * L8;
+        if (c < chunks) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float4 a = acc[v][h];
+                if (MEAN) {
+                    a.x *= scale;
+                    a.y *= scale;
+                    a.z *= scale;
+                    a.w *= scale;
+                }
+                store_words(out + static_cast<size_t>(b) * dim + c * 8 + h * 4, a);
+            }
+        }
+    }
+}
+
+template <int L8, int NV8>
+void fwd_pool_bf16x8_launch(const uint16_t* table, int dim, const int64_t* list_keys, const int32_t* idx, const int32_t* bag_offsets,
+                            int num_bags, int mode, int out_dtype, void* out, hipStream_t stream) {
+    constexpr int GPB = 256 / L8;
+    const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(num_bags) + GPB - 1) / GPB);
+    const bool mean = mode == NP_POOL_MEAN;
+    if (out_dtype == NP_BF16) {
+        if (mean)
+            NP_LAUNCH("fwd_pool", (fwd_pool_bf16x8_kernel<L8, NV8, true, uint16_t>), dim3(grid), dim3(256), 0, stream, table, dim,
+                      list_keys, idx, bag_offsets, num_bags, static_cast<uint16_t*>(out));
+        else
+            NP_LAUNCH("fwd_pool", (fwd_pool_bf16x8_kernel<L8, NV8, false, uint16_t>), dim3(grid), dim3(256), 0, stream, table, dim,
+                      list_keys, idx, bag_offsets, num_bags, static_cast<uint16_t*>(out));
+    } else {
+        if (mean)
+            NP_LAUNCH("fwd_pool", (fwd_pool_bf16x8_kernel<L8, NV8, true, float>), dim3(grid), dim3(256), 0, stream, table, dim,
+                      list_keys, idx, bag_offsets, num_bags, static_cast<float*>(out));
+        else
+            NP_LAUNCH("fwd_pool", (fwd_pool_bf16x8_kernel<L8, NV8, false, float>), dim3(grid), dim3(256), 0, stream, table, dim,
+                      list_keys, idx, bag_offsets, num_bags, static_cast<float*>(out));
+    }
+}
+
 #ifndef NP_SEQ_PER_GROUP
 #define NP_SEQ_PER_GROUP 4
 #endif
 constexpr int kSeqPerGroup = NP_SEQ_PER_GROUP;  // output positions per group, their slot -> key -> row chains in flight together
 
-template <int LPR, int NV, typename OutT>
-__global__ void __launch_bounds__(256)
-fwd_seq_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx,
-               const int32_t* __restrict__ bag_offsets, int num_bags, int max_len, OutT* __restrict__ out) {
-    constexpr int GPB = 256 / LPR;
-    const int r = threadIdx.x % LPR;
-    const int64_t total = static_cast<int64_t>(num_bags) * max_len;
-    const int64_t q0 = (static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR) * kSeqPerGroup;  // first output position
-    const int words = dim / 4;
-    const float4* src[kSeqPerGroup];
-#pragma unroll
-    for (int k = 0; k < kSeqPerGroup; ++k) {
-        const int64_t q = q0 + k;
-        src[k] = nullptr;
-        if (q < total) {
-            const int b = static_cast<int>(static_cast<uint32_t>(q) / static_cast<uint32_t>(max_len));  // total < 2^31
-            const int p = static_cast<int>(q - static_cast<int64_t>(b) * max_len);
-            const int lo = bag_offsets[b];
-            if (p < bag_offsets[b + 1] - lo) {
-                const int j = lo + p;
-                src[k] = reinterpret_cast<const float4*>(table + static_cast<size_t>(list_keys[idx ? load_stream(idx + j) : j]) * dim);
-            }
+// Resolves the wave's output positions once, one lane each (position -> bag -> slot -> key), and hands every
+// group the byte offsets of its SPG rows by shuffle; -1 marks padding or a position past the end.
+// ELEM_BYTES is the size of a table element.  All 64 lanes call it.
+template <int LANES, int SPG, int ELEM_BYTES>
+__device__ __forceinline__ void seq_row_offsets(int64_t wq0, int64_t total, int max_len, int dim, const int64_t* __restrict__ list_keys,
+                                                const int32_t* __restrict__ idx, const int32_t* __restrict__ bag_offsets,
+                                                int64_t (&off)[SPG]) {
+    constexpr int PW = (kWave / LANES) * SPG;  // positions per wave
+    static_assert(PW <= kWave, "one lane per position");
+    const int lane = __lane_id();
+    int64_t my_off = -1;
+    if (lane < PW && wq0 + lane < total) {
+        const int64_t q = wq0 + lane;
+        const int b = static_cast<int>(static_cast<uint32_t>(q) / static_cast<uint32_t>(max_len));  // total < 2^31
+        const int p = static_cast<int>(q - static_cast<int64_t>(b) * max_len);
+        const int lo = bag_offsets[b];
+        if (p < bag_offsets[b + 1] - lo) {
+            const int j = lo + p;
+            my_off = list_keys[idx ? load_stream(idx + j) : j] * static_cast<int64_t>(dim) * ELEM_BYTES;
         }
     }
-    float4 x[kSeqPerGroup][NV];
+    const int off_lo = static_cast<int>(my_off & 0xFFFFFFFFll), off_hi = static_cast<int>(my_off >> 32);
 #pragma unroll
-    for (int k = 0; k < kSeqPerGroup; ++k) {
+    for (int k = 0; k < SPG; ++k) {
+        const int from = (lane / LANES) * SPG + k;
+        const uint32_t lo32 = static_cast<uint32_t>(__shfl(off_lo, from, kWave));
+        const int32_t hi32 = __shfl(off_hi, from, kWave);
+        off[k] = (static_cast<int64_t>(hi32) << 32) | lo32;
+    }
+}
+
+template <int LPR, int NV, typename OutT, typename TabT>
+__global__ void __launch_bounds__(256)
+fwd_seq_kernel(const TabT* __restrict__ table, int dim, const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx,
+               const int32_t* __restrict__ bag_offsets, int num_bags, int max_len, OutT* __restrict__ out) {
+    constexpr int GPB = 256 / LPR;
+    constexpr int SPG = kSeqPerGroup < LPR ? kSeqPerGroup : LPR;  // positions per group; at most 64 per wave
+    const int r = threadIdx.x % LPR;
+    const int64_t total = static_cast<int64_t>(num_bags) * max_len;
+    const int64_t q0 = (static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR) * SPG;  // first output position of the group
+    const int64_t wq0 = (static_cast<int64_t>(blockIdx.x) * GPB + (threadIdx.x / kWave) * (kWave / LPR)) * SPG;  // ... of the wave
+    const int words = dim / 4;
+    int64_t off[SPG];
+    seq_row_offsets<LPR, SPG, static_cast<int>(sizeof(TabT))>(wq0, total, max_len, dim, list_keys, idx, bag_offsets, off);
+    float4 x[SPG][NV];
+#pragma unroll
+    for (int k = 0; k < SPG; ++k) {
+        const TabT* src = reinterpret_cast<const TabT*>(reinterpret_cast<const char*>(table) + (off[k] < 0 ? 0 : off[k]));
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int wv = r + v * LPR;
-            x[k][v] = (src[k] && wv < words) ? src[k][wv] : make_float4(0.f, 0.f, 0.f, 0.f);
+            x[k][v] = (off[k] >= 0 && wv < words) ? load_word(src, wv) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
 #pragma unroll
-    for (int k = 0; k < kSeqPerGroup; ++k) {
+    for (int k = 0; k < SPG; ++k) {
         const int64_t q = q0 + k;
         if (q < total) {
 #pragma unroll
@@ -161,34 +284,13 @@ fwd_seq_bf16x8_kernel(const float* __restrict__ table, int dim, const int64_t* _
     const int64_t total = static_cast<int64_t>(num_bags) * max_len;
     const int64_t q0 = (static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / L8) * SPG;
     const int chunks = dim / 8;
-    // The position -> bag -> slot -> key chain runs once per output position, on one lane each: lane l of the wave
-    // resolves the wave's l-th position, the groups then pick their row offsets up by shuffle.
-    constexpr int PW = (kWave / L8) * SPG;  // positions per wave, <= 64
-    static_assert(PW <= kWave, "one lane per position");
-    const int lane = __lane_id();
     const int64_t wq0 = (static_cast<int64_t>(blockIdx.x) * GPB + (threadIdx.x / kWave) * (kWave / L8)) * SPG;
-    int64_t my_off = -1;  // byte offset of the row of position wq0 + lane; -1: padding or past the end
-    if (lane < PW && wq0 + lane < total) {
-        const int64_t q = wq0 + lane;
-        const int b = static_cast<int>(static_cast<uint32_t>(q) / static_cast<uint32_t>(max_len));  // total < 2^31
-        const int p = static_cast<int>(q - static_cast<int64_t>(b) * max_len);
-        const int lo = bag_offsets[b];
-        if (p < bag_offsets[b + 1] - lo) {
-            const int j = lo + p;
-            my_off = list_keys[idx ? load_stream(idx + j) : j] * static_cast<int64_t>(dim) * static_cast<int64_t>(sizeof(float));
-        }
-    }
-    const int off_lo = static_cast<int>(my_off & 0xFFFFFFFFll), off_hi = static_cast<int>(my_off >> 32);
+    int64_t off[SPG];
+    seq_row_offsets<L8, SPG, 4>(wq0, total, max_len, dim, list_keys, idx, bag_offsets, off);
     const float4* src[SPG];
 #pragma unroll
-    for (int k = 0; k < SPG; ++k) {
-        const int from = (lane / L8) * SPG + k;
-        const uint32_t lo32 = static_cast<uint32_t>(__shfl(off_lo, from, kWave));
-        const int32_t hi32 = __shfl(off_hi, from, kWave);
-        src[k] = hi32 < 0 ? nullptr
-                          : reinterpret_cast<const float4*>(reinterpret_cast<const char*>(table) +
-                                                            ((static_cast<uint64_t>(static_cast<uint32_t>(hi32)) << 32) | lo32));
-    }
+    for (int k = 0; k < SPG; ++k)
+        src[k] = off[k] < 0 ? nullptr : reinterpret_cast<const float4*>(reinterpret_cast<const char*>(table) + off[k]);
     float4 x[SPG][NV8][2];
 #pragma unroll
     for (int k = 0; k < SPG; ++k) {
@@ -233,26 +335,27 @@ void fwd_seq_bf16x8_launch(const float* table, int dim, const int64_t* list_keys
               num_bags, max_len, out);
 }
 
-template <int LPR, int NV>
+template <int LPR, int NV, typename TabT>
 __global__ void __launch_bounds__(256)
-fwd_rows_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys,
-                const int32_t* __restrict__ d_num_list, float* __restrict__ rows_out) {
+fwd_rows_kernel(const TabT* __restrict__ table, int dim, const int64_t* __restrict__ list_keys,
+                const int32_t* __restrict__ d_num_list, TabT* __restrict__ rows_out) {
     constexpr int GPB = 256 / LPR;
     const int r = threadIdx.x % LPR;
     const int words = dim / 4;
     const int L = *d_num_list;
     for (int64_t p = static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR; p < L; p += static_cast<int64_t>(gridDim.x) * GPB) {
-        const float4* src = reinterpret_cast<const float4*>(table + static_cast<size_t>(list_keys[p]) * dim);
+        const TabT* src = table + static_cast<size_t>(list_keys[p]) * dim;
+        TabT* dst = rows_out + static_cast<size_t>(p) * dim;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int wv = r + v * LPR;
-            if (wv < words) store_stream(reinterpret_cast<float4*>(rows_out + static_cast<size_t>(p) * dim + wv * 4), src[wv]);
+            if (wv < words) copy_word_stream(src, dst, wv);
         }
     }
 }
 
 struct FwdArgs {
-    const float* table;
+    const void* table;
     int dim;
     const int64_t* list_keys;
     const int32_t* d_num_list;
@@ -261,40 +364,42 @@ struct FwdArgs {
     const int32_t* bag_offsets;
     int num_bags, mode, max_len, out_dtype;
     void* out;
-    float* rows_out;
+    void* rows_out;
     hipStream_t stream;
 };
 
-template <int LPR, int NV>
+template <int LPR, int NV, typename TabT>
 void fwd_launch(const FwdArgs& a) {
     constexpr int GPB = 256 / LPR;
+    const TabT* table = static_cast<const TabT*>(a.table);
     if (a.num_bags > 0) {
         if (a.mode == NP_SEQ) {
+            constexpr int SPG = kSeqPerGroup < LPR ? kSeqPerGroup : LPR;
             const int64_t total = static_cast<int64_t>(a.num_bags) * a.max_len;
-            const int64_t per_block = static_cast<int64_t>(GPB) * kSeqPerGroup;
+            const int64_t per_block = static_cast<int64_t>(GPB) * SPG;
             const unsigned grid = static_cast<unsigned>((total + per_block - 1) / per_block);
             if (a.out_dtype == NP_BF16)
-                NP_LAUNCH("fwd_seq", (fwd_seq_kernel<LPR, NV, uint16_t>), dim3(grid), dim3(256), 0, a.stream, a.table, a.dim,
+                NP_LAUNCH("fwd_seq", (fwd_seq_kernel<LPR, NV, uint16_t, TabT>), dim3(grid), dim3(256), 0, a.stream, table, a.dim,
                           a.list_keys, a.idx, a.bag_offsets, a.num_bags, a.max_len, static_cast<uint16_t*>(a.out));
             else
-                NP_LAUNCH("fwd_seq", (fwd_seq_kernel<LPR, NV, float>), dim3(grid), dim3(256), 0, a.stream, a.table, a.dim,
+                NP_LAUNCH("fwd_seq", (fwd_seq_kernel<LPR, NV, float, TabT>), dim3(grid), dim3(256), 0, a.stream, table, a.dim,
                           a.list_keys, a.idx, a.bag_offsets, a.num_bags, a.max_len, static_cast<float*>(a.out));
         } else {
             const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(a.num_bags) + GPB - 1) / GPB);
             const bool mean = a.mode == NP_POOL_MEAN;
             if (a.out_dtype == NP_BF16) {
                 if (mean)
-                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, true, uint16_t>), dim3(grid), dim3(256), 0, a.stream, a.table,
+                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, true, uint16_t, TabT>), dim3(grid), dim3(256), 0, a.stream, table,
                               a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, static_cast<uint16_t*>(a.out));
                 else
-                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, false, uint16_t>), dim3(grid), dim3(256), 0, a.stream, a.table,
+                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, false, uint16_t, TabT>), dim3(grid), dim3(256), 0, a.stream, table,
                               a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, static_cast<uint16_t*>(a.out));
             } else {
                 if (mean)
-                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, true, float>), dim3(grid), dim3(256), 0, a.stream, a.table,
+                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, true, float, TabT>), dim3(grid), dim3(256), 0, a.stream, table,
                               a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, static_cast<float*>(a.out));
                 else
-                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, false, float>), dim3(grid), dim3(256), 0, a.stream, a.table,
+                    NP_LAUNCH("fwd_pool", (fwd_pool_kernel<LPR, NV, false, float, TabT>), dim3(grid), dim3(256), 0, a.stream, table,
                               a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, static_cast<float*>(a.out));
             }
         }
@@ -302,9 +407,21 @@ void fwd_launch(const FwdArgs& a) {
     if (a.rows_out && a.cap > 0) {
         int64_t want = (static_cast<int64_t>(a.cap) + GPB - 1) / GPB;
         const unsigned grid = static_cast<unsigned>(want < 16384 ? want : 16384);
-        NP_LAUNCH("fwd_rows", (fwd_rows_kernel<LPR, NV>), dim3(grid), dim3(256), 0, a.stream, a.table, a.dim, a.list_keys,
-                  a.d_num_list, a.rows_out);
+        NP_LAUNCH("fwd_rows", (fwd_rows_kernel<LPR, NV, TabT>), dim3(grid), dim3(256), 0, a.stream, table, a.dim, a.list_keys,
+                  a.d_num_list, static_cast<TabT*>(a.rows_out));
     }
+}
+
+template <typename TabT>
+void fwd_dispatch(const FwdArgs& a) {
+    const int words = a.dim / 4;
+    if (words <= 4) fwd_launch<4, 1, TabT>(a);
+    else if (words <= 8) fwd_launch<8, 1, TabT>(a);
+    else if (words <= 16) fwd_launch<16, 1, TabT>(a);
+    else if (words <= 32) fwd_launch<32, 1, TabT>(a);
+    else if (words <= 64) fwd_launch<64, 1, TabT>(a);
+    else if (words <= 128) fwd_launch<64, 2, TabT>(a);
+    else fwd_launch<64, 4, TabT>(a);
 }
 
 }  // namespace np
@@ -313,46 +430,67 @@ extern "C" {
 
 size_t np_lookup_fwd_workspace_bytes(int32_t, int32_t, int32_t, int32_t) { return 0; }
 
-int np_lookup_fwd(const float* table, int64_t num_rows, int32_t dim, const int64_t* list_keys,
-                  const int32_t* d_num_list, int32_t cap, const int32_t* idx, const int32_t* bag_offsets,
-                  int32_t num_bags, int32_t n, int32_t mode, int32_t max_len, int32_t out_dtype, void* out,
-                  float* rows_out, void* ws, size_t ws_bytes, void* stream) {
+int np_lookup_fwd_t(const void* table, int32_t table_dtype, int64_t num_rows, int32_t dim, const int64_t* list_keys,
+                    const int32_t* d_num_list, int32_t cap, const int32_t* idx, const int32_t* bag_offsets,
+                    int32_t num_bags, int32_t n, int32_t mode, int32_t max_len, int32_t out_dtype, void* out,
+                    void* rows_out, void* ws, size_t ws_bytes, void* stream) {
     (void)ws;
     (void)ws_bytes;
     if (!table || num_rows < 1 || num_bags < 0 || n < 0 || cap < 0 || !bag_offsets) return NP_ERR_INVALID_ARG;
+    if (table_dtype != NP_F32 && table_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
     if (mode != NP_POOL_SUM && mode != NP_POOL_MEAN && mode != NP_SEQ) return NP_ERR_INVALID_ARG;
     if (out_dtype != NP_F32 && out_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
     if (mode == NP_SEQ && max_len < 1) return NP_ERR_INVALID_ARG;
     if (dim < 4 || dim % 4 != 0 || dim > NP_MAX_DIM) return NP_ERR_UNSUPPORTED;
     if ((num_bags > 0 && !out) || (n > 0 && !list_keys)) return NP_ERR_INVALID_ARG;
     if (rows_out && (!d_num_list || !list_keys)) return NP_ERR_INVALID_ARG;
-    if (!np::aligned(table, 16) || !np::aligned(out, out_dtype == NP_BF16 ? 8 : 16) || !np::aligned(rows_out, 16))
+    const size_t row_align = table_dtype == NP_BF16 ? 8 : 16;
+    if (!np::aligned(table, row_align) || !np::aligned(out, out_dtype == NP_BF16 ? 8 : 16) || !np::aligned(rows_out, row_align))
         return NP_ERR_INVALID_ARG;
     if (mode == NP_SEQ && static_cast<int64_t>(num_bags) * max_len > INT32_MAX) return NP_ERR_UNSUPPORTED;
     np::FwdArgs a{table, dim, list_keys, d_num_list, cap, idx, bag_offsets, num_bags, mode, max_len, out_dtype, out, rows_out,
                   static_cast<hipStream_t>(stream)};
-    const int words = dim / 4;
+    if (table_dtype == NP_BF16) {
+        if (mode != NP_SEQ && dim % 8 == 0 && dim >= 32 && num_bags > 0 && np::aligned(table, 16)) {
+            // full-width route: 16-byte loads of 8 bf16 each; rows_out, if asked for, still goes through the generic launcher
+            hipStream_t st = static_cast<hipStream_t>(stream);
+            const uint16_t* t = static_cast<const uint16_t*>(table);
+            const int chunks = dim / 8;
+            if (chunks <= 4) np::fwd_pool_bf16x8_launch<4, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
+            else if (chunks <= 8) np::fwd_pool_bf16x8_launch<8, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
+            else if (chunks <= 16) np::fwd_pool_bf16x8_launch<16, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
+            else if (chunks <= 32) np::fwd_pool_bf16x8_launch<32, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
+            else if (chunks <= 64) np::fwd_pool_bf16x8_launch<64, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
+            else np::fwd_pool_bf16x8_launch<64, 2>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
+            a.num_bags = 0;
+        }
+        np::fwd_dispatch<uint16_t>(a);
+        return np::launch_status();
+    }
     if (mode == NP_SEQ && out_dtype == NP_BF16 && dim % 8 == 0 && num_bags > 0 && np::aligned(out, 16)) {
         // full-width route for bf16 sequences; the optional rows_out copy still goes through the generic launcher
         hipStream_t st = static_cast<hipStream_t>(stream);
         uint16_t* o = static_cast<uint16_t*>(out);
+        const float* t = static_cast<const float*>(table);
         const int chunks = dim / 8;
-        if (chunks <= 4) np::fwd_seq_bf16x8_launch<4, 1>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
-        else if (chunks <= 8) np::fwd_seq_bf16x8_launch<8, 1>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
-        else if (chunks <= 16) np::fwd_seq_bf16x8_launch<16, 1>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
-        else if (chunks <= 32) np::fwd_seq_bf16x8_launch<32, 1>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
-        else if (chunks <= 64) np::fwd_seq_bf16x8_launch<64, 1>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
-        else np::fwd_seq_bf16x8_launch<64, 2>(table, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        if (chunks <= 4) np::fwd_seq_bf16x8_launch<4, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        else if (chunks <= 8) np::fwd_seq_bf16x8_launch<8, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        else if (chunks <= 16) np::fwd_seq_bf16x8_launch<16, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        else if (chunks <= 32) np::fwd_seq_bf16x8_launch<32, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        else if (chunks <= 64) np::fwd_seq_bf16x8_launch<64, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
+        else np::fwd_seq_bf16x8_launch<64, 2>(t, dim, list_keys, idx, bag_offsets, num_bags, max_len, o, st);
         a.num_bags = 0;  // pooled / sequence part done; what remains for the generic launcher is rows_out
     }
-    if (words <= 4) np::fwd_launch<4, 1>(a);
-    else if (words <= 8) np::fwd_launch<8, 1>(a);
-    else if (words <= 16) np::fwd_launch<16, 1>(a);
-    else if (words <= 32) np::fwd_launch<32, 1>(a);
-    else if (words <= 64) np::fwd_launch<64, 1>(a);
-    else if (words <= 128) np::fwd_launch<64, 2>(a);
-    else np::fwd_launch<64, 4>(a);
+    np::fwd_dispatch<float>(a);
     return np::launch_status();
+}
+
+int np_lookup_fwd(const float* table, int64_t num_rows, int32_t dim, const int64_t* list_keys,
+                  const int32_t* d_num_list, int32_t cap, const int32_t* idx, const int32_t* bag_offsets,
+                  int32_t num_bags, int32_t n, int32_t mode, int32_t max_len, int32_t out_dtype, void* out,
+                  float* rows_out, void* ws, size_t ws_bytes, void* stream) {
+    return np_lookup_fwd_t(table, NP_F32, num_rows, dim, list_keys, d_num_list, cap, idx, bag_offsets, num_bags, n, mode,
+                           max_len, out_dtype, out, rows_out, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

@@ -40,22 +40,27 @@ void prof_end(hipStream_t stream) {
 
 // ---------------------------------------------------------------- harness kernels -----------------
 
-__global__ void __launch_bounds__(256) table_init_kernel(float4* __restrict__ table, uint64_t num_words, uint64_t seed_term) {
+// Initial value of table element e (row * dim + column): a hash of e and the seed mapped to [-0.01, 0.01).
+__device__ __forceinline__ float table_init_value(uint64_t e, uint64_t seed_term) {
+    uint64_t h = e + seed_term;
+    h ^= h >> 31;
+    h *= 0xD6E8FEB86659FD93ull;
+    h ^= h >> 27;
+    h *= 0xA3B195354A39B70Dull;
+    h ^= h >> 33;
+    const int q = static_cast<int>(h >> 40) - 8388608;
+    return static_cast<float>(q) * (0.01f / 8388608.0f);
+}
+
+// TabT = float: the value itself; TabT = uint16_t: the value rounded to bf16 (nearest even).
+template <typename TabT>
+__global__ void __launch_bounds__(256) table_init_kernel(TabT* __restrict__ table, uint64_t num_words, uint64_t seed_term) {
     const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
     for (uint64_t w = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; w < num_words; w += stride) {
         float v[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            uint64_t h = w * 4 + c + seed_term;
-            h ^= h >> 31;
-            h *= 0xD6E8FEB86659FD93ull;
-            h ^= h >> 27;
-            h *= 0xA3B195354A39B70Dull;
-            h ^= h >> 33;
-            const int q = static_cast<int>(h >> 40) - 8388608;
-            v[c] = static_cast<float>(q) * (0.01f / 8388608.0f);
-        }
-        table[w] = make_float4(v[0], v[1], v[2], v[3]);
+        for (int c = 0; c < 4; ++c) v[c] = table_init_value(w * 4 + c, seed_term);
+        store_word_stream(table + w * 4, 0, make_float4(v[0], v[1], v[2], v[3]));
     }
 }
 
@@ -64,27 +69,23 @@ __global__ void zero_u64_kernel(unsigned long long* p) {
 }
 
 // One thread per row (test harness code: simplicity over speed); integer atomics only.
+template <typename TabT>
 __global__ void __launch_bounds__(256)
-table_count_changed_kernel(const float4* __restrict__ table, uint64_t num_rows, int words_per_row, uint64_t seed_term,
+table_count_changed_kernel(const TabT* __restrict__ table, uint64_t num_rows, int words_per_row, uint64_t seed_term,
                            unsigned long long* __restrict__ count) {
+    constexpr bool kBf16 = sizeof(TabT) == 2;
     const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
     unsigned long long local = 0;
     for (uint64_t row = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; row < num_rows; row += stride) {
         bool changed = false;
         for (int wq = 0; wq < words_per_row && !changed; ++wq) {
             const uint64_t w = row * words_per_row + wq;
-            const float4 t = table[w];
+            const float4 t = load_word(table + w * 4, 0);
             const float got[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                uint64_t h = w * 4 + c + seed_term;
-                h ^= h >> 31;
-                h *= 0xD6E8FEB86659FD93ull;
-                h ^= h >> 27;
-                h *= 0xA3B195354A39B70Dull;
-                h ^= h >> 33;
-                const int q = static_cast<int>(h >> 40) - 8388608;
-                const float v = static_cast<float>(q) * (0.01f / 8388608.0f);
+                float v = table_init_value(w * 4 + c, seed_term);
+                if (kBf16) v = bf16_to_f32(f32_to_bf16(v));
                 changed |= __float_as_uint(v) != __float_as_uint(got[c]);
             }
         }
@@ -118,30 +119,52 @@ const char* np_status_string(int status) {
     }
 }
 
-int np_util_table_init(float* table, int64_t num_rows, int32_t dim, uint64_t seed, void* stream) {
-    if (!table || num_rows < 0 || dim < 4 || dim % 4 != 0 || !np::aligned(table, 16)) return NP_ERR_INVALID_ARG;
+int np_util_table_init_t(void* table, int32_t table_dtype, int64_t num_rows, int32_t dim, uint64_t seed, void* stream) {
+    if (table_dtype != NP_F32 && table_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
+    if (!table || num_rows < 0 || dim < 4 || dim % 4 != 0 || !np::aligned(table, table_dtype == NP_BF16 ? 8 : 16))
+        return NP_ERR_INVALID_ARG;
     const uint64_t words = static_cast<uint64_t>(num_rows) * static_cast<uint64_t>(dim) / 4;
     if (words == 0) return NP_OK;
     const uint64_t want = (words + 255) / 256;
     const unsigned grid = static_cast<unsigned>(want < 65536 ? want : 65536);
-    NP_LAUNCH("table_init", np::table_init_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
-              reinterpret_cast<float4*>(table), words, seed * 0x2545F4914F6CDD1Dull);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t seed_term = seed * 0x2545F4914F6CDD1Dull;
+    if (table_dtype == NP_BF16)
+        NP_LAUNCH("table_init", np::table_init_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, static_cast<uint16_t*>(table), words,
+                  seed_term);
+    else
+        NP_LAUNCH("table_init", np::table_init_kernel<float>, dim3(grid), dim3(256), 0, s, static_cast<float*>(table), words, seed_term);
     return np::launch_status();
 }
 
-int np_util_table_count_changed(const float* table, int64_t num_rows, int32_t dim, uint64_t seed,
-                                unsigned long long* d_count, void* stream) {
-    if (!table || !d_count || num_rows < 0 || dim < 4 || dim % 4 != 0 || !np::aligned(table, 16)) return NP_ERR_INVALID_ARG;
+int np_util_table_init(float* table, int64_t num_rows, int32_t dim, uint64_t seed, void* stream) {
+    return np_util_table_init_t(table, NP_F32, num_rows, dim, seed, stream);
+}
+
+int np_util_table_count_changed_t(const void* table, int32_t table_dtype, int64_t num_rows, int32_t dim, uint64_t seed,
+                                  unsigned long long* d_count, void* stream) {
+    if (table_dtype != NP_F32 && table_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
+    if (!table || !d_count || num_rows < 0 || dim < 4 || dim % 4 != 0 || !np::aligned(table, table_dtype == NP_BF16 ? 8 : 16))
+        return NP_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     NP_LAUNCH("zero_u64", np::zero_u64_kernel, dim3(1), dim3(64), 0, s, d_count);
     if (num_rows > 0) {
         const uint64_t want = (static_cast<uint64_t>(num_rows) + 255) / 256;
         const unsigned grid = static_cast<unsigned>(want < 65536 ? want : 65536);
-        NP_LAUNCH("table_count_changed", np::table_count_changed_kernel, dim3(grid), dim3(256), 0, s,
-                  reinterpret_cast<const float4*>(table), static_cast<uint64_t>(num_rows), dim / 4, seed * 0x2545F4914F6CDD1Dull,
-                  d_count);
+        const uint64_t seed_term = seed * 0x2545F4914F6CDD1Dull;
+        if (table_dtype == NP_BF16)
+            NP_LAUNCH("table_count_changed", np::table_count_changed_kernel<uint16_t>, dim3(grid), dim3(256), 0, s,
+                      static_cast<const uint16_t*>(table), static_cast<uint64_t>(num_rows), dim / 4, seed_term, d_count);
+        else
+            NP_LAUNCH("table_count_changed", np::table_count_changed_kernel<float>, dim3(grid), dim3(256), 0, s,
+                      static_cast<const float*>(table), static_cast<uint64_t>(num_rows), dim / 4, seed_term, d_count);
     }
     return np::launch_status();
+}
+
+int np_util_table_count_changed(const float* table, int64_t num_rows, int32_t dim, uint64_t seed,
+                                unsigned long long* d_count, void* stream) {
+    return np_util_table_count_changed_t(table, NP_F32, num_rows, dim, seed, d_count, stream);
 }
 
 int np_util_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {
