@@ -136,7 +136,6 @@ def main() -> int:
 
     # np_route needs only np_dedup's output and nothing before np_lookup_bwd needs np_route's, so it runs on a second
     # stream (default priority) beside np_lookup_fwd; events order the two streams around it
-    main_stream = torch.cuda.current_stream()
     side_stream = torch.cuda.Stream()
     ev_dedup = torch.cuda.Event()
     ev_route = torch.cuda.Event()
@@ -144,6 +143,7 @@ def main() -> int:
     def step(i: int) -> None:
         bt = dbatch[i % 2]
         n = bt["n"]
+        main_stream = torch.cuda.current_stream()   # the recording stream while a graph is being captured
         B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
         ev_dedup.record(main_stream)
         side_stream.wait_event(ev_dedup)
@@ -215,6 +215,23 @@ def main() -> int:
         step(args.warmup + i)
     torch.cuda.synchronize()
     ms_per_step_noevents = (time.perf_counter() - t2) * 1e3 / args.steps
+
+    # ---- the same step recorded into one HIP graph per batch and replayed (the library only enqueues kernels, so a
+    # caller can do this; the launch-bound small workloads gain, configuration 5 does not)
+    graphs = []
+    for b in range(2):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step(b)
+        graphs.append(g)
+    for i in range(2):
+        graphs[(args.warmup + i) % 2].replay()
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    for i in range(args.steps):
+        graphs[(args.warmup + i) % 2].replay()
+    torch.cuda.synchronize()
+    graph_ms = (time.perf_counter() - t3) * 1e3 / args.steps
 
     kern = {}
     for name, ms in records:
@@ -343,6 +360,7 @@ def main() -> int:
         "dual_buffer_sync": dbsync,
         "frozen_window_dedup": fwp,
         "ms_per_step_without_events": ms_per_step_noevents,
+        "hip_graph_replay": {"ms_per_step": graph_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (graph_ms * 1e-3 * args.steps)},
         "stream_copy_GBps": copy_gbs,
         "input_generation_s": gen_s,
     }

@@ -13,6 +13,8 @@
 // runs they append to each bin then merge in that die's L2 instead of reaching HBM as partial lines.
 #pragma once
 
+#include <atomic>
+
 #include "np_common.hpp"
 
 namespace np {
@@ -30,6 +32,7 @@ constexpr int kPartTile = kPartThreads * kPartIPT;
 static_assert(kPartIPT * kWave <= 65535, "per-wave digit counters are 16 bits wide");
 constexpr int kPartMaxBins = 4096;
 constexpr int kTargetChunks = 1024;
+constexpr int kMaxDevices = 64;  // devices whose dynamic-LDS opt-in is remembered
 constexpr int kColscanThreads = 1024;
 
 struct ChunkPlan {
@@ -323,9 +326,19 @@ inline void run_partition_pass(const P& pol, int n_host, const int* d_n, int bin
     NP_LAUNCH(tag_scan, part_colscan_kernel<kColscanThreads>, dim3((bins + kWave - 1) / kWave), dim3(kColscanThreads), 0, stream, H,
               plan.num_chunks, bins, bin_total);
     const size_t lds = part_scatter_lds_bytes<typename P::KeyT>(bins, P::kStageDigit);
-    if (lds > 48 * 1024)  // above the default dynamic-LDS allowance: opt in (a failure shows up as a failed launch)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(part_scatter_kernel<P>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (lds > 48 * 1024) {
+        // above the default dynamic-LDS allowance: opt in, once per device and size (a failure shows up as a failed
+        // launch); later calls, e.g. while a caller records a graph, then enqueue kernels only
+        static std::atomic<int> granted[kMaxDevices];
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        const bool tracked = dev >= 0 && dev < kMaxDevices;
+        if (!tracked || granted[dev].load(std::memory_order_relaxed) < static_cast<int>(lds)) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(part_scatter_kernel<P>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+            if (tracked) granted[dev].store(static_cast<int>(lds), std::memory_order_relaxed);
+        }
+    }
     NP_LAUNCH(tag_scatter, part_scatter_kernel<P>, dim3(plan.num_chunks), dim3(kPartThreads), lds, stream, pol, n_host,
               d_n, bins, nbits, plan, H, bin_total, totals_out, offsets_out);
 }
