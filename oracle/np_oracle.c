@@ -25,8 +25,8 @@
  *     definition asks for row-wise Adagrad);
  *   - an empty bag pools to zeros and sends no gradient;
  *   - sequence output is bf16 (round to nearest even), zero padded to max_len;
- *   - a table kept in bf16 is read exactly (every bf16 value is an fp32 value) and an updated row is the
- *     fp64 result rounded once to bf16, nearest, ties to even (no stochastic rounding, no fp32 shadow copy).
+ *   - a table kept in bf16 or fp16 is read exactly (every such value is an fp32 value) and an updated row is the
+ *     fp64 result rounded once to that format, nearest, ties to even (no stochastic rounding, no fp32 shadow copy).
  *
  * All functions return 0 on success, a negative value on a bad argument.
  */
@@ -40,6 +40,7 @@
 #define REF_SEQ 2
 #define REF_F32 0
 #define REF_BF16 1
+#define REF_F16 2
 #define REF_SHARD_MOD 0
 #define REF_SHARD_HASH 1
 
@@ -63,25 +64,57 @@ float np_ref_bf16_to_f32(uint16_t h) {
 }
 
 /*
- * Round an fp64 value to bf16 in one step, nearest, ties to even (going through fp32 first would round twice).
- * bf16 has 8 significant bits, exponents like fp32, subnormals that are multiples of 2^-133.
+ * Round an fp64 value to a binary format with `sig` significant bits whose subnormals are multiples of 2^qmin, in
+ * one step, nearest, ties to even (going through fp32 first would round twice).  The result is returned as the fp64
+ * value of the rounded number (exact); the caller encodes it.  x is finite and non-zero.
  */
+static double ref_round_sig(double a, int sig, int qmin) {
+    int e;
+    (void)frexp(a, &e);            /* a = m * 2^e with m in [0.5, 1) */
+    int q = e - sig;               /* keep `sig` significant bits: the result is an integer times 2^q */
+    if (q < qmin) q = qmin;        /* subnormal range: fixed spacing */
+    return ldexp(rint(ldexp(a, -q)), q); /* rint: the default rounding mode is nearest-even; both scalings are exact */
+}
+
+/* bf16: 8 significant bits, exponents like fp32, subnormals that are multiples of 2^-133. */
 uint16_t np_ref_f64_to_bf16(double x) {
     if (isnan(x)) return 0x7FC0u;
     uint16_t sign = signbit(x) ? 0x8000u : 0u;
     double a = fabs(x);
     if (a == 0.0) return sign;
     if (isinf(a)) return (uint16_t)(sign | 0x7F80u);
-    int e;
-    (void)frexp(a, &e);           /* a = m * 2^e with m in [0.5, 1) */
-    int q = e - 8;                /* keep 8 significant bits: the result is an integer times 2^q */
-    if (q < -133) q = -133;       /* subnormal range: fixed spacing */
-    double r = ldexp(rint(ldexp(a, -q)), q); /* rint: the default rounding mode is nearest-even; both scalings are exact */
+    double r = ref_round_sig(a, 8, -133);
     if (r >= ldexp(1.0, 128)) return (uint16_t)(sign | 0x7F80u);
-    float f = (float)r;           /* exact: r has at most 8 significant bits in fp32's range */
+    float f = (float)r;            /* exact: r has at most 8 significant bits in fp32's range */
     uint32_t b;
     memcpy(&b, &f, 4);
     return (uint16_t)(sign | (uint16_t)(b >> 16));
+}
+
+/* IEEE binary16: 11 significant bits, 5 exponent bits (bias 15), subnormals that are multiples of 2^-24. */
+uint16_t np_ref_f64_to_f16(double x) {
+    if (isnan(x)) return 0x7E00u;
+    uint16_t sign = signbit(x) ? 0x8000u : 0u;
+    double a = fabs(x);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return (uint16_t)(sign | 0x7C00u);
+    double r = ref_round_sig(a, 11, -24);
+    if (r >= 65536.0) return (uint16_t)(sign | 0x7C00u);   /* above the largest finite value 65504 after rounding */
+    if (r == 0.0) return sign;
+    if (r < ldexp(1.0, -14)) return (uint16_t)(sign | (uint16_t)ldexp(r, 24));   /* subnormal: the integer r / 2^-24 */
+    int e;
+    double m = frexp(r, &e);       /* r = m * 2^e, m in [0.5, 1): value 1.f * 2^(e-1) */
+    uint16_t frac = (uint16_t)(ldexp(m, 11) - 1024.0);     /* the 10 fraction bits */
+    return (uint16_t)(sign | (uint16_t)((e - 1 + 15) << 10) | frac);
+}
+
+float np_ref_f16_to_f32(uint16_t h) {
+    int e = (h >> 10) & 0x1F, f = h & 0x3FF;
+    double v;
+    if (e == 0) v = ldexp((double)f, -24);
+    else if (e == 31) v = f ? NAN : INFINITY;
+    else v = ldexp(1.0 + (double)f / 1024.0, e - 15);
+    return (float)((h & 0x8000u) ? -v : v);
 }
 
 /* ---------------------------------------------------------------- step 1: dedup ---- */
@@ -363,12 +396,14 @@ int np_ref_sparse_adagrad(float* table, float* state, int64_t num_rows, int32_t 
 }
 
 /*
- * The same update on a table stored in bf16 (bit patterns, [num_rows, dim]); the state stays fp32.  The old row is
- * widened exactly, the step is taken in fp64 with the fp64 state sum, and the new row is rounded once to bf16.
+ * The same update on a table stored in 16 bits (bit patterns, [num_rows, dim]; table_dtype REF_BF16 or REF_F16); the
+ * state stays fp32.  The old row is widened exactly, the step is taken in fp64 with the fp64 state sum, and the new
+ * row is rounded once to the storage format.
  */
-int np_ref_sparse_adagrad_bf16(uint16_t* table, float* state, int64_t num_rows, int32_t dim, const int64_t* list_keys,
-                               const float* grads, int32_t num_list, float lr, float eps) {
+int np_ref_sparse_adagrad_16(uint16_t* table, int32_t table_dtype, float* state, int64_t num_rows, int32_t dim,
+                             const int64_t* list_keys, const float* grads, int32_t num_list, float lr, float eps) {
     if (!table || !state || dim < 1 || num_list < 0) return -1;
+    if (table_dtype != REF_BF16 && table_dtype != REF_F16) return -1;
     for (int32_t p = 0; p < num_list; ++p) {
         int64_t k = list_keys[p];
         if (k < 0 || k >= num_rows) return -3;
@@ -379,10 +414,18 @@ int np_ref_sparse_adagrad_bf16(uint16_t* table, float* state, int64_t num_rows, 
         state[k] = (float)G;
         double denom = sqrt(G) + (double)eps;
         uint16_t* w = table + (size_t)k * (size_t)dim;
-        for (int32_t d = 0; d < dim; ++d)
-            w[d] = np_ref_f64_to_bf16((double)np_ref_bf16_to_f32(w[d]) - (double)lr * (double)g[d] / denom);
+        for (int32_t d = 0; d < dim; ++d) {
+            double old = table_dtype == REF_BF16 ? (double)np_ref_bf16_to_f32(w[d]) : (double)np_ref_f16_to_f32(w[d]);
+            double upd = old - (double)lr * (double)g[d] / denom;
+            w[d] = table_dtype == REF_BF16 ? np_ref_f64_to_bf16(upd) : np_ref_f64_to_f16(upd);
+        }
     }
     return 0;
+}
+
+int np_ref_sparse_adagrad_bf16(uint16_t* table, float* state, int64_t num_rows, int32_t dim, const int64_t* list_keys,
+                               const float* grads, int32_t num_list, float lr, float eps) {
+    return np_ref_sparse_adagrad_16(table, REF_BF16, state, num_rows, dim, list_keys, grads, num_list, lr, eps);
 }
 
 /* ------------------------------------------------- dual-buffer synchronisation (Section IV-B) -------- */

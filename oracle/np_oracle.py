@@ -20,7 +20,7 @@ _SRC = os.path.join(_HERE, "np_oracle.c")
 _LIB = os.path.join(_HERE, "libnp_oracle.so")
 
 POOL_SUM, POOL_MEAN, SEQ = 0, 1, 2
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 SHARD_MOD, SHARD_HASH = 0, 1
 
 _lib = None
@@ -59,8 +59,12 @@ def _load():
         _lib.np_ref_bf16_to_f32.argtypes = [ctypes.c_uint16]
         _lib.np_ref_f64_to_bf16.restype = ctypes.c_uint16
         _lib.np_ref_f64_to_bf16.argtypes = [ctypes.c_double]
+        _lib.np_ref_f64_to_f16.restype = ctypes.c_uint16
+        _lib.np_ref_f64_to_f16.argtypes = [ctypes.c_double]
+        _lib.np_ref_f16_to_f32.restype = ctypes.c_float
+        _lib.np_ref_f16_to_f32.argtypes = [ctypes.c_uint16]
         for name in ("np_ref_dedup", "np_ref_route", "np_ref_compose", "np_ref_lookup_fwd", "np_ref_lookup_bwd",
-                     "np_ref_sparse_adagrad", "np_ref_sparse_adagrad_bf16", "np_ref_intersect", "np_ref_sync_rows"):
+                     "np_ref_sparse_adagrad", "np_ref_sparse_adagrad_bf16", "np_ref_sparse_adagrad_16", "np_ref_intersect", "np_ref_sync_rows"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -91,6 +95,14 @@ def shard(key: int, num_shards: int, shard_fn: int) -> int:
 
 def f64_to_bf16(x: float) -> int:
     return int(_load().np_ref_f64_to_bf16(ctypes.c_double(x)))
+
+
+def f64_to_f16(x: float) -> int:
+    return int(_load().np_ref_f64_to_f16(ctypes.c_double(x)))
+
+
+def f16_to_f32(bits: int) -> float:
+    return float(_load().np_ref_f16_to_f32(ctypes.c_uint16(bits)))
 
 
 def f32_to_bf16(x: float) -> int:
@@ -146,10 +158,13 @@ def lookup_fwd(table, list_keys, idx, bag_offsets, mode: int, max_len: int = 1, 
                want_rows: bool = False, want_abs: bool = False):
     """-> out (fp32 array, or uint16 array of bf16 bit patterns), rows_out or None, abs_out or None.
 
-    ``table`` is fp32, or uint16 bf16 bit patterns (widened exactly before use; rows_out then holds the widened rows).
+    ``table`` is fp32, uint16 bf16 bit patterns, or a numpy float16 array (both widened exactly before use; rows_out
+    then holds the widened rows).
     """
     if isinstance(table, np.ndarray) and table.dtype == np.uint16:
         table = bf16_bits_to_f32(table)
+    elif isinstance(table, np.ndarray) and table.dtype == np.float16:
+        table = f16_bits_to_f32(table.view(np.uint16))
     table = _as(table, np.float32)
     R, D = table.shape
     list_keys = _as(list_keys, np.int64)
@@ -214,6 +229,19 @@ def sparse_adagrad_bf16(table_bits: np.ndarray, state: np.ndarray, list_keys, gr
     _chk(rc, "sparse_adagrad_bf16")
 
 
+def sparse_adagrad_f16(table_bits: np.ndarray, state: np.ndarray, list_keys, grads, lr: float, eps: float) -> None:
+    """In place on ``table_bits`` [R, D] uint16 (IEEE binary16 bit patterns) and ``state`` [R] fp32."""
+    assert table_bits.dtype == np.uint16 and state.dtype == np.float32
+    assert table_bits.flags["C_CONTIGUOUS"] and state.flags["C_CONTIGUOUS"]
+    R, D = table_bits.shape
+    list_keys = _as(list_keys, np.int64)
+    grads = _as(grads, np.float32)
+    rc = _load().np_ref_sparse_adagrad_16(_p(table_bits), ctypes.c_int32(F16), _p(state), ctypes.c_int64(R), ctypes.c_int32(D),
+                                          _p(list_keys), _p(grads), ctypes.c_int32(list_keys.shape[0]), ctypes.c_float(lr),
+                                          ctypes.c_float(eps))
+    _chk(rc, "sparse_adagrad_f16")
+
+
 def intersect(keys_a, keys_b) -> Tuple[np.ndarray, np.ndarray]:
     """-> idx_a, idx_b (int32): positions of the common keys of two ascending distinct key lists, ascending."""
     a = _as(keys_a, np.int64)
@@ -236,6 +264,16 @@ def sync_rows(src: np.ndarray, src_idx, dst: np.ndarray, dst_idx) -> None:
     di = _as(dst_idx, np.int32)
     rc = _load().np_ref_sync_rows(_p(src), _p(si), _p(dst), _p(di), ctypes.c_int32(si.shape[0]), ctypes.c_int32(src.shape[1]))
     _chk(rc, "sync_rows")
+
+
+def f16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of IEEE binary16 bit patterns (uint16) to fp32 values, element by element through the oracle's
+    decoder (array helper for comparisons; small and medium arrays only)."""
+    flat = np.ascontiguousarray(bits, np.uint16).ravel()
+    lut = np.array([f16_to_f32(b) for b in range(65536)], np.float32) if flat.size > 65536 else None
+    if lut is not None:
+        return lut[flat].reshape(bits.shape)
+    return np.array([f16_to_f32(int(b)) for b in flat], np.float32).reshape(bits.shape)
 
 
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
