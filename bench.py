@@ -61,8 +61,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large")
-    ap.add_argument("--table-dtype", choices=("f32", "bf16"), default="f32",
-                    help="storage type of the table; bf16 runs np_lookup_fwd_t / np_sparse_adagrad_t (not the headline)")
+    ap.add_argument("--table-dtype", choices=("f32", "bf16", "f16"), default="f32",
+                    help="storage type of the table; bf16 / f16 run np_lookup_fwd_t / np_sparse_adagrad_t (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-div", type=int, default=4)
     ap.add_argument("--fwp-report", action="store_true",
@@ -95,8 +95,9 @@ def main() -> int:
 
     R, D, S = cfg.num_rows, cfg.dim, cfg.num_shards
     seq = cfg.mode == wl.SEQ
-    bf16_table = args.table_dtype == "bf16"
-    table = torch.empty((R, D), dtype=torch.bfloat16 if bf16_table else torch.float32, device=dev)
+    bf16_table = args.table_dtype != "f32"     # a 16-bit table, bf16 or fp16
+    table = torch.empty((R, D), dtype={"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[args.table_dtype],
+                        device=dev)
     state = torch.zeros(R, dtype=torch.float32, device=dev)
     if bf16_table:
         B.np_util_table_init_t(table, cfg.table_seed)
@@ -322,7 +323,7 @@ def main() -> int:
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, b0, wl, args.cpu_sample_div, bf16_table)
+        cpu = cpu_baseline(cfg, b0, wl, args.cpu_sample_div, args.table_dtype)
 
     line = {
         "metric": "embedding lookups/sec (fwd+bwd+update) and achieved HBM GB/s on 1 MI355X",
@@ -337,7 +338,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {len(cfg.table_rows)} table(s), {R} rows x dim {D} {'bf16' if bf16_table else 'fp32'}, batch {cfg.batch} x "
+        "config": {"workload": f"{cfg.name}: {len(cfg.table_rows)} table(s), {R} rows x dim {D} {args.table_dtype}, batch {cfg.batch} x "
                                f"{cfg.features} features, Zipf({cfg.alpha}), {S} shards, mode "
                                f"{['sum', 'mean', 'seq-bf16'][cfg.mode]}; step = dedup+route+fwd+bwd+adagrad",
                    "n_lookups": [s["n"] for s in stats], "unique_keys": [s["U"] for s in stats],
@@ -372,7 +373,7 @@ def n_steps_lookups(dbatch, args) -> int:
     return sum(dbatch[(args.warmup + i) % 2]["n"] for i in range(args.steps))
 
 
-def cpu_baseline(cfg, batch, wl, div: int, bf16_table: bool = False):
+def cpu_baseline(cfg, batch, wl, div: int, table_dtype: str = "f32"):
     """The CPU oracle, as it stands, on the first 1/div of the batch's bags: the five steps on a table that holds
     only the rows the sample touches (keys renumbered in order, which changes no result of the path)."""
     from oracle import np_oracle as O
@@ -384,9 +385,11 @@ def cpu_baseline(cfg, batch, wl, div: int, bf16_table: bool = False):
     touched = np.unique(keys)
     local = np.searchsorted(touched, keys).astype(np.int64)
     table = wl.table_init_rows(touched, cfg.dim, cfg.table_seed)
-    if bf16_table:
+    if table_dtype == "bf16":
         import torch
         table = torch.from_numpy(table).bfloat16().view(torch.int16).numpy().view(np.uint16).copy()
+    elif table_dtype == "f16":
+        table = table.astype(np.float16)
     state = np.zeros(touched.shape[0], np.float32)
     rng = np.random.default_rng(1)
     seq = cfg.mode == wl.SEQ
@@ -404,7 +407,12 @@ def cpu_baseline(cfg, batch, wl, div: int, bf16_table: bool = False):
     t3 = time.perf_counter()
     grads, _ = O.lookup_bwd(dY, O.BF16 if seq else O.F32, cfg.dim, cfg.mode, batch.max_len, off, inverse, unique.shape[0], uts)
     t4 = time.perf_counter()
-    (O.sparse_adagrad_bf16 if bf16_table else O.sparse_adagrad)(table, state, unique[sfu], grads, cfg.lr, cfg.eps)
+    if table_dtype == "bf16":
+        O.sparse_adagrad_bf16(table, state, unique[sfu], grads, cfg.lr, cfg.eps)
+    elif table_dtype == "f16":
+        O.sparse_adagrad_f16(table.view(np.uint16), state, unique[sfu], grads, cfg.lr, cfg.eps)
+    else:
+        O.sparse_adagrad(table, state, unique[sfu], grads, cfg.lr, cfg.eps)
     t5 = time.perf_counter()
     total = t5 - t0
     return {"value": n / total, "unit": "lookups/s", "cores": 1, "kind": "oracle",

@@ -52,7 +52,7 @@ typedef enum np_status {
 
 enum { NP_SHARD_MOD = 0, NP_SHARD_HASH = 1 };
 enum { NP_POOL_SUM = 0, NP_POOL_MEAN = 1, NP_SEQ = 2 };
-enum { NP_F32 = 0, NP_BF16 = 1 };
+enum { NP_F32 = 0, NP_BF16 = 1, NP_F16 = 2 };  /* NP_F16 (IEEE binary16) is a table dtype only */
 
 #define NP_MAX_SHARDS 4096
 #define NP_MAX_DIM 1024
@@ -173,15 +173,15 @@ int np_sparse_adagrad(float* table, float* state, int64_t num_rows, int32_t dim,
                       void* stream);
 
 /*
- * Tables stored in bf16 (a storage variant of this build; the paper stores fp32 vectors, Section IV-B).
- * table_dtype is NP_F32 or NP_BF16; with NP_F32 the two calls below are np_lookup_fwd and np_sparse_adagrad.
+ * Tables stored in 16 bits (a storage variant of this build; the paper stores fp32 vectors, Section IV-B).
+ * table_dtype is NP_F32, NP_BF16 or NP_F16; with NP_F32 the two calls below are np_lookup_fwd and np_sparse_adagrad.
  *
- * np_lookup_fwd_t: a bf16 row is widened exactly to fp32, then everything is as in np_lookup_fwd (fp32 sums in
+ * np_lookup_fwd_t: a 16-bit row is widened exactly to fp32, then everything is as in np_lookup_fwd (fp32 sums in
  *   ascending lookup order).  rows_out has the table's dtype and is a bit copy.  table and rows_out need 8-byte
- *   alignment for bf16 (16 for fp32).
+ *   alignment for 16-bit rows (16 for fp32).  out_dtype stays NP_F32 or NP_BF16.
  * np_sparse_adagrad_t: the row is widened, the fp32 step of np_sparse_adagrad is taken, and the new row is rounded
- *   to bf16, nearest, ties to even (no stochastic rounding, no fp32 shadow copy); the state stays fp32.  A zero
- *   gradient leaves the row's bits as they are.
+ *   to the table's format, nearest, ties to even (no stochastic rounding, no fp32 shadow copy); the state stays
+ *   fp32.  A zero gradient leaves the row's bits as they are.
  * Errors as for the fp32 calls, plus NP_ERR_INVALID_ARG for an unknown table_dtype.
  */
 int np_lookup_fwd_t(const void* table, int32_t table_dtype, int64_t num_rows, int32_t dim, const int64_t* list_keys,
@@ -244,7 +244,7 @@ int np_sync_rows(const float* src_rows, const int32_t* src_idx, float* dst_rows,
  * uniform on [-0.01, 0.01), one rounding, identical on every platform.
  */
 int np_util_table_init(float* table, int64_t num_rows, int32_t dim, uint64_t seed, void* stream);
-/* The same for a table of dtype NP_F32 or NP_BF16 (the value above rounded to bf16, nearest even). */
+/* The same for a table of dtype NP_F32, NP_BF16 or NP_F16 (the value above rounded to that format, nearest even). */
 int np_util_table_init_t(void* table, int32_t table_dtype, int64_t num_rows, int32_t dim, uint64_t seed, void* stream);
 
 /*

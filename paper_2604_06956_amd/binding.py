@@ -26,7 +26,7 @@ if not os.path.exists(LIB_PATH):
 NP_OK = 0
 SHARD_MOD, SHARD_HASH = 0, 1
 POOL_SUM, POOL_MEAN, SEQ = 0, 1, 2
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 MAX_SHARDS = 4096
 
 _vp, _i32, _i64, _sz, _f32, _u64 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float,
@@ -206,7 +206,9 @@ def _table_dtype(table: torch.Tensor) -> int:
         return F32
     if table.dtype == torch.bfloat16:
         return BF16
-    raise NestPipeError(f"table dtype {table.dtype} is not supported (float32 or bfloat16)")
+    if table.dtype == torch.float16:
+        return F16
+    raise NestPipeError(f"table dtype {table.dtype} is not supported (float32, bfloat16 or float16)")
 
 
 def np_lookup_fwd_t(table: torch.Tensor, list_keys: torch.Tensor, idx: Optional[torch.Tensor], bag_offsets: torch.Tensor,

@@ -79,14 +79,16 @@ extern "C" {
 int np_sparse_adagrad_t(void* table, int32_t table_dtype, float* state, int64_t num_rows, int32_t dim, const int64_t* list_keys,
                         const float* grads, const int32_t* d_num_list, int32_t cap, float lr, float eps, void* stream) {
     if (!table || !state || num_rows < 1 || cap < 0 || !d_num_list) return NP_ERR_INVALID_ARG;
-    if (table_dtype != NP_F32 && table_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
+    if (table_dtype != NP_F32 && table_dtype != NP_BF16 && table_dtype != NP_F16) return NP_ERR_INVALID_ARG;
     if (dim < 4 || dim % 4 != 0 || dim > NP_MAX_DIM) return NP_ERR_UNSUPPORTED;
     if (cap == 0) return NP_OK;
-    if (!list_keys || !grads || !np::aligned(table, table_dtype == NP_BF16 ? 8 : 16) || !np::aligned(grads, 16))
+    if (!list_keys || !grads || !np::aligned(table, table_dtype == NP_F32 ? 16 : 8) || !np::aligned(grads, 16))
         return NP_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (table_dtype == NP_BF16)
         np::adagrad_dispatch(static_cast<uint16_t*>(table), state, dim, list_keys, grads, d_num_list, cap, lr, eps, s);
+    else if (table_dtype == NP_F16)
+        np::adagrad_dispatch(static_cast<__half*>(table), state, dim, list_keys, grads, d_num_list, cap, lr, eps, s);
     else
         np::adagrad_dispatch(static_cast<float*>(table), state, dim, list_keys, grads, d_num_list, cap, lr, eps, s);
     return np::launch_status();

@@ -2,6 +2,7 @@
 // primitives, the XCD-aware block mapping and the routing hash.
 #pragma once
 
+#include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -218,6 +219,35 @@ __device__ __forceinline__ void store_word_stream(float* row, int w, const float
 
 __device__ __forceinline__ void store_word_stream(uint16_t* row, int w, const float4& a) {
     store_stream(reinterpret_cast<uint2*>(row) + w, pack_bf16x4(a));
+}
+
+// fp16 rows are typed __half (bf16 rows are uint16_t): same 8-byte words, hardware conversions (nearest even).
+__device__ __forceinline__ float4 load_word(const __half* row, int w) {
+    const uint2 u = reinterpret_cast<const uint2*>(row)[w];
+    const __half2 lo = *reinterpret_cast<const __half2*>(&u.x), hi = *reinterpret_cast<const __half2*>(&u.y);
+    return make_float4(__low2float(lo), __high2float(lo), __low2float(hi), __high2float(hi));
+}
+
+// fp32 -> fp16, nearest even, of a value that has already been rounded to fp32.  The empty asm pins the fp32 value in
+// a register: without it the compiler may merge the producing fp32 multiply or subtract with the conversion into
+// one mixed-precision instruction that rounds the exact result once, which differs from the two-step result on
+// double-rounding ties.
+__device__ __forceinline__ __half f32_to_f16(float x) {
+    asm volatile("" : "+v"(x));
+    return __float2half_rn(x);
+}
+
+__device__ __forceinline__ void store_word_stream(__half* row, int w, const float4& a) {
+    const __half2 lo = __halves2half2(f32_to_f16(a.x), f32_to_f16(a.y));
+    const __half2 hi = __halves2half2(f32_to_f16(a.z), f32_to_f16(a.w));
+    uint2 o;
+    o.x = *reinterpret_cast<const uint32_t*>(&lo);
+    o.y = *reinterpret_cast<const uint32_t*>(&hi);
+    store_stream(reinterpret_cast<uint2*>(row) + w, o);
+}
+
+__device__ __forceinline__ void copy_word_stream(const __half* src, __half* dst, int w) {
+    store_stream(reinterpret_cast<uint2*>(dst) + w, reinterpret_cast<const uint2*>(src)[w]);
 }
 
 // Bit copy of one word (no conversion, so NaN payloads survive).

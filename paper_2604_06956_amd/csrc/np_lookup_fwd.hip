@@ -92,19 +92,25 @@ fwd_pool_kernel(const TabT* __restrict__ table, int dim, const int64_t* __restri
     }
 }
 
-// Pooling over a bf16 table whose rows are a multiple of 8 elements wide: a lane owns 8 consecutive elements (one
+// Pooling over a 16-bit (bf16 or fp16) table whose rows are a multiple of 8 elements wide: a lane owns 8 consecutive elements (one
 // 16-byte load per row, as wide as an fp32 lane's), L8 lanes share a row, so a wave keeps twice as many rows in
 // flight as with 8-byte lanes.  Same walk and same order of additions as fwd_pool_kernel.
-__device__ __forceinline__ void widen8(const uint4& u, float4& a, float4& b) {
+__device__ __forceinline__ void widen8(const __half*, const uint4& u, float4& a, float4& b) {
+    const __half2* h = reinterpret_cast<const __half2*>(&u);
+    a = make_float4(__low2float(h[0]), __high2float(h[0]), __low2float(h[1]), __high2float(h[1]));
+    b = make_float4(__low2float(h[2]), __high2float(h[2]), __low2float(h[3]), __high2float(h[3]));
+}
+
+__device__ __forceinline__ void widen8(const uint16_t*, const uint4& u, float4& a, float4& b) {
     a = make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
                     __uint_as_float(u.y & 0xFFFF0000u));
     b = make_float4(__uint_as_float(u.z << 16), __uint_as_float(u.z & 0xFFFF0000u), __uint_as_float(u.w << 16),
                     __uint_as_float(u.w & 0xFFFF0000u));
 }
 
-template <int L8, int NV8, bool MEAN, typename OutT>
+template <int L8, int NV8, bool MEAN, typename OutT, typename TabT>
 __global__ void __launch_bounds__(256)
-fwd_pool_bf16x8_kernel(const uint16_t* __restrict__ table, int dim, const int64_t* __restrict__ list_keys,
+fwd_pool_x8_kernel(const TabT* __restrict__ table, int dim, const int64_t* __restrict__ list_keys,
                        const int32_t* __restrict__ idx, const int32_t* __restrict__ bag_offsets, int num_bags, OutT* __restrict__ out) {
     constexpr int GPB = 256 / L8;
     const int r = threadIdx.x % L8;
@@ -142,7 +148,7 @@ fwd_pool_bf16x8_kernel(const uint16_t* __restrict__ table, int dim, const int64_
 #pragma unroll
                 for (int v = 0; v < NV8; ++v) {  // rows that were not loaded are zeros
                     float4 a, c;
-                    widen8(x[q][v], a, c);
+                    widen8(table, x[q][v], a, c);
                     acc[v][0].x += a.x;
                     acc[v][0].y += a.y;
                     acc[v][0].z += a.z;
@@ -176,25 +182,25 @@ fwd_pool_bf16x8_kernel(const uint16_t* __restrict__ table, int dim, const int64_
     }
 }
 
-template <int L8, int NV8>
-void fwd_pool_bf16x8_launch(const uint16_t* table, int dim, const int64_t* list_keys, const int32_t* idx, const int32_t* bag_offsets,
+template <int L8, int NV8, typename TabT>
+void fwd_pool_x8_launch(const TabT* table, int dim, const int64_t* list_keys, const int32_t* idx, const int32_t* bag_offsets,
                             int num_bags, int mode, int out_dtype, void* out, hipStream_t stream) {
     constexpr int GPB = 256 / L8;
     const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(num_bags) + GPB - 1) / GPB);
     const bool mean = mode == NP_POOL_MEAN;
     if (out_dtype == NP_BF16) {
         if (mean)
-            NP_LAUNCH("fwd_pool", (fwd_pool_bf16x8_kernel<L8, NV8, true, uint16_t>), dim3(grid), dim3(256), 0, stream, table, dim,
+            NP_LAUNCH("fwd_pool", (fwd_pool_x8_kernel<L8, NV8, true, uint16_t, TabT>), dim3(grid), dim3(256), 0, stream, table, dim,
                       list_keys, idx, bag_offsets, num_bags, static_cast<uint16_t*>(out));
         else
-            NP_LAUNCH("fwd_pool", (fwd_pool_bf16x8_kernel<L8, NV8, false, uint16_t>), dim3(grid), dim3(256), 0, stream, table, dim,
+            NP_LAUNCH("fwd_pool", (fwd_pool_x8_kernel<L8, NV8, false, uint16_t, TabT>), dim3(grid), dim3(256), 0, stream, table, dim,
                       list_keys, idx, bag_offsets, num_bags, static_cast<uint16_t*>(out));
     } else {
         if (mean)
-            NP_LAUNCH("fwd_pool", (fwd_pool_bf16x8_kernel<L8, NV8, true, float>), dim3(grid), dim3(256), 0, stream, table, dim,
+            NP_LAUNCH("fwd_pool", (fwd_pool_x8_kernel<L8, NV8, true, float, TabT>), dim3(grid), dim3(256), 0, stream, table, dim,
                       list_keys, idx, bag_offsets, num_bags, static_cast<float*>(out));
         else
-            NP_LAUNCH("fwd_pool", (fwd_pool_bf16x8_kernel<L8, NV8, false, float>), dim3(grid), dim3(256), 0, stream, table, dim,
+            NP_LAUNCH("fwd_pool", (fwd_pool_x8_kernel<L8, NV8, false, float, TabT>), dim3(grid), dim3(256), 0, stream, table, dim,
                       list_keys, idx, bag_offsets, num_bags, static_cast<float*>(out));
     }
 }
@@ -424,6 +430,23 @@ void fwd_dispatch(const FwdArgs& a) {
     else fwd_launch<64, 4, TabT>(a);
 }
 
+// A table of 16-bit elements: the full-width pooled route where the row shape allows, the generic kernels otherwise
+// (sequence mode, narrow or odd rows, and the optional rows_out copy).
+template <typename TabT>
+void fwd_16bit(FwdArgs a, const TabT* t) {
+    if (a.mode != NP_SEQ && a.dim % 8 == 0 && a.dim >= 32 && a.num_bags > 0 && aligned(t, 16)) {
+        const int chunks = a.dim / 8;
+        if (chunks <= 4) fwd_pool_x8_launch<4, 1>(t, a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, a.mode, a.out_dtype, a.out, a.stream);
+        else if (chunks <= 8) fwd_pool_x8_launch<8, 1>(t, a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, a.mode, a.out_dtype, a.out, a.stream);
+        else if (chunks <= 16) fwd_pool_x8_launch<16, 1>(t, a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, a.mode, a.out_dtype, a.out, a.stream);
+        else if (chunks <= 32) fwd_pool_x8_launch<32, 1>(t, a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, a.mode, a.out_dtype, a.out, a.stream);
+        else if (chunks <= 64) fwd_pool_x8_launch<64, 1>(t, a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, a.mode, a.out_dtype, a.out, a.stream);
+        else fwd_pool_x8_launch<64, 2>(t, a.dim, a.list_keys, a.idx, a.bag_offsets, a.num_bags, a.mode, a.out_dtype, a.out, a.stream);
+        a.num_bags = 0;  // what remains for the generic launcher is rows_out
+    }
+    fwd_dispatch<TabT>(a);
+}
+
 }  // namespace np
 
 extern "C" {
@@ -437,34 +460,25 @@ int np_lookup_fwd_t(const void* table, int32_t table_dtype, int64_t num_rows, in
     (void)ws;
     (void)ws_bytes;
     if (!table || num_rows < 1 || num_bags < 0 || n < 0 || cap < 0 || !bag_offsets) return NP_ERR_INVALID_ARG;
-    if (table_dtype != NP_F32 && table_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
+    if (table_dtype != NP_F32 && table_dtype != NP_BF16 && table_dtype != NP_F16) return NP_ERR_INVALID_ARG;
     if (mode != NP_POOL_SUM && mode != NP_POOL_MEAN && mode != NP_SEQ) return NP_ERR_INVALID_ARG;
     if (out_dtype != NP_F32 && out_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
     if (mode == NP_SEQ && max_len < 1) return NP_ERR_INVALID_ARG;
     if (dim < 4 || dim % 4 != 0 || dim > NP_MAX_DIM) return NP_ERR_UNSUPPORTED;
     if ((num_bags > 0 && !out) || (n > 0 && !list_keys)) return NP_ERR_INVALID_ARG;
     if (rows_out && (!d_num_list || !list_keys)) return NP_ERR_INVALID_ARG;
-    const size_t row_align = table_dtype == NP_BF16 ? 8 : 16;
+    const size_t row_align = table_dtype == NP_F32 ? 16 : 8;
     if (!np::aligned(table, row_align) || !np::aligned(out, out_dtype == NP_BF16 ? 8 : 16) || !np::aligned(rows_out, row_align))
         return NP_ERR_INVALID_ARG;
     if (mode == NP_SEQ && static_cast<int64_t>(num_bags) * max_len > INT32_MAX) return NP_ERR_UNSUPPORTED;
     np::FwdArgs a{table, dim, list_keys, d_num_list, cap, idx, bag_offsets, num_bags, mode, max_len, out_dtype, out, rows_out,
                   static_cast<hipStream_t>(stream)};
     if (table_dtype == NP_BF16) {
-        if (mode != NP_SEQ && dim % 8 == 0 && dim >= 32 && num_bags > 0 && np::aligned(table, 16)) {
-            // full-width route: 16-byte loads of 8 bf16 each; rows_out, if asked for, still goes through the generic launcher
-            hipStream_t st = static_cast<hipStream_t>(stream);
-            const uint16_t* t = static_cast<const uint16_t*>(table);
-            const int chunks = dim / 8;
-            if (chunks <= 4) np::fwd_pool_bf16x8_launch<4, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
-            else if (chunks <= 8) np::fwd_pool_bf16x8_launch<8, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
-            else if (chunks <= 16) np::fwd_pool_bf16x8_launch<16, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
-            else if (chunks <= 32) np::fwd_pool_bf16x8_launch<32, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
-            else if (chunks <= 64) np::fwd_pool_bf16x8_launch<64, 1>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
-            else np::fwd_pool_bf16x8_launch<64, 2>(t, dim, list_keys, idx, bag_offsets, num_bags, mode, out_dtype, out, st);
-            a.num_bags = 0;
-        }
-        np::fwd_dispatch<uint16_t>(a);
+        np::fwd_16bit<uint16_t>(a, static_cast<const uint16_t*>(table));
+        return np::launch_status();
+    }
+    if (table_dtype == NP_F16) {
+        np::fwd_16bit<__half>(a, static_cast<const __half*>(table));
         return np::launch_status();
     }
     if (mode == NP_SEQ && out_dtype == NP_BF16 && dim % 8 == 0 && num_bags > 0 && np::aligned(out, 16)) {

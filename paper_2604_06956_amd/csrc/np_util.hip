@@ -52,7 +52,12 @@ __device__ __forceinline__ float table_init_value(uint64_t e, uint64_t seed_term
     return static_cast<float>(q) * (0.01f / 8388608.0f);
 }
 
-// TabT = float: the value itself; TabT = uint16_t: the value rounded to bf16 (nearest even).
+// What a value reads back as after being stored in a table of the given element type.
+__device__ __forceinline__ float as_stored(const float*, float v) { return v; }
+__device__ __forceinline__ float as_stored(const uint16_t*, float v) { return bf16_to_f32(f32_to_bf16(v)); }
+__device__ __forceinline__ float as_stored(const __half*, float v) { return __half2float(f32_to_f16(v)); }
+
+// TabT = float: the value itself; uint16_t: rounded to bf16; __half: rounded to fp16 (nearest even).
 template <typename TabT>
 __global__ void __launch_bounds__(256) table_init_kernel(TabT* __restrict__ table, uint64_t num_words, uint64_t seed_term) {
     const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
@@ -73,7 +78,6 @@ template <typename TabT>
 __global__ void __launch_bounds__(256)
 table_count_changed_kernel(const TabT* __restrict__ table, uint64_t num_rows, int words_per_row, uint64_t seed_term,
                            unsigned long long* __restrict__ count) {
-    constexpr bool kBf16 = sizeof(TabT) == 2;
     const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
     unsigned long long local = 0;
     for (uint64_t row = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; row < num_rows; row += stride) {
@@ -85,7 +89,7 @@ table_count_changed_kernel(const TabT* __restrict__ table, uint64_t num_rows, in
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 float v = table_init_value(w * 4 + c, seed_term);
-                if (kBf16) v = bf16_to_f32(f32_to_bf16(v));
+                v = as_stored(static_cast<const TabT*>(nullptr), v);
                 changed |= __float_as_uint(v) != __float_as_uint(got[c]);
             }
         }
@@ -120,8 +124,8 @@ const char* np_status_string(int status) {
 }
 
 int np_util_table_init_t(void* table, int32_t table_dtype, int64_t num_rows, int32_t dim, uint64_t seed, void* stream) {
-    if (table_dtype != NP_F32 && table_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
-    if (!table || num_rows < 0 || dim < 4 || dim % 4 != 0 || !np::aligned(table, table_dtype == NP_BF16 ? 8 : 16))
+    if (table_dtype != NP_F32 && table_dtype != NP_BF16 && table_dtype != NP_F16) return NP_ERR_INVALID_ARG;
+    if (!table || num_rows < 0 || dim < 4 || dim % 4 != 0 || !np::aligned(table, table_dtype == NP_F32 ? 16 : 8))
         return NP_ERR_INVALID_ARG;
     const uint64_t words = static_cast<uint64_t>(num_rows) * static_cast<uint64_t>(dim) / 4;
     if (words == 0) return NP_OK;
@@ -132,6 +136,8 @@ int np_util_table_init_t(void* table, int32_t table_dtype, int64_t num_rows, int
     if (table_dtype == NP_BF16)
         NP_LAUNCH("table_init", np::table_init_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, static_cast<uint16_t*>(table), words,
                   seed_term);
+    else if (table_dtype == NP_F16)
+        NP_LAUNCH("table_init", np::table_init_kernel<__half>, dim3(grid), dim3(256), 0, s, static_cast<__half*>(table), words, seed_term);
     else
         NP_LAUNCH("table_init", np::table_init_kernel<float>, dim3(grid), dim3(256), 0, s, static_cast<float*>(table), words, seed_term);
     return np::launch_status();
@@ -143,8 +149,8 @@ int np_util_table_init(float* table, int64_t num_rows, int32_t dim, uint64_t see
 
 int np_util_table_count_changed_t(const void* table, int32_t table_dtype, int64_t num_rows, int32_t dim, uint64_t seed,
                                   unsigned long long* d_count, void* stream) {
-    if (table_dtype != NP_F32 && table_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
-    if (!table || !d_count || num_rows < 0 || dim < 4 || dim % 4 != 0 || !np::aligned(table, table_dtype == NP_BF16 ? 8 : 16))
+    if (table_dtype != NP_F32 && table_dtype != NP_BF16 && table_dtype != NP_F16) return NP_ERR_INVALID_ARG;
+    if (!table || !d_count || num_rows < 0 || dim < 4 || dim % 4 != 0 || !np::aligned(table, table_dtype == NP_F32 ? 16 : 8))
         return NP_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     NP_LAUNCH("zero_u64", np::zero_u64_kernel, dim3(1), dim3(64), 0, s, d_count);
@@ -155,6 +161,9 @@ int np_util_table_count_changed_t(const void* table, int32_t table_dtype, int64_
         if (table_dtype == NP_BF16)
             NP_LAUNCH("table_count_changed", np::table_count_changed_kernel<uint16_t>, dim3(grid), dim3(256), 0, s,
                       static_cast<const uint16_t*>(table), static_cast<uint64_t>(num_rows), dim / 4, seed_term, d_count);
+        else if (table_dtype == NP_F16)
+            NP_LAUNCH("table_count_changed", np::table_count_changed_kernel<__half>, dim3(grid), dim3(256), 0, s,
+                      static_cast<const __half*>(table), static_cast<uint64_t>(num_rows), dim / 4, seed_term, d_count);
         else
             NP_LAUNCH("table_count_changed", np::table_count_changed_kernel<float>, dim3(grid), dim3(256), 0, s,
                       static_cast<const float*>(table), static_cast<uint64_t>(num_rows), dim / 4, seed_term, d_count);

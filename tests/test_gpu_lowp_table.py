@@ -1,8 +1,9 @@
-"""GPU parity of the bf16-table variant (np_lookup_fwd_t, np_sparse_adagrad_t, the dtype-generic harness calls) against
-the CPU oracle.  Reading a bf16 row is exact, so forward results carry the fp32 bar (1e-5 against the sum of absolute
-terms; copies bit exact).  An updated row is a value rounded to bf16: the bar is the bf16 one (1e-2), and on top of it
-all but a tiny fraction of the elements must carry the oracle's bit pattern, the others the pattern next to it (the two
-sides round values that agree to fp32 precision, so they part only where such a value sits on a rounding boundary)."""
+"""GPU parity of the 16-bit-table variants, bf16 and fp16 (np_lookup_fwd_t, np_sparse_adagrad_t, the dtype-generic
+harness calls) against the CPU oracle.  Reading a 16-bit row is exact, so forward results carry the fp32 bar (1e-5
+against the sum of absolute terms; copies bit exact).  An updated row is a value rounded to the storage format: the bar
+is 1e-2 for bf16 (the stated one) and 2e-3 for fp16 (two of its 2^-10 spacings), and on top of it all but a tiny
+fraction of the elements must carry the oracle's bit pattern, the others the pattern next to it (the two sides round
+values that agree to fp32 precision, so they part only where such a value sits on a rounding boundary)."""
 import numpy as np
 import pytest
 
@@ -18,22 +19,54 @@ def H():
     return gpu_helpers
 
 
-def _to_bits(a32):
+class _Kind:
+    """One 16-bit storage format: conversions through library routines (torch / numpy), the oracle's entry points."""
+
+    def __init__(self, name):
+        import torch
+        self.name = name
+        self.torch_dtype = torch.bfloat16 if name == "bf16" else torch.float16
+        self.rtol = 1e-2 if name == "bf16" else 2e-3
+
+    def to_bits(self, a):
+        import torch
+        a = np.ascontiguousarray(a, np.float32)
+        if self.name == "bf16":
+            return torch.from_numpy(a).bfloat16().view(torch.int16).numpy().view(np.uint16).copy()
+        return a.astype(np.float16).view(np.uint16).copy()
+
+    def widen(self, bits):
+        if self.name == "bf16":
+            return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+        return bits.view(np.float16).astype(np.float32)
+
+    def dev(self, bits):
+        import torch
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(self.torch_dtype)
+
+    def oracle_table(self, bits):
+        return bits if self.name == "bf16" else bits.view(np.float16)
+
+    def oracle_adagrad(self, O):
+        return O.sparse_adagrad_bf16 if self.name == "bf16" else O.sparse_adagrad_f16
+
+
+@pytest.fixture(params=["bf16", "f16"])
+def K(request):
+    return _Kind(request.param)
+
+
+def _host_bits(t):
     import torch
-    return torch.from_numpy(np.ascontiguousarray(a32, np.float32)).bfloat16().view(torch.int16).numpy().view(np.uint16).copy()
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def _dev_bf16(bits):
-    import torch
-    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
-
-
-def _assert_bf16_rows(H, got_bits, ref_bits, scale, what):
-    got, ref = H.O.bf16_bits_to_f32(got_bits), H.O.bf16_bits_to_f32(ref_bits)
-    H.assert_close(got, ref, scale, H.RTOL_BF16, what)
+def _assert_rows(H, K, got_bits, ref_bits, scale, what):
+    got, ref = K.widen(got_bits), K.widen(ref_bits)
+    H.assert_close(got, ref, scale, K.rtol, what)
     diff = got_bits != ref_bits
     frac = float(diff.mean()) if diff.size else 0.0
-    assert frac < 2e-3, f"{what}: {frac:.2e} of the elements differ from the oracle's bf16 pattern"
+    assert frac < 2e-3, f"{what}: {frac:.2e} of the elements differ from the oracle's bit pattern"
     # away from cancellation (result not much smaller than its terms) a differing element is the neighbouring pattern
     big = diff & (np.abs(ref) > 0.05 * scale)
     if big.any():
@@ -48,13 +81,13 @@ def _bags(rng, B, max_l, R):
     return off, keys
 
 
-def test_table_init_bf16_is_the_rounded_generator(H):
+def test_table_init_is_the_rounded_generator(H, K):
     import torch
     for R, D in ((1000, 16), (777, 64), (50, 128), (3, 4)):
-        t = torch.empty((R, D), dtype=torch.bfloat16, device="cuda")
+        t = torch.empty((R, D), dtype=K.torch_dtype, device="cuda")
         H.B.np_util_table_init_t(t, 7)
-        ref = _to_bits(H.wl.table_init_rows(np.arange(R), D, 7))
-        assert np.array_equal(H.host(t), ref)
+        ref = K.to_bits(H.wl.table_init_rows(np.arange(R), D, 7))
+        assert np.array_equal(_host_bits(t), ref)
         assert H.B.np_util_table_count_changed_t(t, 7) == 0
         t[R // 2, D - 1] = 1.0
         t[0, 0] = 1.0
@@ -66,18 +99,18 @@ def test_table_init_bf16_is_the_rounded_generator(H):
 
 @pytest.mark.parametrize("dim", [4, 8, 16, 48, 64, 128, 256, 512, 1024])
 @pytest.mark.parametrize("mode", [0, 1])
-def test_fwd_pooled_bf16_table(H, dim, mode):
+def test_fwd_pooled_16bit_table(H, K, dim, mode):
     import torch
     rng = np.random.default_rng(dim * 5 + mode)
     R, Bn = 3000, 1237
-    tbits = _to_bits(rng.standard_normal((R, dim)))
+    tbits = K.to_bits(rng.standard_normal((R, dim)))
     off, keys = _bags(rng, Bn, 70 if dim <= 128 else 9, R)
     unique, inverse, *_ = H.O.dedup(keys)
-    ref, _, ab = H.O.lookup_fwd(tbits, unique, inverse, off, mode, want_abs=True)
-    tab = _dev_bf16(tbits)
+    ref, _, ab = H.O.lookup_fwd(K.oracle_table(tbits), unique, inverse, off, mode, want_abs=True)
+    tab = K.dev(tbits)
     out, _ = H.B.np_lookup_fwd_t(tab, H.dev(unique), H.dev(inverse), H.dev(off), keys.shape[0], mode)
     torch.cuda.synchronize()
-    H.assert_close(H.host(out), ref, ab, H.RTOL_F32, f"fwd pooled bf16 table dim={dim} mode={mode}")
+    H.assert_close(H.host(out), ref, ab, H.RTOL_F32, f"fwd pooled {K.name} table dim={dim} mode={mode}")
     assert not H.host(out)[np.diff(off) == 0].any()
     out2, _ = H.B.np_lookup_fwd_t(tab, H.dev(keys), None, H.dev(off), keys.shape[0], mode)
     torch.cuda.synchronize()
@@ -89,33 +122,33 @@ def test_fwd_pooled_bf16_table(H, dim, mode):
 
 
 @pytest.mark.parametrize("dim", [16, 128, 512])
-def test_fwd_seq_and_rows_out_bf16_table_bit_exact(H, dim):
+def test_fwd_seq_and_rows_out_16bit_table_bit_exact(H, K, dim):
     import torch
     rng = np.random.default_rng(dim + 11)
     R, Bn = 5000, 211
-    tbits = _to_bits(rng.standard_normal((R, dim)))
+    tbits = K.to_bits(rng.standard_normal((R, dim)))
     off, keys = _bags(rng, Bn, 37, R)
     max_len = int(np.diff(off).max())
     unique, inverse, *_ = H.O.dedup(keys)
     U = unique.shape[0]
-    tab = _dev_bf16(tbits)
+    tab = K.dev(tbits)
     for dt in (H.B.BF16, H.B.F32):
-        ref, rows, _ = H.O.lookup_fwd(tbits, unique, inverse, off, 2, max_len, dt, want_rows=True)
+        ref, rows, _ = H.O.lookup_fwd(K.oracle_table(tbits), unique, inverse, off, 2, max_len, dt, want_rows=True)
         out = torch.full((Bn, max_len, dim), 7.0, dtype=torch.bfloat16 if dt == H.B.BF16 else torch.float32, device="cuda")
         out, rows_g = H.B.np_lookup_fwd_t(tab, H.dev(unique), H.dev(inverse), H.dev(off), keys.shape[0], 2, max_len, dt,
                                           num_list=H.dev(np.array([U], np.int32)), cap=U + 5, want_rows=True, out=out)
         torch.cuda.synchronize()
         assert H.host(out).tobytes() == ref.tobytes()
-        assert rows_g.dtype == torch.bfloat16
-        assert np.array_equal(H.O.bf16_bits_to_f32(H.host(rows_g)[:U]), rows)
+        assert rows_g.dtype == K.torch_dtype
+        assert np.array_equal(K.widen(_host_bits(rows_g)[:U]), rows)
 
 
 @pytest.mark.parametrize("dim", [4, 16, 64, 128, 512, 1024])
-def test_adagrad_bf16_table(H, dim):
+def test_adagrad_16bit_table(H, K, dim):
     import torch
     rng = np.random.default_rng(dim + 3)
     R, U = 20000, 6000
-    t0 = _to_bits(rng.standard_normal((R, dim)) * 0.01)
+    t0 = K.to_bits(rng.standard_normal((R, dim)) * 0.01)
     s0 = (rng.random(R) * 0.1).astype(np.float32)
     s0[::3] = 0
     keys = rng.permutation(np.sort(rng.choice(R, size=U, replace=False))).astype(np.int64)
@@ -123,18 +156,18 @@ def test_adagrad_bf16_table(H, dim):
     grads[5] = 0.0
     s0[keys[5]] = 0.0
     tr, sr = t0.copy(), s0.copy()
-    H.O.sparse_adagrad_bf16(tr, sr, keys, grads, 0.01, 1e-8)
-    tg, sg = _dev_bf16(t0), H.dev(s0)
+    K.oracle_adagrad(H.O)(tr, sr, keys, grads, 0.01, 1e-8)
+    tg, sg = K.dev(t0), H.dev(s0)
     gbuf = np.zeros((U + 50, dim), np.float32)
     gbuf[:U] = grads
     kbuf = np.zeros(U + 50, np.int64)
     kbuf[:U] = keys
     H.B.np_sparse_adagrad_t(tg, sg, H.dev(kbuf), H.dev(gbuf), H.dev(np.array([U], np.int32)), U + 50, 0.01, 1e-8)
     torch.cuda.synchronize()
-    tgot, sgot = H.host(tg), H.host(sg)
-    w0 = H.O.bf16_bits_to_f32(t0).astype(np.float64)
-    delta = np.abs(H.O.bf16_bits_to_f32(tr).astype(np.float64) - w0)
-    _assert_bf16_rows(H, tgot[keys], tr[keys], np.abs(w0[keys]) + delta[keys], f"updated bf16 rows dim={dim}")
+    tgot, sgot = _host_bits(tg), H.host(sg)
+    w0 = K.widen(t0).astype(np.float64)
+    delta = np.abs(K.widen(tr).astype(np.float64) - w0)
+    _assert_rows(H, K, tgot[keys], tr[keys], np.abs(w0[keys]) + delta[keys], f"updated {K.name} rows dim={dim}")
     H.assert_close(sgot[keys], sr[keys], np.abs(sr[keys]), H.RTOL_F32, "updated state")
     rest = np.setdiff1d(np.arange(R), keys)
     assert np.array_equal(tgot[rest], t0[rest]) and sgot[rest].tobytes() == s0[rest].tobytes()
@@ -155,7 +188,9 @@ def test_bad_table_dtype_and_alignment_are_refused(H):
     args = (16, 8, k.data_ptr(), 0, 0, 0, off.data_ptr(), 2, 4, 0, 1, 0, out.data_ptr(), 0, 0, 0, st)
     assert L.np_lookup_fwd_t(t.data_ptr(), 7, *args) == -1
     assert L.np_lookup_fwd_t(t.data_ptr() + 2, 1, *args) == -1
+    assert L.np_lookup_fwd_t(t.data_ptr() + 4, 2, *args) == -1
     assert L.np_lookup_fwd_t(t.data_ptr(), 1, *args) == 0
+    assert L.np_lookup_fwd_t(t.data_ptr(), 2, *args) == 0
     assert L.np_sparse_adagrad_t(t.data_ptr(), 5, s.data_ptr(), 16, 8, k.data_ptr(), g.data_ptr(), one.data_ptr(), 1, 0.01, 1e-8,
                                  st) == -1
     assert L.np_sparse_adagrad_t(t.data_ptr() + 4, 1, s.data_ptr(), 16, 8, k.data_ptr(), g.data_ptr(), one.data_ptr(), 1, 0.01,
@@ -165,17 +200,16 @@ def test_bad_table_dtype_and_alignment_are_refused(H):
     assert not H.host(out).any() and not H.host(t).any()
 
 
-def _step_bf16(H, cfg, steps, table=None, compact=False):
+def _step_16bit(H, K, cfg, steps):
     """`steps` consecutive batches through dedup -> route -> np_lookup_fwd_t -> np_lookup_bwd -> np_sparse_adagrad_t on a
-    bf16 table.  Each call is held against the oracle on the inputs the GPU call had (the rows the GPU holds before the
+    16-bit table.  Each call is held against the oracle on the inputs the GPU call had (the rows the GPU holds before the
     step), so rounding differences do not leak from one step into the next."""
     import torch
     wl, O, B = H.wl, H.O, H.B
     R, D, S = cfg.num_rows, cfg.dim, cfg.num_shards
     seq = cfg.mode == wl.SEQ
     dt = O.BF16 if seq else O.F32
-    if table is None:
-        table = torch.empty((R, D), dtype=torch.bfloat16, device="cuda")
+    table = torch.empty((R, D), dtype=K.torch_dtype, device="cuda")
     B.np_util_table_init_t(table, cfg.table_seed)
     state = torch.zeros(R, dtype=torch.float32, device="cuda")
     prev = None
@@ -190,7 +224,7 @@ def _step_bf16(H, cfg, steps, table=None, compact=False):
         U = unique.shape[0]
         send_keys, _, _, sfu, uts = O.route(unique, S, cfg.shard_fn)
         l2s = O.compose(inverse, uts)
-        rows_before = H.host(table[H.dev(unique)])           # [U, D] bf16 bits as the GPU holds them, compact
+        rows_before = _host_bits(table[H.dev(unique)])       # [U, D] bit patterns as the GPU holds them, compact
         state_before = H.host(state[H.dev(unique)])
         d = B.np_dedup(keys_d, cfg.key_bits)
         r = B.np_route(d["unique"], d["num_unique"], n, S, cfg.shard_fn, inverse=d["inverse"], n=n)
@@ -202,39 +236,40 @@ def _step_bf16(H, cfg, steps, table=None, compact=False):
         torch.cuda.synchronize()
         assert int(d["num_unique"].item()) == U and np.array_equal(H.host(r["send_keys"])[:U], send_keys)
         list_c = sfu.astype(np.int64)                         # send slot -> row of the compact table
-        out_ref, _, ab = O.lookup_fwd(rows_before, list_c, l2s, batch.bag_offsets, cfg.mode, max_len, dt, want_abs=not seq)
+        out_ref, _, ab = O.lookup_fwd(K.oracle_table(rows_before), list_c, l2s, batch.bag_offsets, cfg.mode, max_len, dt, want_abs=not seq)
         if seq:
             assert H.host(out).tobytes() == out_ref.tobytes()
         else:
-            H.assert_close(H.host(out), out_ref, ab, H.RTOL_F32, f"{cfg.name} step {t} forward (bf16 table)")
+            H.assert_close(H.host(out), out_ref, ab, H.RTOL_F32, f"{cfg.name} step {t} forward ({K.name} table)")
         g_gpu = H.host(grads)[:U]
         rows_ref, state_ref = rows_before.copy(), state_before.copy()
-        O.sparse_adagrad_bf16(rows_ref, state_ref, list_c, g_gpu, cfg.lr, cfg.eps)
-        rows_after = H.host(table[H.dev(unique)])
-        w0 = O.bf16_bits_to_f32(rows_before).astype(np.float64)
-        delta = np.abs(O.bf16_bits_to_f32(rows_ref).astype(np.float64) - w0)
-        _assert_bf16_rows(H, rows_after, rows_ref, np.abs(w0) + delta, f"{cfg.name} step {t} updated bf16 rows")
+        K.oracle_adagrad(O)(rows_ref, state_ref, list_c, g_gpu, cfg.lr, cfg.eps)
+        rows_after = _host_bits(table[H.dev(unique)])
+        w0 = K.widen(rows_before).astype(np.float64)
+        delta = np.abs(K.widen(rows_ref).astype(np.float64) - w0)
+        _assert_rows(H, K, rows_after, rows_ref, np.abs(w0) + delta, f"{cfg.name} step {t} updated {K.name} rows")
         H.assert_close(H.host(state[H.dev(unique)]), state_ref, np.abs(state_ref), H.RTOL_F32, f"{cfg.name} step {t} state")
         # rows outside the batches keep their bits, everywhere in the table
         touched = np.union1d(touched, unique)
-        rows_all = H.host(table[H.dev(touched)])
-        init_all = _to_bits(wl.table_init_rows(touched, D, cfg.table_seed))
+        rows_all = _host_bits(table[H.dev(touched)])
+        init_all = K.to_bits(wl.table_init_rows(touched, D, cfg.table_seed))
         changed = int(np.any(rows_all != init_all, axis=1).sum())
         assert B.np_util_table_count_changed_t(table, cfg.table_seed) == changed
         assert changed > 0.5 * touched.size
-        H.progress(f"[{cfg.name} bf16 table] step {t}: U={U} ok")
+        H.progress(f"[{cfg.name} {K.name} table] step {t}: U={U} ok")
 
 
-def test_step_tiny_bf16_table(H):
-    _step_bf16(H, H.wl.config("tiny"), steps=2)
+def test_step_tiny_16bit_table(H, K):
+    _step_16bit(H, K, H.wl.config("tiny"), steps=2)
 
 
 @pytest.mark.parametrize("name,row_div,batch_div", [("dlrm", 64, 16), ("seq", 256, 64), ("skew", 128, 16), ("large", 2048, 64)])
-def test_step_scaled_configs_bf16_table(H, name, row_div, batch_div):
-    _step_bf16(H, H.wl.scaled(H.wl.config(name), row_div, batch_div), steps=2)
+def test_step_scaled_configs_16bit_table(H, K, name, row_div, batch_div):
+    _step_16bit(H, K, H.wl.scaled(H.wl.config(name), row_div, batch_div), steps=2)
 
 
 @pytest.mark.timeout(900)
-def test_full_large_bf16_table_one_batch(H):
-    """Configuration 5 at full size with the table in bf16 (102 GB)."""
-    _step_bf16(H, H.wl.config("large"), steps=1)
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+def test_full_large_16bit_table_one_batch(H, kind):
+    """Configuration 5 at full size with the table in 16 bits (102 GB)."""
+    _step_16bit(H, _Kind(kind), H.wl.config("large"), steps=1)
