@@ -64,7 +64,7 @@ def main() -> int:
     ap.add_argument("--table-dtype", choices=("f32", "bf16", "f16"), default="f32",
                     help="storage type of the table; bf16 / f16 run np_lookup_fwd_t / np_sparse_adagrad_t (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-div", type=int, default=4)
+    ap.add_argument("--cpu-sample-div", type=int, default=2)
     ap.add_argument("--fwp-report", action="store_true",
                     help="also dedup batch 0 split into N micro-batches of consecutive samples and report sum(U_i)/U")
     args = ap.parse_args()
