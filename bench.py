@@ -48,7 +48,7 @@ def algorithmic_bytes(n: int, U: int, B: int, D: int, S: int, mode: int, max_len
 # HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the copy-kernel
 # calibration; see profiles/large_step_kernels.txt), keyed by (workload, kernel).  Static: bench.py cannot run
 # the profiler on itself.
-MEASURED_TRAFFIC = {("large", "bwd_main"): 14.66e9, ("large", "fwd_pool"): 9.64e9, ("large", "sparse_adagrad"): 8.39e9}
+MEASURED_TRAFFIC = {("large", "bwd_main"): 14.59e9, ("large", "fwd_pool"): 9.52e9, ("large", "sparse_adagrad"): 8.38e9}
 
 # the kernel that carries (nearly all of) each call's algorithmic bytes
 KERNEL_OF_CALL = {"sparse_adagrad": "np_sparse_adagrad", "bwd_main": "np_lookup_bwd", "fwd_pool": "np_lookup_fwd",
