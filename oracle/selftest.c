@@ -2,13 +2,15 @@
  * Stand-alone self-check of the CPU oracle (test infrastructure), meant to be built with the address and
  * undefined-behaviour sanitizers:
  *     gcc -std=c11 -g -fsanitize=address,undefined -static-libasan oracle/np_oracle.c oracle/selftest.c -lm
- * It runs the oracle on small pseudo-random inputs and checks four properties that any correct
+ * It runs the oracle on small pseudo-random inputs and checks five properties that any correct
  * implementation of the path has:
  *   1. the inverse indices reconstruct the input keys;
  *   2. the per-shard splits sum to the number of distinct keys, and every key sits in its owner's segment;
  *   3. pooled outputs equal a brute-force loop;
  *   4. two consecutive batches with overlapping keys, run as lookup -> update -> lookup, give the sequential
  *      result, and rows outside the first batch keep their bits (Eq. (2)).
+ *   5. 16-bit tables: decoding and one-step rounding are inverse to each other on every finite bf16 / fp16
+ *      pattern, rounding is monotone, and the 16-bit Adagrad step stays within half a spacing of the fp32 one.
  * Exit status 0 on success, the number of the failed check otherwise.
  */
 #include <math.h>
@@ -26,6 +28,59 @@ int np_ref_lookup_fwd(const float*, int64_t, int32_t, const int64_t*, int32_t, c
 int np_ref_lookup_bwd(const void*, int32_t, int32_t, int32_t, int32_t, const int32_t*, int32_t, int32_t, const int32_t*, int32_t,
                       const int32_t*, float*, double*);
 int np_ref_sparse_adagrad(float*, float*, int64_t, int32_t, const int64_t*, const float*, int32_t, float, float);
+int np_ref_sparse_adagrad_16(uint16_t*, int32_t, float*, int64_t, int32_t, const int64_t*, const float*, int32_t, float, float);
+uint16_t np_ref_f64_to_bf16(double);
+uint16_t np_ref_f64_to_f16(double);
+float np_ref_bf16_to_f32(uint16_t);
+float np_ref_f16_to_f32(uint16_t);
+
+static int check_16bit(void) {
+    /* every finite pattern survives decode -> round; rounding is monotone between neighbouring patterns */
+    for (int kind = 1; kind <= 2; ++kind) {
+        double prev = -INFINITY;
+        for (uint32_t h = 0; h < 0x8000u; ++h) {
+            float v = kind == 1 ? np_ref_bf16_to_f32((uint16_t)h) : np_ref_f16_to_f32((uint16_t)h);
+            if (isnan(v) || isinf(v)) continue;
+            uint16_t back = kind == 1 ? np_ref_f64_to_bf16((double)v) : np_ref_f64_to_f16((double)v);
+            if (back != h) return 5;
+            uint16_t neg = kind == 1 ? np_ref_f64_to_bf16(-(double)v) : np_ref_f64_to_f16(-(double)v);
+            if (neg != (uint16_t)(h | 0x8000u)) return 5;
+            if (h > 0 && !((double)v > prev)) return 5;
+            if (h > 0) {  /* a value just above / below the midpoint of two neighbours goes to the nearer one */
+                double mid = 0.5 * ((double)v + prev);
+                uint16_t up = kind == 1 ? np_ref_f64_to_bf16(mid * (1.0 + 1e-12)) : np_ref_f64_to_f16(mid * (1.0 + 1e-12));
+                uint16_t dn = kind == 1 ? np_ref_f64_to_bf16(mid * (1.0 - 1e-12)) : np_ref_f64_to_f16(mid * (1.0 - 1e-12));
+                if (up != h || dn != (uint16_t)(h - 1)) return 5;
+            }
+            prev = (double)v;
+        }
+    }
+    /* the 16-bit step against the fp32 step on the same (exactly representable) rows */
+    enum { R16 = 40, D16 = 8, L16 = 10 };
+    for (int kind = 1; kind <= 2; ++kind) {
+        uint16_t t16[R16 * D16];
+        float t32[R16 * D16], s16[R16], s32[R16], g[L16 * D16];
+        int64_t keys[L16];
+        for (int i = 0; i < R16 * D16; ++i) {
+            double x = ((double)((i * 2654435761u) >> 8 & 0xFFFF) / 65536.0 - 0.5) * 0.05;
+            t16[i] = kind == 1 ? np_ref_f64_to_bf16(x) : np_ref_f64_to_f16(x);
+            t32[i] = kind == 1 ? np_ref_bf16_to_f32(t16[i]) : np_ref_f16_to_f32(t16[i]);
+        }
+        for (int r = 0; r < R16; ++r) s16[r] = s32[r] = (float)(r % 3) * 0.01f;
+        for (int p = 0; p < L16; ++p) keys[p] = (p * 7) % R16;
+        for (int i = 0; i < L16 * D16; ++i) g[i] = (float)((i * 40503u) >> 4 & 0xFF) / 128.0f - 1.0f;
+        if (np_ref_sparse_adagrad_16(t16, kind, s16, R16, D16, keys, g, L16, 0.01f, 1e-8f)) return 5;
+        if (np_ref_sparse_adagrad(t32, s32, R16, D16, keys, g, L16, 0.01f, 1e-8f)) return 5;
+        for (int r = 0; r < R16; ++r)
+            if (s16[r] != s32[r]) return 5;
+        const double half_spacing = kind == 1 ? ldexp(1.0, -8) : ldexp(1.0, -11);
+        for (int i = 0; i < R16 * D16; ++i) {
+            double a = kind == 1 ? (double)np_ref_bf16_to_f32(t16[i]) : (double)np_ref_f16_to_f32(t16[i]);
+            if (fabs(a - (double)t32[i]) > fabs((double)t32[i]) * (half_spacing + 1e-6) + ldexp(1.0, -25)) return 5;
+        }
+    }
+    return 0;
+}
 
 static uint64_t rng_state = 88172645463325252ull;
 static uint32_t rnd(void) {
@@ -113,6 +168,7 @@ int main(void) {
             if (shared_moved != (memcmp(out, out2, sizeof(out)) != 0)) return 4;
         }
     }
+    if (check_16bit()) return 5;
     printf("oracle selftest ok\n");
     return 0;
 }

@@ -1,5 +1,5 @@
 """The oracle under AddressSanitizer and UndefinedBehaviorSanitizer: a stand-alone C program (oracle/selftest.c)
-linked with the oracle runs the four self-checks of the path on small inputs."""
+linked with the oracle runs the five self-checks of the path on small inputs."""
 import os
 import subprocess
 
