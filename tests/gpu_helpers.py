@@ -14,7 +14,8 @@ RTOL_BF16 = 1e-2
 
 
 def progress(msg: str) -> None:
-    """A line in gpurun_out/test_progress.log: long full-size tests stay visibly alive while pytest captures stdout."""
+    """A timestamped line in a progress log beside the test outputs: long full-size tests stay visibly alive while
+    pytest captures stdout."""
     import os
     import time
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
