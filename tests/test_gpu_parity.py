@@ -51,6 +51,12 @@ def _keys_case(name):
         return rng.integers(0, 1 << 27, size=5_000_000).astype(np.int64), 27
     if name == "bits_1":
         return rng.integers(0, 2, size=30000).astype(np.int64), 1
+    if name == "bits_32":      # the widest key that still sorts as 32 bits: values with the top bit set
+        k = rng.integers(0, 1 << 32, size=150000).astype(np.int64)
+        k[:100] = (1 << 32) - 1
+        k[100:200] = 1 << 31
+        k[200:300] = 0
+        return k, 32
     if name == "bits_33":
         return rng.integers(0, 1 << 33, size=200000).astype(np.int64), 33
     if name == "bits_40_dups":
@@ -67,7 +73,7 @@ def _keys_case(name):
 
 
 DEDUP_CASES = ["one", "all_equal", "all_distinct", "wave_edges", "tile_minus_1", "tile_exact", "tile_plus_1",
-               "multi_chunk", "bits_1", "bits_33", "bits_40_dups", "bits_63", "hot_key"]
+               "multi_chunk", "bits_1", "bits_32", "bits_33", "bits_40_dups", "bits_63", "hot_key"]
 
 
 @pytest.mark.parametrize("case", DEDUP_CASES)
