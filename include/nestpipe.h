@@ -265,9 +265,12 @@ int np_util_stream_copy(void* dst, const void* src, size_t bytes, void* stream);
  * of the library record a start and stop event (events are created on first use and reused);
  * np_prof_collect synchronises those events and copies up to `max_entries` records, in launch order, into
  * host arrays: names[i] points to a static string, ms[i] is the kernel's duration.  Returns the number of
- * records and clears the log.  Host functions; not thread safe; meant for the benchmark only.
+ * records and clears the log.  np_prof_only("a,b") restricts the timing to launches with these names (host string,
+ * copied; NULL or "" lifts the restriction), so that a timed run pays for a few events only.  Host functions; not
+ * thread safe; meant for the benchmark only.
  */
 int np_prof_enable(int on);
+int np_prof_only(const char* names /* host */);
 int np_prof_collect(const char** names /* host */, float* ms /* host */, int max_entries);
 
 #ifdef __cplusplus

@@ -84,6 +84,8 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.np_util_stream_copy.argtypes = [_vp, _vp, _sz, _vp]
     L.np_prof_enable.restype = ctypes.c_int
     L.np_prof_enable.argtypes = [ctypes.c_int]
+    L.np_prof_only.restype = ctypes.c_int
+    L.np_prof_only.argtypes = [ctypes.c_char_p]
     L.np_prof_collect.restype = ctypes.c_int
     L.np_prof_collect.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float), ctypes.c_int]
     return L
@@ -342,6 +344,12 @@ def np_util_stream_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
 
 def np_prof_enable(on: bool) -> None:
     lib.np_prof_enable(1 if on else 0)
+
+
+def np_prof_only(names) -> None:
+    """Restrict event timing to launches with these names (an iterable of str); None or empty lifts the restriction."""
+    joined = ",".join(names) if names else ""
+    lib.np_prof_only(joined.encode() if joined else None)
 
 
 def np_prof_collect(max_entries: int = 4096):

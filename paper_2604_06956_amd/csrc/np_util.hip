@@ -1,5 +1,6 @@
 // Host-side odds and ends of the library (version, status text, per-kernel event timing) and the two
 // harness kernels: the stateless table initialiser and the plain copy used as a bandwidth yardstick.
+#include <string>
 #include <vector>
 
 #include "np_common.hpp"
@@ -15,10 +16,16 @@ bool g_prof_on = false;
 std::vector<ProfRecord> g_prof_log;                       // records of the current collection window
 std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_pool;  // events created so far, reused
 size_t g_prof_next = 0;
+std::vector<std::string> g_prof_only;                     // when not empty: only launches with these names are timed
 }  // namespace
 
 void prof_begin(const char* name, hipStream_t stream) {
     if (!g_prof_on) return;
+    if (!g_prof_only.empty()) {
+        bool wanted = false;
+        for (const std::string& w : g_prof_only) wanted |= w == name;
+        if (!wanted) return;
+    }
     if (g_prof_next == g_prof_pool.size()) {
         hipEvent_t a = nullptr, b = nullptr;
         if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
@@ -191,6 +198,22 @@ int np_prof_enable(int on) {
     np::g_prof_on = on != 0;
     np::g_prof_log.clear();
     np::g_prof_next = 0;
+    return NP_OK;
+}
+
+int np_prof_only(const char* names) {
+    np::g_prof_only.clear();
+    if (!names) return NP_OK;
+    std::string cur;
+    for (const char* p = names;; ++p) {
+        if (*p == ',' || *p == '\0') {
+            if (!cur.empty()) np::g_prof_only.push_back(cur);
+            cur.clear();
+            if (*p == '\0') break;
+        } else {
+            cur.push_back(*p);
+        }
+    }
     return NP_OK;
 }
 
