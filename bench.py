@@ -223,6 +223,33 @@ def main() -> int:
                  "bwd_update_ms": sum(v for k, v in fk.items() if k.startswith("bwd")),
                  "kernels_ms": {k: v for k, v in fk.items() if k.startswith("bwd")}}
 
+    # ---- a worker that reads its own table by key needs no inverse map: np_dedup without it, forward over the raw
+    # keys (idx = NULL); reported beside the headline, whose forward goes through (unique, inverse)
+    def step_local(i: int) -> None:
+        bt = dbatch[i % 2]
+        n = bt["n"]
+        main_stream = torch.cuda.current_stream()
+        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d, want_inverse=False)
+        ev_dedup.record(main_stream)
+        side_stream.wait_event(ev_dedup)
+        with torch.cuda.stream(side_stream):
+            B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
+            ev_route.record(side_stream)
+        fwd_call(table, bt["keys"], None, bt["off"], n, cfg.mode, max_len, out_dtype, out=out)
+        main_stream.wait_event(ev_route)
+        B.np_lookup_bwd(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
+                        unique_to_send=rr["unique_to_send"], grads=grads, ws=ws_b)
+        adagrad_call(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
+
+    for i in range(2):
+        step_local(args.warmup + i)
+    torch.cuda.synchronize()
+    tl = time.perf_counter()
+    for i in range(args.steps):
+        step_local(args.warmup + i)
+    torch.cuda.synchronize()
+    local_ms = (time.perf_counter() - tl) * 1e3 / args.steps
+
     # ---- the same K steps without event recording (what the events cost)
     torch.cuda.synchronize()
     t2 = time.perf_counter()
@@ -379,6 +406,8 @@ def main() -> int:
                   for c in alg},
         "kernels": kernels,
         "streams": "np_route runs on a second stream beside np_lookup_fwd; its event times include that sharing",
+        "local_table_step": {"ms_per_step": local_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (local_ms * 1e-3 * args.steps),
+                             "what": "np_dedup without the inverse map, forward over the raw keys; no events"},
         "fused_bwd_update_step": fused,
         "dual_buffer_sync": dbsync,
         "frozen_window_dedup": fwp,

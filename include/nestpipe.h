@@ -69,7 +69,8 @@ const char* np_status_string(int status);
  *
  *   keys         [n]   in   int64, only the low key_bits bits may be non-zero (1 <= key_bits <= 63)
  *   unique       [n]   out  the U distinct keys, ascending; entries >= U are not written
- *   inverse      [n]   out  inverse[j] = index of keys[j] in unique
+ *   inverse      [n]   out  inverse[j] = index of keys[j] in unique; optional (NULL: not produced, which saves the
+ *                           random 4-byte scatter; a worker that reads its own table by key does not need it)
  *   counts       [n]   out  counts[u] = multiplicity of unique[u], u < U
  *   occ_offsets  [n+1] out  exclusive prefix sum of counts; occ_offsets[U] = n
  *   occ          [n]   out  positions 0..n-1 sorted by (key, position): the stable argsort of keys.

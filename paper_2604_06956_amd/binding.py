@@ -138,20 +138,22 @@ def np_dedup_workspace_bytes(n: int, key_bits: int) -> int:
 
 
 def np_dedup(keys: torch.Tensor, key_bits: int, out: Optional[Dict[str, torch.Tensor]] = None,
-             ws: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+             ws: Optional[torch.Tensor] = None, want_inverse: bool = True) -> Dict[str, torch.Tensor]:
     """-> dict(unique[n] i64, inverse[n] i32, counts[n] i32, occ_offsets[n+1] i32, occ[n] i32, num_unique[1] i32).
-    Only the first U = num_unique entries of unique / counts / occ_offsets(+1) are meaningful."""
+    Only the first U = num_unique entries of unique / counts / occ_offsets(+1) are meaningful.  ``want_inverse=False``
+    (or ``out["inverse"] is None``) passes NULL for the optional inverse map."""
     n = keys.numel()
     dev = keys.device
     if out is None:
         out = dict(unique=torch.empty(max(n, 1), dtype=torch.int64, device=dev),
-                   inverse=torch.empty(max(n, 1), dtype=torch.int32, device=dev),
+                   inverse=torch.empty(max(n, 1), dtype=torch.int32, device=dev) if want_inverse else None,
                    counts=torch.empty(max(n, 1), dtype=torch.int32, device=dev),
                    occ_offsets=torch.empty(n + 1, dtype=torch.int32, device=dev),
                    occ=torch.empty(max(n, 1), dtype=torch.int32, device=dev),
                    num_unique=torch.empty(1, dtype=torch.int32, device=dev))
     ws, ws_bytes = _ws(np_dedup_workspace_bytes(n, key_bits), ws, dev)
-    rc = lib.np_dedup(_ptr(keys), n, key_bits, _ptr(out["unique"]), _ptr(out["inverse"]), _ptr(out["counts"]),
+    rc = lib.np_dedup(_ptr(keys), n, key_bits, _ptr(out["unique"]), _ptr(out.get("inverse") if want_inverse else None),
+                      _ptr(out["counts"]),
                       _ptr(out["occ_offsets"]), _ptr(out["occ"]), _ptr(out["num_unique"]), _ptr(ws), ws_bytes, _stream())
     _chk("np_dedup", rc)
     return out

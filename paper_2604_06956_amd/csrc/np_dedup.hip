@@ -196,7 +196,8 @@ dedup_emit_kernel(const K* __restrict__ sorted, const int32_t* __restrict__ occ,
                     unique[u] = static_cast<int64_t>(k[i]);
                     occ_offsets[u] = static_cast<int32_t>(p);
                 }
-                inverse[occ[p]] = u;  // a plain store: L2 merges the partial lines (a non-temporal one doubles the kernel's time)
+                // a plain store: L2 merges the partial lines (a non-temporal one doubles the kernel's time)
+                if (inverse) inverse[occ[p]] = u;
             }
         }
         running += total;
@@ -303,7 +304,7 @@ int np_dedup(const int64_t* keys, int32_t n, int32_t key_bits, int64_t* unique, 
         NP_LAUNCH("dedup_empty", np::dedup_empty_kernel, dim3(1), dim3(64), 0, s, occ_offsets, d_num_unique);
         return np::launch_status();
     }
-    if (!keys || !unique || !inverse || !counts || !occ) return NP_ERR_INVALID_ARG;
+    if (!keys || !unique || !counts || !occ) return NP_ERR_INVALID_ARG;  // inverse is optional
     if (n > INT32_MAX - (1 << 20)) return NP_ERR_UNSUPPORTED;  // tile-rounded indices must stay below 2^31
     if (!np::aligned(keys, 8) || !np::aligned(unique, 8) || !np::aligned(inverse, 4) || !np::aligned(counts, 4) ||
         !np::aligned(occ_offsets, 4) || !np::aligned(occ, 4))

@@ -98,6 +98,21 @@ def test_dedup_is_deterministic(H):
         assert a[k].tobytes() == b[k].tobytes()
 
 
+def test_dedup_without_inverse(H):
+    """The inverse map is optional: the other outputs do not change, and a buffer passed in its place stays untouched."""
+    import torch
+    keys, bits = _keys_case("multi_chunk")
+    full, _ = H.gpu_dedup(keys, bits)
+    d = H.B.np_dedup(H.dev(keys), bits, want_inverse=False)
+    torch.cuda.synchronize()
+    assert d["inverse"] is None
+    U = int(d["num_unique"].item())
+    assert U == full["U"]
+    n = keys.shape[0]
+    for name, k in (("unique", U), ("counts", U), ("occ_offsets", U + 1), ("occ", n)):
+        assert H.host(d[name])[:k].tobytes() == full[name].tobytes(), name
+
+
 # ------------------------------------------------------------------------------------------ route
 
 @pytest.mark.parametrize("S,fn", [(1, 0), (8, 0), (8, 1), (64, 1), (1000, 0), (1536, 1), (4096, 1)])
