@@ -258,6 +258,16 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_per_step_noevents = (time.perf_counter() - t2) * 1e3 / args.steps
 
+    # ---- and once more with one event pair per step: the spread over the steps (the two batches differ a little)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks[0].record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    step_spread = {"min_ms": per_step[0], "median_ms": per_step[len(per_step) // 2], "max_ms": per_step[-1]}
+
     # ---- the same step recorded into one HIP graph per batch and replayed (the library only enqueues kernels, so a
     # caller can do this; the launch-bound small workloads gain, configuration 5 does not)
     graphs = []
@@ -412,6 +422,7 @@ def main() -> int:
         "dual_buffer_sync": dbsync,
         "frozen_window_dedup": fwp,
         "ms_per_step_without_events": ms_per_step_noevents,
+        "step_time_spread": step_spread,
         "ms_per_step_with_events_on_every_launch": ms_per_step_all_events,
         "hip_graph_replay": {"ms_per_step": graph_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (graph_ms * 1e-3 * args.steps)},
         "stream_copy_GBps": copy_gbs,

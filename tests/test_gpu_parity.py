@@ -360,3 +360,30 @@ def test_step_tiny_config_two_batches(H):
                                                     ("large", 8000, 256)])
 def test_step_scaled_configs(H, name, row_div, batch_div):
     _dense_step_check(H, H.wl.scaled(H.wl.config(name), row_div, batch_div), steps=2)
+
+
+def _random_config(H, rng, case):
+    """A small random configuration of the path: every structural parameter drawn independently."""
+    wl = H.wl
+    mode = int(rng.integers(0, 3))
+    dim = int(rng.choice([4, 8, 12, 16, 32, 36, 64, 72, 128, 256, 520]))
+    tables = int(rng.integers(1, 4))
+    rows = tuple(int(rng.integers(64, 20000)) for _ in range(tables))
+    law, args = [("uniform", (1, int(rng.integers(2, 40)))), ("poisson", (int(rng.integers(1, 9)),)),
+                 ("fixed", (int(rng.integers(1, 33)),)), ("poisson_clip", (4, 1, 64))][int(rng.integers(0, 4))]
+    if mode == wl.SEQ:
+        law, args = "seq_uniform", (1, int(rng.integers(2, 60)))
+    S = int(rng.choice([1, 2, 7, 8, 64, 100, 1536, 4096]))
+    return wl.Config(f"random{case}", 1 + case % 5, rows, dim, int(rng.integers(1, 300)), int(rng.integers(1, 6)), law, args,
+                     float(rng.choice([0.0, 0.8, 1.05, 1.5])), S, int(rng.integers(0, 2)), mode, table_seed=100 + case)
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_step_random_small_configurations(H, block):
+    """Sixty small configurations with independently drawn modes, widths, table counts, length laws, skews and shard
+    counts, two consecutive batches each, every call against the oracle."""
+    rng = np.random.default_rng(777 + block)
+    for case in range(block * 15, block * 15 + 15):
+        cfg = _random_config(H, rng, case)
+        H.progress(f"[random step] {cfg}")
+        _dense_step_check(H, cfg, steps=2)
