@@ -4,8 +4,8 @@
 // those updates).  Afterwards the prefetch buffer holds exactly the parameters a sequential run would read
 // (Proposition 1, Eq. (2)).
 //
-//   intersect_probe  every key of B is looked up in A by binary search (both lists ascending; neighbouring
-//                    threads search neighbouring keys, so the probes share cache lines); hits per chunk
+//   intersect_probe  every key of B is looked up in A by binary search, tile by tile inside the slice of A that can
+//                    hold the tile's keys (both lists ascend), staged in LDS; hits per chunk
 //   intersect_emit   ranks the hits (block scan over a blocked arrangement) and writes the index pairs in
 //                    ascending key order; deterministic, no atomics
 //   sync_rows        one LPR-lane group per pair copies a row with 16-byte lane accesses
@@ -33,40 +33,74 @@ inline IsPlan make_is_plan(int cap) {
     return p;
 }
 
+constexpr int kIsStage = 4096;      // keys of A staged in LDS per tile of B (32 KB)
+constexpr int kIsTileBatch = 64;    // tiles whose ranges in A are located together
+
+// First index in [l, h) of an ascending list whose key is not below `key` (h if there is none).
+__device__ __forceinline__ int lower_bound_keys(const int64_t* __restrict__ keys, int l, int h, int64_t key) {
+    while (l < h) {
+        const int m = l + (h - l) / 2;
+        if (keys[m] < key) l = m + 1;
+        else h = m;
+    }
+    return l;
+}
+
+// One block per chunk of B.  Both lists ascend, so a tile of kIsTile consecutive keys of B can only match inside
+// [first A >= the tile's first key, first A >= the next tile's first key): that slice of A is staged in LDS
+// (coalesced) and every key of the tile is located in it by binary search; a slice that does not fit is searched
+// in place.  The slice boundaries of up to kIsTileBatch tiles are found together, one thread each.
 __global__ void __launch_bounds__(kIsThreads)
 intersect_probe_kernel(const int64_t* __restrict__ keys_a, const int32_t* __restrict__ d_num_a, const int64_t* __restrict__ keys_b,
                        const int32_t* __restrict__ d_num_b, int chunk_items, int32_t* __restrict__ found, int32_t* __restrict__ chunk_hits) {
+    __shared__ int64_t sa[kIsStage];
+    __shared__ int bound[kIsTileBatch + 1];
     __shared__ int wsum[kIsThreads / kWave];
-    __shared__ int range_a[2];
     const int na = *d_num_a, nb = *d_num_b;
     const int64_t lo = static_cast<int64_t>(blockIdx.x) * chunk_items;
     int64_t hi = lo + chunk_items;
     if (hi > nb) hi = nb;
-    // both lists ascend, so the chunk's keys can only match inside [first A >= chunk's first key, first A > its last)
-    if (threadIdx.x < 2 && lo < hi) {
-        const int64_t key = threadIdx.x == 0 ? keys_b[lo] : keys_b[hi - 1];
-        int l = 0, h = na;
-        while (l < h) {
-            const int m = l + (h - l) / 2;
-            if (threadIdx.x == 0 ? keys_a[m] < key : keys_a[m] <= key) l = m + 1;
-            else h = m;
-        }
-        range_a[threadIdx.x] = l;
-    }
-    __syncthreads();
-    const int a_lo = lo < hi ? range_a[0] : 0, a_hi = lo < hi ? range_a[1] : 0;
     int hits = 0;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kIsThreads) {
-        const int64_t key = keys_b[i];
-        int l = a_lo, h = a_hi;  // first position of A in the range with a key not below `key`
-        while (l < h) {
-            const int m = l + (h - l) / 2;
-            if (keys_a[m] < key) l = m + 1;
-            else h = m;
+    for (int64_t batch = lo; batch < hi; batch += static_cast<int64_t>(kIsTileBatch) * kIsTile) {
+        __syncthreads();  // bound[] and sa[] of the previous batch are no longer read
+        if (threadIdx.x <= kIsTileBatch) {
+            const int64_t first = batch + static_cast<int64_t>(threadIdx.x) * kIsTile;  // first key of tile threadIdx.x of the batch
+            bound[threadIdx.x] = first < nb ? lower_bound_keys(keys_a, 0, na, keys_b[first]) : na;
         }
-        const int f = (l < a_hi && keys_a[l] == key) ? l : -1;
-        found[i] = f;
-        hits += f >= 0 ? 1 : 0;
+        __syncthreads();
+        for (int t = 0; t < kIsTileBatch; ++t) {
+            const int64_t tile = batch + static_cast<int64_t>(t) * kIsTile;
+            if (tile >= hi) break;  // uniform
+            const int a_lo = bound[t], a_hi = bound[t + 1];
+            const int len = a_hi - a_lo;
+            const bool staged = len <= kIsStage;
+            if (staged)
+                for (int k = threadIdx.x; k < len; k += kIsThreads) sa[k] = keys_a[a_lo + k];
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < kIsIPT; ++q) {
+                const int64_t i = tile + q * kIsThreads + threadIdx.x;
+                if (i < hi) {
+                    const int64_t key = keys_b[i];
+                    int f = -1;
+                    if (staged) {
+                        int l = 0, h = len;
+                        while (l < h) {
+                            const int m = (l + h) >> 1;
+                            if (sa[m] < key) l = m + 1;
+                            else h = m;
+                        }
+                        if (l < len && sa[l] == key) f = a_lo + l;
+                    } else {
+                        const int l = lower_bound_keys(keys_a, a_lo, a_hi, key);
+                        if (l < a_hi && keys_a[l] == key) f = l;
+                    }
+                    found[i] = f;
+                    hits += f >= 0 ? 1 : 0;
+                }
+            }
+            __syncthreads();  // sa[] is rewritten by the next tile
+        }
     }
 #pragma unroll
     for (int d = kWave / 2; d > 0; d >>= 1) hits += __shfl_xor(hits, d, kWave);

@@ -30,7 +30,10 @@
 namespace np {
 
 constexpr int kBwdTile = 256;
-constexpr int kBwdUnroll = 8;
+#ifndef NP_BWD_UNROLL
+#define NP_BWD_UNROLL 8
+#endif
+constexpr int kBwdUnroll = NP_BWD_UNROLL;  // dY row loads in flight per lane
 constexpr int kOrderBuckets = 1024;   // relative positions inside a long segment
 #ifndef NP_ORDER_MIN_COUNT
 #define NP_ORDER_MIN_COUNT 2048

@@ -41,6 +41,19 @@ def test_intersect_bit_exact(H, na, nb, hi):
     assert np.array_equal(ia, ra) and np.array_equal(ib, rb)
 
 
+def test_intersect_uneven_densities(H):
+    """Slices of A far longer than the staged window (dense A, sparse B), and far shorter (the reverse); B spanning
+    several tiles and more than one batch of tiles per chunk."""
+    rng = np.random.default_rng(5)
+    dense = np.arange(0, 3_000_000, dtype=np.int64)
+    sparse = np.unique(rng.integers(0, 3_000_000, size=9000)).astype(np.int64)
+    for a, b in ((dense, sparse), (sparse, dense), (dense[::3], dense[::5]),
+                 (np.concatenate([dense[:5000], dense[2_900_000:]]), sparse)):
+        ia, ib, _ = _gpu_intersect(H, a, b)
+        ra, rb = H.O.intersect(a, b)
+        assert np.array_equal(ia, ra) and np.array_equal(ib, rb)
+
+
 def test_intersect_degenerate(H):
     a = np.arange(0, 5000, 2, dtype=np.int64)
     ia, ib, _ = _gpu_intersect(H, a, a)
