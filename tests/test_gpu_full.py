@@ -66,6 +66,12 @@ def _full_check(H, name, steps):
         B.np_route(d["unique"], d["num_unique"], cap, S, cfg.shard_fn, inverse=d["inverse"], n=n, out=rr)
         out, _ = B.np_lookup_fwd(table, rr["send_keys"], rr["lookup_to_send"], off_d, n, cfg.mode, max_len,
                                  B.BF16 if seq else B.F32, num_list=d["num_unique"], cap=cap)
+        # the forward exactly as bench.py issues it (requester-side list: distinct keys + inverse map): same rows in the
+        # same order, so the same bits
+        out_b, _ = B.np_lookup_fwd(table, d["unique"], d["inverse"], off_d, n, cfg.mode, max_len, B.BF16 if seq else B.F32,
+                                   num_list=d["num_unique"], cap=cap)
+        assert torch.equal(out, out_b)
+        del out_b
         grads = B.np_lookup_bwd(dY, D, cfg.mode, max_len, off_d, n, d["occ_offsets"], d["occ"], d["num_unique"], cap,
                                 unique_to_send=rr["unique_to_send"])
         grads2 = B.np_lookup_bwd(dY, D, cfg.mode, max_len, off_d, n, d["occ_offsets"], d["occ"], d["num_unique"], cap,
