@@ -250,6 +250,38 @@ def main() -> int:
     torch.cuda.synchronize()
     local_ms = (time.perf_counter() - tl) * 1e3 / args.steps
 
+    # ---- both sides of the sharded flow on the one GPU (what every GPU does around the three All2Alls): the owner
+    # gathers the rows of the routed keys into the send buffer, the requester pools straight from that buffer through
+    # lookup_to_send; backward and update as in the headline.  fp32 tables only.
+    sharded_ms = None
+    if not bf16_table:
+        l2s = torch.empty(n_max, dtype=i32, device=dev)
+        rows_buf = torch.empty((cap, D), dtype=torch.float32, device=dev)
+        no_bags = torch.zeros(1, dtype=i32, device=dev)
+        rr_full = dict(rr, lookup_to_send=l2s)
+
+        def step_sharded(i: int) -> None:
+            bt = dbatch[i % 2]
+            n = bt["n"]
+            B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
+            B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, inverse=dd["inverse"], n=n, out=rr_full, ws=ws_r)
+            B.np_lookup_fwd(table, rr["send_keys"], None, no_bags, 0, cfg.mode, max_len, out_dtype, num_list=dd["num_unique"],
+                            cap=cap, out=out, rows_out=rows_buf)
+            B.np_lookup_fwd(rows_buf, None, l2s, bt["off"], n, cfg.mode, max_len, out_dtype, out=out)
+            B.np_lookup_bwd(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
+                            unique_to_send=rr["unique_to_send"], grads=grads, ws=ws_b)
+            B.np_sparse_adagrad(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
+
+        for i in range(2):
+            step_sharded(args.warmup + i)
+        torch.cuda.synchronize()
+        ts = time.perf_counter()
+        for i in range(args.steps):
+            step_sharded(args.warmup + i)
+        torch.cuda.synchronize()
+        sharded_ms = (time.perf_counter() - ts) * 1e3 / args.steps
+        del l2s, rows_buf
+
     # ---- the same K steps without event recording (what the events cost)
     torch.cuda.synchronize()
     t2 = time.perf_counter()
@@ -418,6 +450,10 @@ def main() -> int:
         "streams": "np_route runs on a second stream beside np_lookup_fwd; its event times include that sharing",
         "local_table_step": {"ms_per_step": local_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (local_ms * 1e-3 * args.steps),
                              "what": "np_dedup without the inverse map, forward over the raw keys; no events"},
+        "sharded_flow_step": None if sharded_ms is None else {
+            "ms_per_step": sharded_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (sharded_ms * 1e-3 * args.steps),
+            "what": "owner-side row gather into the send buffer + requester-side pooling from it through lookup_to_send "
+                    "(np_route with the composed map); backward and update as in the headline; no events"},
         "fused_bwd_update_step": fused,
         "dual_buffer_sync": dbsync,
         "frozen_window_dedup": fwp,

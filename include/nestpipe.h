@@ -118,6 +118,9 @@ size_t np_route_workspace_bytes(int32_t cap, int32_t num_shards);
  *   list_keys  [cap]  in   key list (np_route's send_keys, or np_dedup's unique)
  *   d_num_list [1]    in   number of valid list entries; read only when rows_out != NULL (may be NULL otherwise)
  *   idx        [n]    in   lookup -> list slot; NULL means list_keys has n entries and lookup j reads slot j
+ *              list_keys may be NULL when idx is given: the slot itself is the row, value_j = table[idx[j], :]
+ *              (the requester's side of the embedding All2All: pooling straight from the buffer of received rows,
+ *              table = that buffer, idx = np_route's lookup_to_send)
  *   mode / out:
  *     NP_POOL_SUM   out[b,:] = sum of value_j over bag b                  out is [num_bags, dim]
  *     NP_POOL_MEAN  the sum times 1/length; an empty bag gives zeros       out is [num_bags, dim]

@@ -24,6 +24,13 @@ __device__ __forceinline__ void store_words(uint16_t* p, const float4& a) { stor
 
 constexpr int kFwdUnroll = 4;
 
+// Table row read by lookup j: list_keys[idx[j]]; without idx the list has one entry per lookup; without list_keys the
+// slot itself is the row (pooling straight from a buffer of received rows).
+__device__ __forceinline__ int64_t lookup_row(const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx, int j) {
+    const int64_t slot = idx ? static_cast<int64_t>(load_stream(idx + j)) : static_cast<int64_t>(j);
+    return list_keys ? list_keys[slot] : slot;
+}
+
 template <int LPR, int NV, bool MEAN, typename OutT, typename TabT>
 __global__ void __launch_bounds__(256)
 fwd_pool_kernel(const TabT* __restrict__ table, int dim, const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx,
@@ -44,7 +51,7 @@ fwd_pool_kernel(const TabT* __restrict__ table, int dim, const int64_t* __restri
         // one lane per lookup: slot, key and the byte offset of the row (the 64-bit multiply happens here, once
         // per lookup, instead of in every lane of the walk below)
         int64_t row_off = 0;
-        if (j < hi) row_off = list_keys[idx ? load_stream(idx + j) : j] * static_cast<int64_t>(dim) * static_cast<int64_t>(sizeof(TabT));
+        if (j < hi) row_off = lookup_row(list_keys, idx, j) * static_cast<int64_t>(dim) * static_cast<int64_t>(sizeof(TabT));
         const int off_lo = static_cast<int>(row_off & 0xFFFFFFFFll), off_hi = static_cast<int>(row_off >> 32);
         const int cnt = hi - base < LPR ? hi - base : LPR;
         for (int k0 = 0; k0 < cnt; k0 += kFwdUnroll) {
@@ -125,7 +132,7 @@ fwd_pool_x8_kernel(const TabT* __restrict__ table, int dim, const int64_t* __res
     for (int base = lo; base < hi; base += L8) {
         const int j = base + r;
         int64_t row_off = 0;
-        if (j < hi) row_off = list_keys[idx ? load_stream(idx + j) : j] * static_cast<int64_t>(dim) * 2;
+        if (j < hi) row_off = lookup_row(list_keys, idx, j) * static_cast<int64_t>(dim) * 2;
         const int off_lo = static_cast<int>(row_off & 0xFFFFFFFFll), off_hi = static_cast<int>(row_off >> 32);
         const int cnt = hi - base < L8 ? hi - base : L8;
         for (int k0 = 0; k0 < cnt; k0 += kFwdUnroll) {
@@ -228,7 +235,7 @@ __device__ __forceinline__ void seq_row_offsets(int64_t wq0, int64_t total, int 
         const int lo = bag_offsets[b];
         if (p < bag_offsets[b + 1] - lo) {
             const int j = lo + p;
-            my_off = list_keys[idx ? load_stream(idx + j) : j] * static_cast<int64_t>(dim) * ELEM_BYTES;
+            my_off = lookup_row(list_keys, idx, j) * static_cast<int64_t>(dim) * ELEM_BYTES;
         }
     }
     const int off_lo = static_cast<int>(my_off & 0xFFFFFFFFll), off_hi = static_cast<int>(my_off >> 32);
@@ -465,7 +472,7 @@ int np_lookup_fwd_t(const void* table, int32_t table_dtype, int64_t num_rows, in
     if (out_dtype != NP_F32 && out_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
     if (mode == NP_SEQ && max_len < 1) return NP_ERR_INVALID_ARG;
     if (dim < 4 || dim % 4 != 0 || dim > NP_MAX_DIM) return NP_ERR_UNSUPPORTED;
-    if ((num_bags > 0 && !out) || (n > 0 && !list_keys)) return NP_ERR_INVALID_ARG;
+    if ((num_bags > 0 && !out) || (n > 0 && !list_keys && !idx)) return NP_ERR_INVALID_ARG;
     if (rows_out && (!d_num_list || !list_keys)) return NP_ERR_INVALID_ARG;
     const size_t row_align = table_dtype == NP_F32 ? 16 : 8;
     if (!np::aligned(table, row_align) || !np::aligned(out, out_dtype == NP_BF16 ? 8 : 16) || !np::aligned(rows_out, row_align))

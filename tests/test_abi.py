@@ -93,3 +93,4 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.np_lookup_fwd(16, 100, 64, 16, None, 0, None, 16, 4, 10, 5, 1, 0, 16, None, None, 0, None) == -1  # bad mode
     assert lib.np_lookup_fwd(16, 100, 6, 16, None, 0, None, 16, 4, 10, 0, 1, 0, 16, None, None, 0, None) == -3   # dim
     assert lib.np_lookup_fwd(20, 100, 64, 16, None, 0, None, 16, 4, 10, 0, 1, 0, 16, None, None, 0, None) == -1  # misaligned table
+    assert lib.np_lookup_fwd(16, 100, 64, None, None, 0, None, 16, 4, 10, 0, 1, 0, 16, None, None, 0, None) == -1  # neither list nor idx

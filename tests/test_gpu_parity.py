@@ -197,6 +197,36 @@ def test_fwd_seq_bit_exact_and_rows_out(H, dim):
         assert H.host(rows_g)[:U].tobytes() == rows.tobytes()
 
 
+@pytest.mark.parametrize("dim,mode", [(16, 0), (64, 1), (128, 2), (520, 0)])
+def test_fwd_in_two_stages_like_the_sharded_flow(H, dim, mode):
+    """Owner side: rows_out = table[send_keys] (the payload of the embedding All2All).  Requester side: pooling straight
+    from that buffer through lookup_to_send (list_keys = NULL: the slot is the row).  Same rows in the same order as the
+    one-call forward, so the same bits; and equal to the oracle's forward over the identity key list."""
+    import torch
+    rng = np.random.default_rng(dim + mode)
+    R, Bn, S = 4000, 700, 64
+    table = rng.standard_normal((R, dim)).astype(np.float32)
+    off, keys = _bags(rng, Bn, 30, R)
+    max_len = max(1, int(np.diff(off).max()))
+    n = keys.shape[0]
+    d = H.B.np_dedup(H.dev(keys), 12)
+    r = H.B.np_route(d["unique"], d["num_unique"], n, S, 1, inverse=d["inverse"], n=n)
+    dt = H.B.BF16 if mode == 2 else H.B.F32
+    tab = H.dev(table)
+    one, rows = H.B.np_lookup_fwd(tab, r["send_keys"], r["lookup_to_send"], H.dev(off), n, mode, max_len, dt,
+                                  num_list=d["num_unique"], cap=n, want_rows=True)
+    two, _ = H.B.np_lookup_fwd(rows, None, r["lookup_to_send"], H.dev(off), n, mode, max_len, dt)
+    torch.cuda.synchronize()
+    U = int(d["num_unique"].item())
+    assert H.host(two).tobytes() == H.host(one).tobytes()
+    l2s = H.host(r["lookup_to_send"])[:n]
+    ref, _, ab = H.O.lookup_fwd(H.host(rows)[:U], np.arange(U, dtype=np.int64), l2s, off, mode, max_len, dt, want_abs=mode != 2)
+    if mode == 2:
+        assert H.host(two).tobytes() == ref.tobytes()
+    else:
+        H.assert_close(H.host(two), ref, ab, H.RTOL_F32, "requester-side pooling")
+
+
 # ------------------------------------------------------------------------------------------ backward
 
 def _bwd_case(rng, dim, Bn, max_l, R, hot=0.0):
