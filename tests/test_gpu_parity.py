@@ -269,6 +269,26 @@ def test_bwd_pooled(H, dim, mode, hot):
         assert np.array_equal(H.host(gc)[:U], np.repeat(counts[:, None], dim, 1).astype(np.float32))
 
 
+@pytest.mark.parametrize("dim,mode", [(16, 0), (64, 1), (256, 0)])
+def test_bwd_pooled_bf16_upstream_gradient(H, dim, mode):
+    """Pooled modes with the upstream gradient stored in bf16 (read exactly, accumulated in fp32)."""
+    import torch
+    rng = np.random.default_rng(dim * 7 + mode)
+    off, keys, dY = _bwd_case(rng, dim, 2500, 13, 3000, 0.3)
+    dYb = H.wl.round_to_bf16(dY)
+    n = keys.shape[0]
+    g, d = H.gpu_dedup(keys, 12)
+    unique, inverse, *_ = H.assert_dedup_equal(g, keys)
+    U = unique.shape[0]
+    dev_dy = H.bf16_dev(dYb)
+    ref, ab = H.O.lookup_bwd(H.host(dev_dy), 1, dim, mode, 1, off, inverse, U, None, want_abs=True)
+    grads = H.B.np_lookup_bwd(dev_dy, dim, mode, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], n)
+    torch.cuda.synchronize()
+    H.assert_close(H.host(grads)[:U], ref, ab, H.RTOL_F32, f"bwd pooled bf16 dY dim={dim} mode={mode}")
+    ref32, _ = H.O.lookup_bwd(dYb, 0, dim, mode, 1, off, inverse, U, None)
+    assert np.array_equal(ref, ref32)          # the oracle reads bf16 exactly
+
+
 @pytest.mark.parametrize("dim", [16, 128])
 def test_bwd_seq_bf16(H, dim):
     import torch
