@@ -199,13 +199,14 @@ def main() -> int:
         n = bt["n"]
         B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
         B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
-        B.np_lookup_fwd(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
-                        num_list=dd["num_unique"], cap=cap, out=out)
-        B.np_lookup_bwd_adagrad(bt["dY"], cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["unique"],
-                                dd["num_unique"], cap, table, state, cfg.lr, cfg.eps, ws=ws_b)
+        fwd_call(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
+                 num_list=dd["num_unique"], cap=cap, out=out)
+        (B.np_lookup_bwd_adagrad_t if bf16_table else B.np_lookup_bwd_adagrad)(
+            bt["dY"], cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["unique"], dd["num_unique"], cap, table,
+            state, cfg.lr, cfg.eps, ws=ws_b)
 
     fused = None
-    if D <= 256 and not bf16_table:   # the fused call takes fp32 tables only
+    if D <= 256:
         step_fused(0)
         B.np_prof_enable(True)
         torch.cuda.synchronize()

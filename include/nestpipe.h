@@ -210,6 +210,13 @@ int np_lookup_bwd_adagrad(const void* dY, int32_t dy_dtype, int32_t dim, int32_t
                           const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
                           const int32_t* occ, const int64_t* unique, const int32_t* d_num_unique, int32_t cap, float* table,
                           float* state, int64_t num_rows, float lr, float eps, void* ws, size_t ws_bytes, void* stream);
+/* The same for a table of dtype NP_F32, NP_BF16 or NP_F16 (the update rounds as np_sparse_adagrad_t does, so the table
+ * and state again match the two separate calls bit for bit). */
+int np_lookup_bwd_adagrad_t(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
+                            const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
+                            const int32_t* occ, const int64_t* unique, const int32_t* d_num_unique, int32_t cap, void* table,
+                            int32_t table_dtype, float* state, int64_t num_rows, float lr, float eps, void* ws,
+                            size_t ws_bytes, void* stream);
 
 /* ---- dual-buffer synchronisation (Section IV-B) --------------------------------------------------- */
 

@@ -59,6 +59,9 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.np_lookup_bwd_adagrad.restype = ctypes.c_int
     L.np_lookup_bwd_adagrad.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i64,
                                         _f32, _f32, _vp, _sz, _vp]
+    L.np_lookup_bwd_adagrad_t.restype = ctypes.c_int
+    L.np_lookup_bwd_adagrad_t.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp,
+                                          _i64, _f32, _f32, _vp, _sz, _vp]
     L.np_sparse_adagrad.restype = ctypes.c_int
     L.np_sparse_adagrad.argtypes = [_vp, _vp, _i64, _i32, _vp, _vp, _vp, _i32, _f32, _f32, _vp]
     L.np_lookup_fwd_t.restype = ctypes.c_int
@@ -272,6 +275,23 @@ def np_lookup_bwd_adagrad(dY: torch.Tensor, mode: int, max_len: int, bag_offsets
                                    _ptr(occ), _ptr(unique), _ptr(num_unique), cap, _ptr(table), _ptr(state), num_rows, lr, eps,
                                    _ptr(ws), ws_bytes, _stream())
     _chk("np_lookup_bwd_adagrad", rc)
+
+
+def np_lookup_bwd_adagrad_t(dY: torch.Tensor, mode: int, max_len: int, bag_offsets: torch.Tensor, n: int,
+                            occ_offsets: torch.Tensor, occ: torch.Tensor, unique: torch.Tensor, num_unique: torch.Tensor, cap: int,
+                            table: torch.Tensor, state: torch.Tensor, lr: float, eps: float,
+                            ws: Optional[torch.Tensor] = None) -> None:
+    """np_lookup_bwd_adagrad for a float32, bfloat16 or float16 table."""
+    num_rows, dim = table.shape
+    num_bags = bag_offsets.numel() - 1
+    if dY.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("dY must be fp32 or bf16")
+    dy_dtype = BF16 if dY.dtype == torch.bfloat16 else F32
+    ws, ws_bytes = _ws(np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode), ws, dY.device)
+    rc = lib.np_lookup_bwd_adagrad_t(_ptr(dY), dy_dtype, dim, mode, max_len, _ptr(bag_offsets), num_bags, n, _ptr(occ_offsets),
+                                     _ptr(occ), _ptr(unique), _ptr(num_unique), cap, _ptr(table), _table_dtype(table), _ptr(state),
+                                     num_rows, lr, eps, _ptr(ws), ws_bytes, _stream())
+    _chk("np_lookup_bwd_adagrad_t", rc)
 
 
 def np_sparse_adagrad(table: torch.Tensor, state: torch.Tensor, list_keys: torch.Tensor, grads: torch.Tensor,

@@ -156,30 +156,38 @@ __device__ __forceinline__ float4 load_dy(const uint16_t* dY, int row, int dim, 
                        __uint_as_float(p.y & 0xFFFF0000u));
 }
 
-// Where a finished gradient row goes.  Plain: grads[dst, :].  Fused (np_lookup_bwd_adagrad): the row is consumed on
-// the spot by the row-wise Adagrad step on table[keys[dst], :] and never reaches HBM; the arithmetic is the one
-// of np_sparse_adagrad (same butterfly over the LPR lanes of a row), so both routes give the same bits.
+// Where a finished gradient row goes.  Plain (FUSED == 0): grads[dst, :].  Fused (np_lookup_bwd_adagrad): the row is
+// consumed on the spot by the row-wise Adagrad step on table[keys[dst], :] and never reaches HBM; the arithmetic is
+// the one of np_sparse_adagrad (same butterfly over the LPR lanes of a row, same store rounding), so both routes
+// give the same bits.  FUSED also names the table's element type: 1 fp32, 2 bf16, 3 fp16.
+constexpr int kSinkGrads = 0, kSinkF32 = 1, kSinkBf16 = 2, kSinkF16 = 3;
+
+template <int FUSED> struct SinkTable { using type = float; };
+template <> struct SinkTable<kSinkBf16> { using type = uint16_t; };
+template <> struct SinkTable<kSinkF16> { using type = __half; };
+
 struct RowSink {
     float* grads;
-    float* table;
+    void* table;
     float* state;
     const int64_t* keys;
     float lr, eps, inv_dim;
 };
 
 // Called by all LPR lanes that hold a row (lane r holds float4 word r; NV == 1 on the fused route).
-template <int LPR, bool FUSED>
+template <int LPR, int FUSED>
 __device__ __forceinline__ void sink_row(const RowSink& sk, int dst, int dim, int r, int words, const float4& g) {
-    if (!FUSED) {
+    if (FUSED == kSinkGrads) {
         if (r < words) store_stream(reinterpret_cast<float4*>(sk.grads + static_cast<size_t>(dst) * dim) + r, g);
         return;
     }
+    using TabT = typename SinkTable<FUSED>::type;
     const int64_t key = sk.keys[dst];
-    float4* wrow = reinterpret_cast<float4*>(sk.table + static_cast<size_t>(key) * dim);
+    TabT* wrow = static_cast<TabT*>(sk.table) + static_cast<size_t>(key) * dim;
     float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
     float ss = 0.f;
     if (r < words) {
-        w = wrow[r];
+        w = load_word(wrow, r);
         ss += sumsq4(g);
     }
     const float s_old = sk.state[key];
@@ -190,11 +198,11 @@ __device__ __forceinline__ void sink_row(const RowSink& sk, int dst, int dim, in
     if (r == 0) sk.state[key] = G;
     if (r < words) {
         adagrad_step4(w, g, sk.lr, denom);
-        wrow[r] = w;
+        store_word_stream(wrow, r, w);
     }
 }
 
-template <int LPR, int NV, bool MEAN, typename DyT, bool FUSED>
+template <int LPR, int NV, bool MEAN, typename DyT, int FUSED>
 __global__ void __launch_bounds__(256)
 bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const int32_t* __restrict__ bag_offsets, int n,
                 const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ occ, const int32_t* __restrict__ d_num_unique,
@@ -418,7 +426,7 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
 constexpr int kFixupShort = 8;
 constexpr int kFixupThreads = 1024;
 
-template <int LPR, int NV, bool FUSED>
+template <int LPR, int NV, int FUSED>
 __global__ void __launch_bounds__(256)
 bwd_fixup_short_kernel(int dim, int num_tiles, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
                        const float* __restrict__ tile_left, const float* __restrict__ tile_right,
@@ -469,7 +477,7 @@ bwd_fixup_short_kernel(int dim, int num_tiles, const int32_t* __restrict__ occ_o
     }
 }
 
-template <int LPR, int NV, bool FUSED>
+template <int LPR, int NV, int FUSED>
 __global__ void __launch_bounds__(kFixupThreads)
 bwd_fixup_long_kernel(int dim, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
                       const float* __restrict__ tile_left, const float* __restrict__ tile_right,
@@ -571,7 +579,7 @@ struct BwdArgs {
     hipStream_t stream;
 };
 
-template <int LPR, int NV, bool FUSED>
+template <int LPR, int NV, int FUSED>
 void bwd_launch(const BwdArgs& a) {
     const BwdWs L = bwd_ws_layout(a.n, a.dim);
     WsCursor cur(a.ws);
@@ -628,6 +636,15 @@ void bwd_launch(const BwdArgs& a) {
               a.unique_to_send, tile_left, tile_right, tile_rseg, a.sink, long_count, long_tiles);
 }
 
+template <int FUSED>
+void bwd_fused_dispatch(const BwdArgs& a, int words) {
+    if (words <= 4) bwd_launch<4, 1, FUSED>(a);
+    else if (words <= 8) bwd_launch<8, 1, FUSED>(a);
+    else if (words <= 16) bwd_launch<16, 1, FUSED>(a);
+    else if (words <= 32) bwd_launch<32, 1, FUSED>(a);
+    else bwd_launch<64, 1, FUSED>(a);
+}
+
 }  // namespace np
 
 extern "C" {
@@ -657,21 +674,23 @@ int np_lookup_bwd(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, i
     np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, unique_to_send,
                   np::RowSink{grads, nullptr, nullptr, nullptr, 0.f, 0.f, 0.f}, ws, static_cast<hipStream_t>(stream)};
     const int words = dim / 4;
-    if (words <= 4) np::bwd_launch<4, 1, false>(a);
-    else if (words <= 8) np::bwd_launch<8, 1, false>(a);
-    else if (words <= 16) np::bwd_launch<16, 1, false>(a);
-    else if (words <= 32) np::bwd_launch<32, 1, false>(a);
-    else if (words <= 64) np::bwd_launch<64, 1, false>(a);
-    else if (words <= 128) np::bwd_launch<64, 2, false>(a);
-    else np::bwd_launch<64, 4, false>(a);
+    if (words <= 4) np::bwd_launch<4, 1, np::kSinkGrads>(a);
+    else if (words <= 8) np::bwd_launch<8, 1, np::kSinkGrads>(a);
+    else if (words <= 16) np::bwd_launch<16, 1, np::kSinkGrads>(a);
+    else if (words <= 32) np::bwd_launch<32, 1, np::kSinkGrads>(a);
+    else if (words <= 64) np::bwd_launch<64, 1, np::kSinkGrads>(a);
+    else if (words <= 128) np::bwd_launch<64, 2, np::kSinkGrads>(a);
+    else np::bwd_launch<64, 4, np::kSinkGrads>(a);
     return np::launch_status();
 }
 
-int np_lookup_bwd_adagrad(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
-                          const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
-                          const int32_t* occ, const int64_t* unique, const int32_t* d_num_unique, int32_t cap, float* table,
-                          float* state, int64_t num_rows, float lr, float eps, void* ws, size_t ws_bytes, void* stream) {
+int np_lookup_bwd_adagrad_t(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
+                            const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
+                            const int32_t* occ, const int64_t* unique, const int32_t* d_num_unique, int32_t cap, void* table,
+                            int32_t table_dtype, float* state, int64_t num_rows, float lr, float eps, void* ws, size_t ws_bytes,
+                            void* stream) {
     if (num_bags < 0 || n < 0 || cap < 0 || !d_num_unique || !table || !state || num_rows < 1) return NP_ERR_INVALID_ARG;
+    if (table_dtype != NP_F32 && table_dtype != NP_BF16 && table_dtype != NP_F16) return NP_ERR_INVALID_ARG;
     if (mode != NP_POOL_SUM && mode != NP_POOL_MEAN && mode != NP_SEQ) return NP_ERR_INVALID_ARG;
     if (dy_dtype != NP_F32 && dy_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
     if (mode == NP_SEQ && max_len < 1) return NP_ERR_INVALID_ARG;
@@ -680,18 +699,25 @@ int np_lookup_bwd_adagrad(const void* dY, int32_t dy_dtype, int32_t dim, int32_t
     if (n == 0) return NP_OK;
     if (n > INT32_MAX - (1 << 20)) return NP_ERR_UNSUPPORTED;
     if (!dY || !bag_offsets || !occ_offsets || !occ || !unique || num_bags < 1) return NP_ERR_INVALID_ARG;
-    if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(table, 16)) return NP_ERR_INVALID_ARG;
+    if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(table, table_dtype == NP_F32 ? 16 : 8))
+        return NP_ERR_INVALID_ARG;
     if (!ws || !np::aligned(ws, 256) || ws_bytes < np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode)) return NP_ERR_WORKSPACE;
     np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, nullptr,
                   np::RowSink{nullptr, table, state, unique, lr, eps, 1.0f / static_cast<float>(dim)}, ws,
                   static_cast<hipStream_t>(stream)};
     const int words = dim / 4;
-    if (words <= 4) np::bwd_launch<4, 1, true>(a);
-    else if (words <= 8) np::bwd_launch<8, 1, true>(a);
-    else if (words <= 16) np::bwd_launch<16, 1, true>(a);
-    else if (words <= 32) np::bwd_launch<32, 1, true>(a);
-    else np::bwd_launch<64, 1, true>(a);
+    if (table_dtype == NP_BF16) np::bwd_fused_dispatch<np::kSinkBf16>(a, words);
+    else if (table_dtype == NP_F16) np::bwd_fused_dispatch<np::kSinkF16>(a, words);
+    else np::bwd_fused_dispatch<np::kSinkF32>(a, words);
     return np::launch_status();
+}
+
+int np_lookup_bwd_adagrad(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
+                          const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
+                          const int32_t* occ, const int64_t* unique, const int32_t* d_num_unique, int32_t cap, float* table,
+                          float* state, int64_t num_rows, float lr, float eps, void* ws, size_t ws_bytes, void* stream) {
+    return np_lookup_bwd_adagrad_t(dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, unique,
+                                   d_num_unique, cap, table, NP_F32, state, num_rows, lr, eps, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

@@ -62,6 +62,37 @@ def test_fused_equals_separate_calls_bitwise(H, dim, mode, hot):
     assert H.host(t2)[rest].tobytes() == table0[rest].tobytes() and H.host(s2)[rest].tobytes() == state0[rest].tobytes()
 
 
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+@pytest.mark.parametrize("dim,mode", [(8, 0), (64, 1), (256, 0)])
+def test_fused_on_16bit_tables_equals_separate_calls_bitwise(H, kind, dim, mode):
+    """np_lookup_bwd_adagrad_t on a bf16 / fp16 table against np_lookup_bwd + np_sparse_adagrad_t: same bits."""
+    import torch
+    B = H.B
+    tdt = torch.bfloat16 if kind == "bf16" else torch.float16
+    rng = np.random.default_rng(dim * 3 + mode + (kind == "f16"))
+    R, Bn = 5000, 3001
+    lens = rng.integers(0, 12, size=Bn)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    keys = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+    keys[rng.random(keys.shape[0]) < 0.4] = 11
+    n = keys.shape[0]
+    table0 = torch.from_numpy((rng.standard_normal((R, dim)) * 0.01).astype(np.float32)).to(tdt).cuda()
+    state0 = H.dev((rng.random(R) * 0.1).astype(np.float32))
+    dY = H.dev(rng.standard_normal((Bn, dim)).astype(np.float32))
+    od = H.dev(off)
+    d = B.np_dedup(H.dev(keys), 13)
+    torch.cuda.synchronize()
+    U = int(d["num_unique"].item())
+    t1, s1 = table0.clone(), state0.clone()
+    g = B.np_lookup_bwd(dY, dim, mode, 1, od, n, d["occ_offsets"], d["occ"], d["num_unique"], U)
+    B.np_sparse_adagrad_t(t1, s1, d["unique"], g, d["num_unique"], U, 0.01, 1e-8)
+    t2, s2 = table0.clone(), state0.clone()
+    B.np_lookup_bwd_adagrad_t(dY, mode, 1, od, n, d["occ_offsets"], d["occ"], d["unique"], d["num_unique"], U, t2, s2, 0.01, 1e-8)
+    torch.cuda.synchronize()
+    assert torch.equal(t1.view(torch.int16), t2.view(torch.int16)) and torch.equal(s1, s2)
+    assert not torch.equal(t1.view(torch.int16), table0.view(torch.int16))
+
+
 def test_fused_sequence_mode_bf16(H):
     import torch
     rng = np.random.default_rng(5)
