@@ -287,49 +287,73 @@ fwd_seq_kernel(const TabT* __restrict__ table, int dim, const int64_t* __restric
 // Sequence output in bf16 for rows whose width is a multiple of 8: a lane owns 8 consecutive floats (two
 // 16-byte loads) and writes them as 8 bf16 with one 16-byte store, so loads and stores are both full width.
 // L8 lanes share a row (dim / 8 rounded up to a power of two, at most 64), NV8 chunks of 8 floats per lane.
+// A block owns kSeqBlockPos consecutive output positions.  First every thread
+// resolves several positions at once (position -> bag -> slot -> key -> row offset, all lanes busy, the chains of
+// one thread in flight together) into LDS; then the groups stream over the block's positions, kSeqBatch rows per
+// group in flight, reading each row offset from LDS.  The resolve phase of one block overlaps the copy phase of the
+// others on the same CU.
+#ifndef NP_SEQ_BLOCK_POS
+#define NP_SEQ_BLOCK_POS 1024
+#endif
+constexpr int kSeqBlockPos = NP_SEQ_BLOCK_POS;
+constexpr int kSeqBatch = 4;
+
 template <int L8, int NV8>
 __global__ void __launch_bounds__(256)
-fwd_seq_bf16x8_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys, const int32_t* __restrict__ idx,
-                      const int32_t* __restrict__ bag_offsets, int num_bags, int max_len, uint16_t* __restrict__ out) {
+fwd_seq_bf16x8_kernel(const float* __restrict__ table, int dim, const int64_t* __restrict__ list_keys,
+                             const int32_t* __restrict__ idx, const int32_t* __restrict__ bag_offsets, int num_bags, int max_len,
+                             uint16_t* __restrict__ out) {
     constexpr int GPB = 256 / L8;
-    constexpr int SPG = kSeqPerGroup < L8 ? kSeqPerGroup : L8;  // positions per group; at most 64 per wave
-    const int r = threadIdx.x % L8;
+    static_assert(kSeqBlockPos % (GPB * kSeqBatch) == 0 && kSeqBlockPos % 256 == 0, "whole batches per block");
+    __shared__ int64_t soff[kSeqBlockPos];
     const int64_t total = static_cast<int64_t>(num_bags) * max_len;
-    const int64_t q0 = (static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / L8) * SPG;
-    const int chunks = dim / 8;
-    const int64_t wq0 = (static_cast<int64_t>(blockIdx.x) * GPB + (threadIdx.x / kWave) * (kWave / L8)) * SPG;
-    int64_t off[SPG];
-    seq_row_offsets<L8, SPG, 4>(wq0, total, max_len, dim, list_keys, idx, bag_offsets, off);
-    const float4* src[SPG];
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kSeqBlockPos;
 #pragma unroll
-    for (int k = 0; k < SPG; ++k)
-        src[k] = off[k] < 0 ? nullptr : reinterpret_cast<const float4*>(reinterpret_cast<const char*>(table) + off[k]);
-    float4 x[SPG][NV8][2];
-#pragma unroll
-    for (int k = 0; k < SPG; ++k) {
-#pragma unroll
-        for (int v = 0; v < NV8; ++v) {
-            const int c = r + v * L8;
-            const bool on = src[k] && c < chunks;
-            x[k][v][0] = on ? src[k][2 * c] : make_float4(0.f, 0.f, 0.f, 0.f);
-            x[k][v][1] = on ? src[k][2 * c + 1] : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < SPG; ++k) {
-        const int64_t q = q0 + k;
+    for (int s = 0; s < kSeqBlockPos / 256; ++s) {
+        const int64_t q = base + s * 256 + threadIdx.x;
+        int64_t off = -1;  // padding or past the end
         if (q < total) {
+            const int b = static_cast<int>(static_cast<uint32_t>(q) / static_cast<uint32_t>(max_len));  // total < 2^31
+            const int p = static_cast<int>(q - static_cast<int64_t>(b) * max_len);
+            const int lo = bag_offsets[b];
+            if (p < bag_offsets[b + 1] - lo) off = lookup_row(list_keys, idx, lo + p) * static_cast<int64_t>(dim) * 4;
+        }
+        soff[s * 256 + threadIdx.x] = off;
+    }
+    __syncthreads();
+    const int r = threadIdx.x % L8, g = threadIdx.x / L8;
+    const int chunks = dim / 8;
+    for (int i0 = g; i0 < kSeqBlockPos; i0 += GPB * kSeqBatch) {
+        if (base + i0 >= total) break;  // later positions of this group are further out still
+        float4 x[kSeqBatch][NV8][2];
+#pragma unroll
+        for (int u = 0; u < kSeqBatch; ++u) {
+            const int64_t off = soff[i0 + u * GPB];
+            const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const char*>(table) + (off < 0 ? 0 : off));
 #pragma unroll
             for (int v = 0; v < NV8; ++v) {
                 const int c = r + v * L8;
-                if (c < chunks) {
-                    const float4 a = x[k][v][0], b = x[k][v][1];
-                    uint4 o;
-                    o.x = static_cast<uint32_t>(f32_to_bf16(a.x)) | (static_cast<uint32_t>(f32_to_bf16(a.y)) << 16);
-                    o.y = static_cast<uint32_t>(f32_to_bf16(a.z)) | (static_cast<uint32_t>(f32_to_bf16(a.w)) << 16);
-                    o.z = static_cast<uint32_t>(f32_to_bf16(b.x)) | (static_cast<uint32_t>(f32_to_bf16(b.y)) << 16);
-                    o.w = static_cast<uint32_t>(f32_to_bf16(b.z)) | (static_cast<uint32_t>(f32_to_bf16(b.w)) << 16);
-                    store_stream(reinterpret_cast<uint4*>(out + static_cast<size_t>(q) * dim + c * 8), o);
+                const bool on = off >= 0 && c < chunks;
+                x[u][v][0] = on ? src[2 * c] : make_float4(0.f, 0.f, 0.f, 0.f);
+                x[u][v][1] = on ? src[2 * c + 1] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kSeqBatch; ++u) {
+            const int64_t q = base + i0 + u * GPB;
+            if (q < total) {
+#pragma unroll
+                for (int v = 0; v < NV8; ++v) {
+                    const int c = r + v * L8;
+                    if (c < chunks) {
+                        const float4 a = x[u][v][0], b = x[u][v][1];
+                        uint4 o;
+                        o.x = static_cast<uint32_t>(f32_to_bf16(a.x)) | (static_cast<uint32_t>(f32_to_bf16(a.y)) << 16);
+                        o.y = static_cast<uint32_t>(f32_to_bf16(a.z)) | (static_cast<uint32_t>(f32_to_bf16(a.w)) << 16);
+                        o.z = static_cast<uint32_t>(f32_to_bf16(b.x)) | (static_cast<uint32_t>(f32_to_bf16(b.y)) << 16);
+                        o.w = static_cast<uint32_t>(f32_to_bf16(b.z)) | (static_cast<uint32_t>(f32_to_bf16(b.w)) << 16);
+                        store_stream(reinterpret_cast<uint4*>(out + static_cast<size_t>(q) * dim + c * 8), o);
+                    }
                 }
             }
         }
@@ -339,13 +363,10 @@ fwd_seq_bf16x8_kernel(const float* __restrict__ table, int dim, const int64_t* _
 template <int L8, int NV8>
 void fwd_seq_bf16x8_launch(const float* table, int dim, const int64_t* list_keys, const int32_t* idx, const int32_t* bag_offsets,
                            int num_bags, int max_len, uint16_t* out, hipStream_t stream) {
-    constexpr int GPB = 256 / L8;
-    constexpr int SPG = kSeqPerGroup < L8 ? kSeqPerGroup : L8;
     const int64_t total = static_cast<int64_t>(num_bags) * max_len;
-    const int64_t per_block = static_cast<int64_t>(GPB) * SPG;
-    const unsigned grid = static_cast<unsigned>((total + per_block - 1) / per_block);
-    NP_LAUNCH("fwd_seq", (fwd_seq_bf16x8_kernel<L8, NV8>), dim3(grid), dim3(256), 0, stream, table, dim, list_keys, idx, bag_offsets,
-              num_bags, max_len, out);
+    const unsigned grid = static_cast<unsigned>((total + kSeqBlockPos - 1) / kSeqBlockPos);
+    NP_LAUNCH("fwd_seq", (fwd_seq_bf16x8_kernel<L8, NV8>), dim3(grid), dim3(256), 0, stream, table, dim, list_keys, idx,
+              bag_offsets, num_bags, max_len, out);
 }
 
 template <int LPR, int NV, typename TabT>
