@@ -41,7 +41,8 @@ constexpr int kOrderBuckets = 1024;   // relative positions inside a long segmen
 #ifndef NP_ORDER_XCD_SPLIT
 #define NP_ORDER_XCD_SPLIT 1
 #endif
-constexpr int kOrderMinCount = NP_ORDER_MIN_COUNT;  // segments at least this long take part in the locality order
+constexpr int kOrderMinCount = NP_ORDER_MIN_COUNT;
+constexpr size_t kOrderMinDyBytes = size_t(32) << 20;  // the eight 4 MB L2s together  // segments at least this long take part in the locality order
 
 // One entry per 64 consecutive lookups: where bags start inside the block and which bag the block begins in.
 // 16 bytes per 64 lookups (n/4 bytes in all), so the random reads of bwd_main mostly stay in L2 / Infinity Cache.
@@ -223,7 +224,7 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     // every 8th of the remaining ones
     int tile;
     {
-        const int nh = order_offsets[kOrderBuckets];
+        const int nh = order ? order_offsets[kOrderBuckets] : 0;  // no order given: tiles run in index order
         const int nc = num_tiles - nh;
         const int hc = (nh + kNumXcd - 1) / kNumXcd;
         const int x = blockIdx.x % kNumXcd, sl = blockIdx.x / kNumXcd;
@@ -239,7 +240,7 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
             if (kc >= nc) return;
             k = nh + kc;
         }
-        tile = order[k];
+        tile = order ? order[k] : k;
     }
     const int tile_start = tile * kBwdTile;
     const int i = tile_start + t;
@@ -601,10 +602,15 @@ void bwd_launch(const BwdArgs& a) {
               a.n, bagmap);
     NP_LAUNCH("bwd_tile_seg0", bwd_tile_seg0_kernel, dim3((L.num_tiles + 255) / 256), dim3(256), 0, a.stream, a.occ_offsets,
               a.d_num_unique, L.num_tiles, tile_seg0, long_count);
-    {
+    // The locality order pays when dY is far larger than the L2s; below that it only costs three launches.
+    const size_t dy_bytes = static_cast<size_t>(a.num_bags) * (seq ? a.max_len : 1) * a.dim * (a.dy_dtype == NP_BF16 ? 2 : 4);
+    if (dy_bytes > kOrderMinDyBytes) {
         TileOrderPolicy pol{tile_seg0, a.occ_offsets, order, a.n};
         run_partition_pass(pol, L.num_tiles, nullptr, kOrderBuckets + 1, 11, oplan, oH, obin, nullptr, order_offsets, a.stream,
                            "bwd_order_hist", "bwd_order_colscan", "bwd_order_scatter");
+    } else {
+        order = nullptr;
+        order_offsets = nullptr;
     }
     const unsigned main_grid = static_cast<unsigned>((L.num_tiles + 2 * kNumXcd + kNumXcd - 1) / kNumXcd * kNumXcd);
     const bool mean = a.mode == NP_POOL_MEAN;
