@@ -269,6 +269,36 @@ def test_bwd_pooled(H, dim, mode, hot):
         assert np.array_equal(H.host(gc)[:U], np.repeat(counts[:, None], dim, 1).astype(np.float32))
 
 
+@pytest.mark.parametrize("dim,Bn,mode", [(64, 1_100_000, 0), (1024, 70_000, 1)])
+def test_bwd_with_an_upstream_gradient_larger_than_the_last_level_cache(H, dim, Bn, mode):
+    """Above 256 MB of dY the backward runs its tiles in the locality order (long segments sorted by relative position,
+    one range per die); popular keys give it segments of many tiles to order."""
+    import torch
+    rng = np.random.default_rng(dim)
+    lens = rng.integers(0, 6, size=Bn)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    n = int(off[-1])
+    keys = rng.integers(0, 200_000, size=n).astype(np.int64)
+    hot = rng.random(n)
+    keys[hot < 0.25] = 5
+    keys[(hot >= 0.25) & (hot < 0.35)] = 77
+    keys[(hot >= 0.35) & (hot < 0.37)] = 4242
+    dY = rng.standard_normal((Bn, dim)).astype(np.float32)
+    assert dY.nbytes > 256 << 20
+    g, d = H.gpu_dedup(keys, 18)
+    unique, inverse, counts, _, _ = H.assert_dedup_equal(g, keys)
+    U = unique.shape[0]
+    assert counts.max() > 100 * 256
+    ref, ab = H.O.lookup_bwd(dY, 0, dim, mode, 1, off, inverse, U, None, want_abs=True)
+    dYd = H.dev(dY)
+    grads = H.B.np_lookup_bwd(dYd, dim, mode, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], U)
+    torch.cuda.synchronize()
+    H.assert_close(H.host(grads)[:U], ref, ab, H.RTOL_F32, f"bwd ordered dim={dim}")
+    grads2 = H.B.np_lookup_bwd(dYd, dim, mode, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], U)
+    torch.cuda.synchronize()
+    assert torch.equal(grads[:U], grads2[:U])
+
+
 @pytest.mark.parametrize("dim,mode", [(16, 0), (64, 1), (256, 0)])
 def test_bwd_pooled_bf16_upstream_gradient(H, dim, mode):
     """Pooled modes with the upstream gradient stored in bf16 (read exactly, accumulated in fp32)."""
