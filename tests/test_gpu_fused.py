@@ -93,6 +93,24 @@ def test_fused_on_16bit_tables_equals_separate_calls_bitwise(H, kind, dim, mode)
     assert not torch.equal(t1.view(torch.int16), table0.view(torch.int16))
 
 
+def test_fused_with_an_upstream_gradient_larger_than_the_last_level_cache(H):
+    """The locality-ordered tile schedule (dY above 256 MB) with the fused sink: still the bits of the separate calls."""
+    import torch
+    rng = np.random.default_rng(9)
+    R, Bn, dim = 200_000, 1_100_000, 64
+    lens = rng.integers(0, 6, size=Bn)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    keys = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+    keys[rng.random(keys.shape[0]) < 0.3] = 5
+    table0 = (rng.standard_normal((R, dim)) * 0.01).astype(np.float32)
+    state0 = np.zeros(R, np.float32)
+    dY = H.dev(rng.standard_normal((Bn, dim)).astype(np.float32))
+    assert dY.numel() * 4 > 256 << 20
+    t1, s1, t2, s2, *_ = _run_both(H, table0, state0, keys, off, dY, 0, 1, 18)
+    assert torch.equal(t1, t2) and torch.equal(s1, s2)
+    assert not torch.equal(t1, H.dev(table0))
+
+
 def test_fused_sequence_mode_bf16(H):
     import torch
     rng = np.random.default_rng(5)
