@@ -467,3 +467,36 @@ def test_step_random_small_configurations(H, block):
         cfg = _random_config(H, rng, case)
         H.progress(f"[random step] {cfg}")
         _dense_step_check(H, cfg, steps=2)
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_step_with_no_lookups(H, mode):
+    """A batch whose bags are all empty: zero distinct keys, zero splits, zero (or zero-padded) outputs, no gradient
+    row written, table and state untouched."""
+    import torch
+    B = H.B
+    Bn, D, S, R, max_len = 300, 32, 16, 500, 3
+    keys = torch.empty(0, dtype=torch.int64, device="cuda")
+    off = torch.zeros(Bn + 1, dtype=torch.int32, device="cuda")
+    table = torch.randn((R, D), device="cuda")
+    state = torch.rand(R, device="cuda")
+    t0, s0 = table.clone(), state.clone()
+    d = B.np_dedup(keys, 9)
+    r = B.np_route(d["unique"], d["num_unique"], 0, S, 1, inverse=d["inverse"], n=0)
+    dt = B.BF16 if mode == 2 else B.F32
+    out = torch.full((Bn, max_len, D) if mode == 2 else (Bn, D), 7.0, dtype=torch.bfloat16 if mode == 2 else torch.float32,
+                     device="cuda")
+    B.np_lookup_fwd(table, r["send_keys"], r["lookup_to_send"], off, 0, mode, max_len, dt, num_list=d["num_unique"], cap=0, out=out)
+    dY = torch.randn(out.shape, device="cuda").to(out.dtype)
+    grads = torch.full((4, D), 3.0, device="cuda")
+    B.np_lookup_bwd(dY, D, mode, max_len, off, 0, d["occ_offsets"], d["occ"], d["num_unique"], 0,
+                    unique_to_send=r["unique_to_send"], grads=grads)
+    B.np_sparse_adagrad(table, state, r["send_keys"], grads, d["num_unique"], 0, 0.01, 1e-8)
+    B.np_lookup_bwd_adagrad(dY, mode, max_len, off, 0, d["occ_offsets"], d["occ"], d["unique"], d["num_unique"], 0, table, state,
+                            0.01, 1e-8)
+    torch.cuda.synchronize()
+    assert int(d["num_unique"].item()) == 0 and int(d["occ_offsets"][0].item()) == 0
+    assert not H.host(r["splits"]).any() and not H.host(r["send_offsets"]).any()
+    assert not H.host(out).any()
+    assert torch.equal(grads, torch.full((4, D), 3.0, device="cuda"))
+    assert torch.equal(table, t0) and torch.equal(state, s0)
