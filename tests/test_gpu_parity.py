@@ -500,3 +500,29 @@ def test_step_with_no_lookups(H, mode):
     assert not H.host(out).any()
     assert torch.equal(grads, torch.full((4, D), 3.0, device="cuda"))
     assert torch.equal(table, t0) and torch.equal(state, s0)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_one_very_long_bag_between_an_empty_and_a_short_one(H, mode):
+    """Forward and backward with a 100,000-lookup bag (one group walks it; its mean weight is 1e-5)."""
+    import torch
+    rng = np.random.default_rng(41 + mode)
+    R, D = 3000, 32
+    lens = np.array([0, 100_000, 5, 0, 1], np.int64)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    n = int(off[-1])
+    keys = rng.integers(0, R, size=n).astype(np.int64)
+    keys[-1] = R - 1
+    keys[0] = 0
+    table = rng.standard_normal((R, D)).astype(np.float32)
+    dY = rng.standard_normal((lens.size, D)).astype(np.float32)
+    g, d = H.gpu_dedup(keys, 12)
+    unique, inverse, *_ = H.assert_dedup_equal(g, keys)
+    U = unique.shape[0]
+    ref, _, ab = H.O.lookup_fwd(table, unique, inverse, off, mode, want_abs=True)
+    out, _ = H.B.np_lookup_fwd(H.dev(table), d["unique"], d["inverse"], H.dev(off), n, mode)
+    gref, gab = H.O.lookup_bwd(dY, 0, D, mode, 1, off, inverse, U, None, want_abs=True)
+    grads = H.B.np_lookup_bwd(H.dev(dY), D, mode, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], U)
+    torch.cuda.synchronize()
+    H.assert_close(H.host(out), ref, ab, H.RTOL_F32, "forward, long bag")
+    H.assert_close(H.host(grads)[:U], gref, gab, H.RTOL_F32, "backward, long bag")
