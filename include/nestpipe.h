@@ -24,13 +24,14 @@
  *    anything is enqueued, so a call that returns NP_ERR_INVALID_ARG, NP_ERR_WORKSPACE or
  *    NP_ERR_UNSUPPORTED has written nothing.  Nothing throws, aborts or prints.
  *  - Keys are int64 row ids of one fused table, 0 <= key < num_rows (the caller adds a per-table
- *    base to form them).  Every index, offset and count is int32, so n <= 2^31 - 1.
+ *    base to form them).  Every index, offset and count is int32; a batch holds at most
+ *    2^31 - 1 - 2^20 lookups (larger n: NP_ERR_UNSUPPORTED).
  *  - Bags: the lookups of bag b are keys[bag_offsets[b] .. bag_offsets[b+1]), bag_offsets is
  *    non-decreasing with bag_offsets[0] = 0 and bag_offsets[num_bags] = n.  Empty bags are legal.
  *  - Out-of-range keys, repeated keys in an update list, or offsets that break the rules above
  *    are precondition violations (not checked on the device).
  *  - Supported row widths: dim a multiple of 4, 4 <= dim <= 1024; table, gradient and output
- *    buffers 16-byte aligned.
+ *    buffers 16-byte aligned (8-byte for 16-bit tables and bf16 outputs).
  */
 #ifndef NESTPIPE_H_
 #define NESTPIPE_H_
