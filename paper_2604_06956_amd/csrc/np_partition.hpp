@@ -8,7 +8,8 @@
 //                 rank inside the tile, the tile is reordered through LDS and written out in runs
 //
 // A chunk is a run of consecutive tiles owned by one block, sized so that at most kTargetChunks blocks
-// cover the input: all of them are resident at once (no tail wave) and the histogram matrix stays small.
+// cover the input: all of them are resident at once, the same number on every CU (no tail round), and the
+// histogram matrix stays small.
 // The scatter kernel maps chunks to blocks so that neighbouring chunks run on the same die: the short
 // runs they append to each bin then merge in that die's L2 instead of reaching HBM as partial lines.
 #pragma once
@@ -31,23 +32,32 @@ constexpr int kPartIPT = NP_PART_IPT;
 constexpr int kPartTile = kPartThreads * kPartIPT;
 static_assert(kPartIPT * kWave <= 65535, "per-wave digit counters are 16 bits wide");
 constexpr int kPartMaxBins = 4096;
-constexpr int kTargetChunks = 1024;
+#ifndef NP_TARGET_CHUNKS
+#define NP_TARGET_CHUNKS 512  // two blocks on each of the 256 CUs: 384, 640, 768 and 1024 leave a ragged last round
+#endif
+constexpr int kTargetChunks = NP_TARGET_CHUNKS;
 constexpr int kMaxDevices = 64;  // devices whose dynamic-LDS opt-in is remembered
 constexpr int kColscanThreads = 1024;
 
+// The input is cut into whole tiles, the tiles into num_chunks runs that differ by at most one tile, so that the
+// number of blocks is exactly the target whenever there are that many tiles.
 struct ChunkPlan {
     int num_chunks;
-    int chunk_items;  // multiple of kPartTile
+    int num_tiles;  // tiles of kPartTile items
 };
 
 inline ChunkPlan make_chunk_plan(int64_t cap) {
     int64_t tiles = (cap + kPartTile - 1) / kPartTile;
     if (tiles < 1) tiles = 1;
-    const int64_t tpc = (tiles + kTargetChunks - 1) / kTargetChunks;
     ChunkPlan p;
-    p.num_chunks = static_cast<int>((tiles + tpc - 1) / tpc);
-    p.chunk_items = static_cast<int>(tpc * kPartTile);
+    p.num_chunks = static_cast<int>(tiles < kTargetChunks ? tiles : kTargetChunks);
+    p.num_tiles = static_cast<int>(tiles);
     return p;
+}
+
+// First item of chunk c (c = num_chunks gives the end of the last chunk).
+__host__ __device__ __forceinline__ int64_t chunk_begin(const ChunkPlan& p, int c) {
+    return (static_cast<int64_t>(c) * p.num_tiles / p.num_chunks) * kPartTile;
 }
 
 // Words reserved for the histogram matrix: sized for the largest chunk count so that the workspace
@@ -90,8 +100,8 @@ part_hist_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, Chunk
     const int64_t n = d_n ? *d_n : n_host;
     for (int b = threadIdx.x; b < bins; b += kPartThreads) lh[b] = 0;
     __syncthreads();
-    const int64_t lo = static_cast<int64_t>(c) * plan.chunk_items;
-    int64_t hi = lo + plan.chunk_items;
+    const int64_t lo = chunk_begin(plan, c);
+    int64_t hi = chunk_begin(plan, c + 1);
     if (hi > n) hi = n;
     constexpr int kBatch = 8;  // independent loads in flight per thread
     const int lane = threadIdx.x % kWave;
@@ -213,8 +223,8 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
     }
     __syncthreads();
 
-    const int64_t lo = static_cast<int64_t>(c) * plan.chunk_items;
-    int64_t hi = lo + plan.chunk_items;
+    const int64_t lo = chunk_begin(plan, c);
+    int64_t hi = chunk_begin(plan, c + 1);
     if (hi > n) hi = n;
     const uint64_t lt = lanemask_lt();
 
