@@ -7,6 +7,11 @@
 
 namespace np {
 
+#ifndef NP_ADAGRAD_MAX_GRID
+#define NP_ADAGRAD_MAX_GRID 1048576  // one row per group up to 16 M rows of 64 floats (1.61 -> 1.59 ms against 65536 blocks)
+#endif
+constexpr int64_t kAdagradMaxGrid = NP_ADAGRAD_MAX_GRID;
+
 template <int LPR, int NV, typename TabT>
 __global__ void __launch_bounds__(256)
 adagrad_kernel(TabT* __restrict__ table, float* __restrict__ state, int dim, const int64_t* __restrict__ list_keys,
@@ -54,7 +59,7 @@ void adagrad_launch(TabT* table, float* state, int dim, const int64_t* list_keys
                     const int32_t* d_num_list, int cap, float lr, float eps, hipStream_t stream) {
     constexpr int GPB = 256 / LPR;
     int64_t want = (static_cast<int64_t>(cap) + GPB - 1) / GPB;
-    const unsigned grid = static_cast<unsigned>(want < 65536 ? want : 65536);
+    const unsigned grid = static_cast<unsigned>(want < kAdagradMaxGrid ? want : kAdagradMaxGrid);
     NP_LAUNCH("sparse_adagrad", (adagrad_kernel<LPR, NV, TabT>), dim3(grid), dim3(256), 0, stream, table, state, dim, list_keys,
               grads, d_num_list, lr, eps, 1.0f / static_cast<float>(dim));
 }

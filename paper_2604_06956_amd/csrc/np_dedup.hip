@@ -82,7 +82,10 @@ struct SortNextPolicy {
 
 // ---- after the sort: segment heads -> ranks ------------------------------------------------------------
 
-constexpr int kHeadThreads = 256;
+#ifndef NP_HEAD_THREADS
+#define NP_HEAD_THREADS 256
+#endif
+constexpr int kHeadThreads = NP_HEAD_THREADS;
 constexpr int kHeadIPT = 8;
 constexpr int kHeadTile = kHeadThreads * kHeadIPT;
 #ifndef NP_EMIT_CHUNKS
