@@ -38,6 +38,7 @@ constexpr int kPartMaxBins = 4096;
 constexpr int kTargetChunks = NP_TARGET_CHUNKS;
 constexpr int kMaxDevices = 64;  // devices whose dynamic-LDS opt-in is remembered
 constexpr int kColscanThreads = 1024;
+constexpr int kHistThreads = 1024;
 
 // The input is cut into whole tiles, the tiles into num_chunks runs that differ by at most one tile, so that the
 // number of blocks is exactly the target whenever there are that many tiles.
@@ -92,24 +93,26 @@ __device__ __forceinline__ uint64_t match_any(uint32_t d, int nbits, bool valid)
 //   __device__ void store(uint32_t dst, KeyT k, uint32_t v) const; item placed at output slot dst
 //   __device__ void placed(int64_t i, uint32_t dst) const;         input item i went to dst (may be a no-op)
 
+// A streaming read with one LDS add per run: it runs with kHistThreads threads per block, twice the scatter
+// kernel's, to keep enough loads in flight with two blocks per CU (0.21 -> 0.19 ms for three passes).
 template <class P>
-__global__ void __launch_bounds__(kPartThreads)
+__global__ void __launch_bounds__(kHistThreads)
 part_hist_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, ChunkPlan plan, uint32_t* __restrict__ H) {
     extern __shared__ uint32_t lh[];
     const int c = blockIdx.x;
     const int64_t n = d_n ? *d_n : n_host;
-    for (int b = threadIdx.x; b < bins; b += kPartThreads) lh[b] = 0;
+    for (int b = threadIdx.x; b < bins; b += kHistThreads) lh[b] = 0;
     __syncthreads();
     const int64_t lo = chunk_begin(plan, c);
     int64_t hi = chunk_begin(plan, c + 1);
     if (hi > n) hi = n;
     constexpr int kBatch = 8;  // independent loads in flight per thread
     const int lane = threadIdx.x % kWave;
-    for (int64_t base = lo; base < hi; base += static_cast<int64_t>(kPartThreads) * kBatch) {
+    for (int64_t base = lo; base < hi; base += static_cast<int64_t>(kHistThreads) * kBatch) {
         typename P::KeyT k[kBatch];
 #pragma unroll
         for (int q = 0; q < kBatch; ++q) {
-            const int64_t i = base + q * kPartThreads + threadIdx.x;
+            const int64_t i = base + q * kHistThreads + threadIdx.x;
             k[q] = typename P::KeyT(0);
             if (i < hi) k[q] = pol.load_key(i);
         }
@@ -118,7 +121,7 @@ part_hist_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, Chunk
             // The lanes of a wave hold consecutive items, so the valid lanes are a prefix of the wave.  After the
             // first pass equal digits arrive in runs (a popular key fills whole waves): one add per run of equal
             // digits instead of one per lane keeps such waves from serialising on a single LDS address.
-            const int64_t i = base + q * kPartThreads + threadIdx.x;
+            const int64_t i = base + q * kHistThreads + threadIdx.x;
             const bool valid = i < hi;
             const uint32_t d = valid ? pol.digit(k[q]) : 0xFFFFFFFFu;
             const uint32_t dprev = __shfl_up(d, 1, kWave);
@@ -133,7 +136,7 @@ part_hist_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, Chunk
         }
     }
     __syncthreads();
-    for (int b = threadIdx.x; b < bins; b += kPartThreads) H[static_cast<size_t>(c) * bins + b] = lh[b];
+    for (int b = threadIdx.x; b < bins; b += kHistThreads) H[static_cast<size_t>(c) * bins + b] = lh[b];
 }
 
 // Block = 16 waves x 64 bins: wave y sums, then rewrites as exclusive prefixes, its slice of the chunks.
@@ -331,7 +334,7 @@ template <class P>
 inline void run_partition_pass(const P& pol, int n_host, const int* d_n, int bins, int nbits, const ChunkPlan& plan,
                                uint32_t* H, uint32_t* bin_total, int32_t* totals_out, int32_t* offsets_out,
                                hipStream_t stream, const char* tag_hist, const char* tag_scan, const char* tag_scatter) {
-    NP_LAUNCH(tag_hist, part_hist_kernel<P>, dim3(plan.num_chunks), dim3(kPartThreads), sizeof(uint32_t) * bins, stream,
+    NP_LAUNCH(tag_hist, part_hist_kernel<P>, dim3(plan.num_chunks), dim3(kHistThreads), sizeof(uint32_t) * bins, stream,
               pol, n_host, d_n, bins, plan, H);
     NP_LAUNCH(tag_scan, part_colscan_kernel<kColscanThreads>, dim3((bins + kWave - 1) / kWave), dim3(kColscanThreads), 0, stream, H,
               plan.num_chunks, bins, bin_total);
