@@ -500,10 +500,12 @@ bwd_fixup_long_kernel(int dim, const int32_t* __restrict__ occ_offsets, const in
         float4 acc[NV];
 #pragma unroll
         for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int c = c0; c < c1; c += 4) {
-            float4 p[4][NV];
+        // the chain of the most popular key is the critical path of this kernel: many partial rows in flight per lane
+        constexpr int kInFlight = 16 / NV;
+        for (int c = c0; c < c1; c += kInFlight) {
+            float4 p[kInFlight][NV];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kInFlight; ++q) {
                 const float4* src = reinterpret_cast<const float4*>(tile_left + static_cast<size_t>(tile + 1 + (c + q < c1 ? c + q : c)) * dim);
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
@@ -512,7 +514,7 @@ bwd_fixup_long_kernel(int dim, const int32_t* __restrict__ occ_offsets, const in
                 }
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kInFlight; ++q) {
                 if (c + q < c1) {
 #pragma unroll
                     for (int v = 0; v < NV; ++v) {
