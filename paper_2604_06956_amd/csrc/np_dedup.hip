@@ -86,7 +86,10 @@ struct SortNextPolicy {
 #define NP_HEAD_THREADS 256
 #endif
 constexpr int kHeadThreads = NP_HEAD_THREADS;
-constexpr int kHeadIPT = 8;
+#ifndef NP_HEAD_IPT
+#define NP_HEAD_IPT 8
+#endif
+constexpr int kHeadIPT = NP_HEAD_IPT;
 constexpr int kHeadTile = kHeadThreads * kHeadIPT;
 #ifndef NP_EMIT_CHUNKS
 #define NP_EMIT_CHUNKS 512  // measured: 0.82 ms with 1024 blocks, 0.79 with 384, 0.66 with 512 or 256
