@@ -157,6 +157,19 @@ __device__ __forceinline__ float4 load_dy(const uint16_t* dY, int row, int dim, 
                        __uint_as_float(p.y & 0xFFFF0000u));
 }
 
+// Words 2 * pair and 2 * pair + 1 of a bf16 row with one 16-byte load (rows a multiple of 8 elements wide, 16-byte
+// aligned base).  Twice the bytes per load instruction: with 8-byte lanes the gather of 256-byte bf16 rows in
+// sequence mode ran at half the rate of the fp32 one.
+__device__ __forceinline__ void load_dy_pair(const uint16_t* dY, int row, int dim, int pair, float4& a, float4& b) {
+    const uint64_t off = static_cast<uint64_t>(static_cast<uint32_t>(row)) * static_cast<uint32_t>(dim * 2);
+    const uint4 p = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(dY) + off)[pair];
+    a = make_float4(__uint_as_float(p.x << 16), __uint_as_float(p.x & 0xFFFF0000u), __uint_as_float(p.y << 16),
+                    __uint_as_float(p.y & 0xFFFF0000u));
+    b = make_float4(__uint_as_float(p.z << 16), __uint_as_float(p.z & 0xFFFF0000u), __uint_as_float(p.w << 16),
+                    __uint_as_float(p.w & 0xFFFF0000u));
+}
+__device__ __forceinline__ void load_dy_pair(const float*, int, int, int, float4&, float4&) {}  // never selected
+
 // Where a finished gradient row goes.  Plain (FUSED == 0): grads[dst, :].  Fused (np_lookup_bwd_adagrad): the row is
 // consumed on the spot by the row-wise Adagrad step on table[keys[dst], :] and never reaches HBM; the arithmetic is
 // the one of np_sparse_adagrad (same butterfly over the LPR lanes of a row, same store rounding), so both routes
@@ -203,7 +216,15 @@ __device__ __forceinline__ void sink_row(const RowSink& sk, int dst, int dim, in
     }
 }
 
-template <int LPR, int NV, bool MEAN, typename DyT, int FUSED>
+// Which float4 word of the row lane r of a group holds in its v-th accumulator.  Striped (word r + v * LPR) by default;
+// PAIR (NV == 2, bf16 dY): words 2r and 2r + 1, the 16 bytes of one bf16 load.  Everything past the walk (partials in
+// LDS and in the workspace, the fix-up kernels) is indexed by word, so the layout is private to the walk.
+template <int LPR, bool PAIR>
+__device__ __forceinline__ int word_of(int r, int v) {
+    return PAIR ? 2 * r + v : r + v * LPR;
+}
+
+template <int LPR, int NV, bool MEAN, typename DyT, int FUSED, bool PAIR = false>
 __global__ void __launch_bounds__(256)
 bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const int32_t* __restrict__ bag_offsets, int n,
                 const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ occ, const int32_t* __restrict__ d_num_unique,
@@ -211,6 +232,7 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                 const int32_t* __restrict__ tile_seg0, const int32_t* __restrict__ order, const int32_t* __restrict__ order_offsets,
                 int num_tiles, RowSink sink, float* __restrict__ tile_left, float* __restrict__ tile_right,
                 int32_t* __restrict__ tile_rseg) {
+    static_assert(!PAIR || (NV == 2 && FUSED == kSinkGrads), "the pair layout is two words per lane, plain sink");
     constexpr int GPB = 256 / LPR;
     constexpr int ROWW = LPR * NV;  // float4 words per (padded) row
     __shared__ int headmark[kBwdTile + 1];
@@ -307,10 +329,15 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
         for (int q = 0; q < kBwdUnroll; ++q) {
             const bool on = k0 + q < cnt;
             const int srk = group_bcast<LPR>(sr, (k0 + q) & (LPR - 1));
+            if constexpr (PAIR) {
+                x[q][0] = x[q][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (on && 2 * r < words) load_dy_pair(dY, srk, dim, r, x[q][0], x[q][1]);  // words is even here
+            } else {
 #pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                const int wv = r + v * LPR;
-                x[q][v] = (on && wv < words) ? load_dy(dY, srk, dim, wv) : make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int v = 0; v < NV; ++v) {
+                    const int wv = r + v * LPR;
+                    x[q][v] = (on && wv < words) ? load_dy(dY, srk, dim, wv) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
             }
         }
 #pragma unroll
@@ -341,13 +368,13 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                         } else {
 #pragma unroll
                             for (int v = 0; v < NV; ++v) {
-                                const int wv = r + v * LPR;
+                                const int wv = word_of<LPR, PAIR>(r, v);
                                 if (wv < words) store_stream(reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dk) * dim) + wv, acc[v]);
                             }
                         }
                     } else {
 #pragma unroll
-                        for (int v = 0; v < NV; ++v) lpart[g * ROWW + r + v * LPR] = acc[v];
+                        for (int v = 0; v < NV; ++v) lpart[g * ROWW + word_of<LPR, PAIR>(r, v)] = acc[v];
                         le = true;
                         lc = true;
                         ld = dk;
@@ -362,12 +389,12 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     if (cnt > 0 && dlast < 0) {  // the last run goes on past the strip
         if (first_open) {        // one segment covers the whole strip
 #pragma unroll
-            for (int v = 0; v < NV; ++v) lpart[g * ROWW + r + v * LPR] = acc[v];
+            for (int v = 0; v < NV; ++v) lpart[g * ROWW + word_of<LPR, PAIR>(r, v)] = acc[v];
             le = true;
             lc = false;
         } else {
 #pragma unroll
-            for (int v = 0; v < NV; ++v) rpart[g * ROWW + r + v * LPR] = acc[v];
+            for (int v = 0; v < NV; ++v) rpart[g * ROWW + word_of<LPR, PAIR>(r, v)] = acc[v];
             re = true;
         }
     }
@@ -619,27 +646,28 @@ void bwd_launch(const BwdArgs& a) {
     }
     const unsigned main_grid = static_cast<unsigned>((L.num_tiles + 2 * kNumXcd + kNumXcd - 1) / kNumXcd * kNumXcd);
     const bool mean = a.mode == NP_POOL_MEAN;
-    if (a.dy_dtype == NP_BF16) {
-        const uint16_t* dy = static_cast<const uint16_t*>(a.dY);
-        if (mean)
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, uint16_t, FUSED>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.sink,
-                      tile_left, tile_right, tile_rseg);
-        else
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, uint16_t, FUSED>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.sink,
-                      tile_left, tile_right, tile_rseg);
-    } else {
-        const float* dy = static_cast<const float*>(a.dY);
-        if (mean)
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, true, float, FUSED>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.sink,
-                      tile_left, tile_right, tile_rseg);
-        else
-            NP_LAUNCH("bwd_main", (bwd_main_kernel<LPR, NV, false, float, FUSED>), dim3(main_grid), dim3(256), 0, a.stream, dy, a.dim,
-                      seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique, a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.sink,
-                      tile_left, tile_right, tile_rseg);
+#define NP_BWD_MAIN(L_, N_, M_, T_, P_)                                                                                        \
+    NP_LAUNCH("bwd_main", (bwd_main_kernel<L_, N_, M_, T_, FUSED, P_>), dim3(main_grid), dim3(256), 0, a.stream,                 \
+              static_cast<const T_*>(a.dY), a.dim, seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique,     \
+              a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.sink, tile_left, tile_right, tile_rseg)
+    bool launched = false;
+    if constexpr (FUSED == kSinkGrads && NV == 1 && LPR >= 8) {
+        // bf16 rows a multiple of 8 elements wide: half the lanes per row, 16-byte loads (words 2r, 2r + 1 per lane)
+        if (a.dy_dtype == NP_BF16 && a.dim % 8 == 0 && aligned(a.dY, 16)) {
+            if (mean) NP_BWD_MAIN(LPR / 2, 2, true, uint16_t, true);
+            else NP_BWD_MAIN(LPR / 2, 2, false, uint16_t, true);
+            launched = true;
+        }
     }
+    if (launched) {
+    } else if (a.dy_dtype == NP_BF16) {
+        if (mean) NP_BWD_MAIN(LPR, NV, true, uint16_t, false);
+        else NP_BWD_MAIN(LPR, NV, false, uint16_t, false);
+    } else {
+        if (mean) NP_BWD_MAIN(LPR, NV, true, float, false);
+        else NP_BWD_MAIN(LPR, NV, false, float, false);
+    }
+#undef NP_BWD_MAIN
     constexpr int GPB = 256 / LPR;
     NP_LAUNCH("bwd_fixup_short", (bwd_fixup_short_kernel<LPR, NV, FUSED>), dim3((L.num_tiles + GPB - 1) / GPB), dim3(256), 0, a.stream, a.dim,
               L.num_tiles, a.occ_offsets, a.unique_to_send, tile_left, tile_right, tile_rseg, a.sink, long_count, long_tiles);

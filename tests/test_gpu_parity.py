@@ -299,7 +299,7 @@ def test_bwd_with_an_upstream_gradient_larger_than_the_last_level_cache(H, dim, 
     assert torch.equal(grads[:U], grads2[:U])
 
 
-@pytest.mark.parametrize("dim,mode", [(16, 0), (64, 1), (256, 0)])
+@pytest.mark.parametrize("dim,mode", [(16, 0), (64, 1), (256, 0), (20, 0), (24, 1), (40, 0), (136, 1)])
 def test_bwd_pooled_bf16_upstream_gradient(H, dim, mode):
     """Pooled modes with the upstream gradient stored in bf16 (read exactly, accumulated in fp32)."""
     import torch
@@ -319,7 +319,7 @@ def test_bwd_pooled_bf16_upstream_gradient(H, dim, mode):
     assert np.array_equal(ref, ref32)          # the oracle reads bf16 exactly
 
 
-@pytest.mark.parametrize("dim", [16, 128])
+@pytest.mark.parametrize("dim", [16, 128, 24, 72, 36])
 def test_bwd_seq_bf16(H, dim):
     import torch
     rng = np.random.default_rng(dim + 99)
@@ -342,6 +342,30 @@ def test_bwd_seq_bf16(H, dim):
     grads = H.B.np_lookup_bwd(dYp, dim, 2, max_len, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], n)
     torch.cuda.synchronize()
     H.assert_close(H.host(grads)[:U], ref, ab, H.RTOL_F32, f"bwd seq dim={dim}")
+
+
+def test_bwd_bf16_gradient_at_an_8_byte_aligned_base(H):
+    """A bf16 dY whose base is 8- but not 16-byte aligned takes the 8-byte loads and gives the same bits as the aligned
+    copy (which takes the 16-byte ones)."""
+    import torch
+    dim = 64
+    rng = np.random.default_rng(4242)
+    off, keys, dY = _bwd_case(rng, dim, 1800, 11, 2500, 0.3)
+    n = keys.shape[0]
+    g, d = H.gpu_dedup(keys, 12)
+    dev_dy = H.bf16_dev(H.wl.round_to_bf16(dY))
+    store = torch.zeros(dev_dy.numel() + 16, dtype=torch.bfloat16, device="cuda")
+    base = store.data_ptr()
+    shift = 4 if base % 16 == 0 else 0                      # elements; 4 bf16 = 8 bytes
+    odd = store[shift:shift + dev_dy.numel()].view(dev_dy.shape)
+    odd.copy_(dev_dy)
+    assert odd.data_ptr() % 16 == 8
+    args = (dim, 0, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], n)
+    g_al = H.B.np_lookup_bwd(dev_dy, *args)
+    g_odd = H.B.np_lookup_bwd(odd, *args)
+    torch.cuda.synchronize()
+    U = int(d["num_unique"].item())
+    assert torch.equal(g_al[:U], g_odd[:U])
 
 
 # ------------------------------------------------------------------------------------------ update
