@@ -54,8 +54,6 @@ __device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
     return x * q + (x < r ? x : r) + i;
 }
 
-__device__ __forceinline__ int lane_id() { return __lane_id(); }
-
 __device__ __forceinline__ uint64_t lanemask_lt() {
     const int l = __lane_id();
     return l == 0 ? 0ull : (~0ull >> (64 - l));
@@ -271,14 +269,5 @@ __device__ __forceinline__ void adagrad_step4(float4& w, const float4& g, float 
     w.z -= (lr * g.z) / denom;
     w.w -= (lr * g.w) / denom;
 }
-
-// Row geometry shared by the row kernels: a row of `dim` floats is dim/4 float4 words, handled by LPR
-// lanes holding NV words each (word index = lane_in_group + v * LPR).
-template <int LPR, int NV>
-struct RowGeom {
-    static constexpr int kLanes = LPR;
-    static constexpr int kWords = NV;
-    static constexpr int kGroupsPerBlock = 256 / LPR;
-};
 
 }  // namespace np
