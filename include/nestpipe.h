@@ -31,7 +31,12 @@
  *  - Out-of-range keys, repeated keys in an update list, or offsets that break the rules above
  *    are precondition violations (not checked on the device).
  *  - Supported row widths: dim a multiple of 4, 4 <= dim <= 1024; table, gradient and output
- *    buffers 16-byte aligned (8-byte for 16-bit tables and bf16 outputs).
+ *    buffers 16-byte aligned (8-byte for 16-bit tables, bf16 outputs and bf16 dY; a bf16 dY at a
+ *    16-byte aligned address is read with wider loads, with the same result).
+ *  - The compute calls keep no state between calls and act on the calling thread's current
+ *    device: they may be issued from several host threads and on several devices.  Ordering
+ *    calls that share a buffer (through streams and events) is the caller's job.  The np_prof_*
+ *    timing hooks are the exception (process-wide state, one thread at a time).
  */
 #ifndef NESTPIPE_H_
 #define NESTPIPE_H_
