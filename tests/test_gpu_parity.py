@@ -550,3 +550,16 @@ def test_one_very_long_bag_between_an_empty_and_a_short_one(H, mode):
     torch.cuda.synchronize()
     H.assert_close(H.host(out), ref, ab, H.RTOL_F32, "forward, long bag")
     H.assert_close(H.host(grads)[:U], gref, gab, H.RTOL_F32, "backward, long bag")
+
+
+@pytest.mark.parametrize("words", [1, 255, 256, 1025, 4096 * 16384 // 16 + 3, (1 << 22) + 777])
+def test_stream_copy_yardstick_copies_every_word(H, words):
+    """The bandwidth yardstick is a real copy: every 16-byte word arrives, nothing past the end is touched (slabs per
+    block with a ragged last slab, a tail shorter than one round of loads)."""
+    import torch
+    src = torch.arange(words * 4 + 8, dtype=torch.int32, device="cuda")
+    dst = torch.full_like(src, -1)
+    H.B.np_util_stream_copy(dst[: words * 4], src[: words * 4])
+    torch.cuda.synchronize()
+    assert torch.equal(dst[: words * 4], src[: words * 4])
+    assert bool((dst[words * 4:] == -1).all())
