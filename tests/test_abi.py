@@ -94,3 +94,23 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.np_lookup_fwd(16, 100, 6, 16, None, 0, None, 16, 4, 10, 0, 1, 0, 16, None, None, 0, None) == -3   # dim
     assert lib.np_lookup_fwd(20, 100, 64, 16, None, 0, None, 16, 4, 10, 0, 1, 0, 16, None, None, 0, None) == -1  # misaligned table
     assert lib.np_lookup_fwd(16, 100, 64, None, None, 0, None, 16, 4, 10, 0, 1, 0, 16, None, None, 0, None) == -1  # neither list nor idx
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/nestpipe.h is a C header: a C99 translation unit that includes it and takes the address of every
+    declared function compiles with gcc (no C++-only constructs, no missing includes)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    names = declared_symbols()
+    src = tmp_path / "use_header.c"
+    refs = "\n".join(f"    p[{i}] = (void (*)(void))&{n};" for i, n in enumerate(names))
+    src.write_text('#include "nestpipe.h"\n'
+                   f"void (*p[{len(names)}])(void);\n"
+                   "void take_addresses(void) {\n" + refs + "\n}\n"
+                   "int status_is_int[sizeof(np_status) >= 1 ? 1 : -1];\n")
+    r = subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), "-c", str(src), "-o",
+                        str(tmp_path / "use_header.o")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
