@@ -108,11 +108,15 @@ def _chk(call: str, rc: int) -> None:
         raise NestPipeError(call, rc)
 
 
-def _ptr(t: Optional[torch.Tensor]) -> int:
+def _ptr(t: Optional[torch.Tensor], dtype: Optional[torch.dtype] = None) -> int:
+    """Device address of ``t`` (0 for None) after checking what the C side cannot: residency, contiguity and, when
+    ``dtype`` is given, the element type the entry point reads the buffer as."""
     if t is None:
         return 0
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("tensors handed to the library must be contiguous device tensors")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected a {dtype} tensor, got {t.dtype}")
     return t.data_ptr()
 
 
@@ -155,9 +159,9 @@ def np_dedup(keys: torch.Tensor, key_bits: int, out: Optional[Dict[str, torch.Te
                    occ=torch.empty(max(n, 1), dtype=torch.int32, device=dev),
                    num_unique=torch.empty(1, dtype=torch.int32, device=dev))
     ws, ws_bytes = _ws(np_dedup_workspace_bytes(n, key_bits), ws, dev)
-    rc = lib.np_dedup(_ptr(keys), n, key_bits, _ptr(out["unique"]), _ptr(out.get("inverse") if want_inverse else None),
-                      _ptr(out["counts"]),
-                      _ptr(out["occ_offsets"]), _ptr(out["occ"]), _ptr(out["num_unique"]), _ptr(ws), ws_bytes, _stream())
+    rc = lib.np_dedup(_ptr(keys, torch.int64), n, key_bits, _ptr(out["unique"], torch.int64), _ptr(out.get("inverse") if want_inverse else None, torch.int32),
+                      _ptr(out["counts"], torch.int32),
+                      _ptr(out["occ_offsets"], torch.int32), _ptr(out["occ"], torch.int32), _ptr(out["num_unique"], torch.int32), _ptr(ws), ws_bytes, _stream())
     _chk("np_dedup", rc)
     return out
 
@@ -181,10 +185,10 @@ def np_route(unique: torch.Tensor, num_unique: torch.Tensor, cap: int, num_shard
         if inverse is not None:
             out["lookup_to_send"] = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
     ws, ws_bytes = _ws(np_route_workspace_bytes(cap, num_shards), ws, dev)
-    rc = lib.np_route(_ptr(unique), _ptr(num_unique), cap, num_shards, shard_fn, _ptr(out["send_keys"]),
-                      _ptr(out["splits"]), _ptr(out["send_offsets"]), _ptr(out["send_from_unique"]),
-                      _ptr(out["unique_to_send"]), _ptr(inverse), n if inverse is not None else 0,
-                      _ptr(out.get("lookup_to_send")) if inverse is not None else 0, _ptr(ws), ws_bytes, _stream())
+    rc = lib.np_route(_ptr(unique, torch.int64), _ptr(num_unique, torch.int32), cap, num_shards, shard_fn, _ptr(out["send_keys"], torch.int64),
+                      _ptr(out["splits"], torch.int32), _ptr(out["send_offsets"], torch.int32), _ptr(out["send_from_unique"], torch.int32),
+                      _ptr(out["unique_to_send"], torch.int32), _ptr(inverse, torch.int32), n if inverse is not None else 0,
+                      _ptr(out.get("lookup_to_send"), torch.int32) if inverse is not None else 0, _ptr(ws), ws_bytes, _stream())
     _chk("np_route", rc)
     return out
 
@@ -202,8 +206,9 @@ def np_lookup_fwd(table: torch.Tensor, list_keys: torch.Tensor, idx: Optional[to
         out = torch.empty(shape, dtype=_dt(out_dtype), device=dev)
     if want_rows and rows_out is None:
         rows_out = torch.empty((max(cap, 1), dim), dtype=torch.float32, device=dev)
-    rc = lib.np_lookup_fwd(_ptr(table), num_rows, dim, _ptr(list_keys), _ptr(num_list), cap, _ptr(idx), _ptr(bag_offsets),
-                           num_bags, n, mode, max_len, out_dtype, _ptr(out), _ptr(rows_out), 0, 0, _stream())
+    rc = lib.np_lookup_fwd(_ptr(table, torch.float32), num_rows, dim, _ptr(list_keys, torch.int64), _ptr(num_list, torch.int32), cap,
+                           _ptr(idx, torch.int32), _ptr(bag_offsets, torch.int32), num_bags, n, mode, max_len, out_dtype,
+                           _ptr(out, _dt(out_dtype)), _ptr(rows_out, torch.float32), 0, 0, _stream())
     _chk("np_lookup_fwd", rc)
     return out, rows_out
 
@@ -215,7 +220,7 @@ def _table_dtype(table: torch.Tensor) -> int:
         return BF16
     if table.dtype == torch.float16:
         return F16
-    raise NestPipeError(f"table dtype {table.dtype} is not supported (float32, bfloat16 or float16)")
+    raise TypeError(f"table dtype {table.dtype} is not supported (float32, bfloat16 or float16)")
 
 
 def np_lookup_fwd_t(table: torch.Tensor, list_keys: torch.Tensor, idx: Optional[torch.Tensor], bag_offsets: torch.Tensor,
@@ -231,8 +236,8 @@ def np_lookup_fwd_t(table: torch.Tensor, list_keys: torch.Tensor, idx: Optional[
         out = torch.empty(shape, dtype=_dt(out_dtype), device=dev)
     if want_rows and rows_out is None:
         rows_out = torch.empty((max(cap, 1), dim), dtype=table.dtype, device=dev)
-    rc = lib.np_lookup_fwd_t(_ptr(table), _table_dtype(table), num_rows, dim, _ptr(list_keys), _ptr(num_list), cap, _ptr(idx),
-                             _ptr(bag_offsets), num_bags, n, mode, max_len, out_dtype, _ptr(out), _ptr(rows_out), 0, 0, _stream())
+    rc = lib.np_lookup_fwd_t(_ptr(table), _table_dtype(table), num_rows, dim, _ptr(list_keys, torch.int64), _ptr(num_list, torch.int32), cap, _ptr(idx, torch.int32),
+                             _ptr(bag_offsets, torch.int32), num_bags, n, mode, max_len, out_dtype, _ptr(out), _ptr(rows_out), 0, 0, _stream())
     _chk("np_lookup_fwd_t", rc)
     return out, rows_out
 
@@ -254,8 +259,8 @@ def np_lookup_bwd(dY: torch.Tensor, dim: int, mode: int, max_len: int, bag_offse
     if grads is None:
         grads = torch.empty((max(cap, 1), dim), dtype=torch.float32, device=dev)
     ws, ws_bytes = _ws(np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode), ws, dev)
-    rc = lib.np_lookup_bwd(_ptr(dY), dy_dtype, dim, mode, max_len, _ptr(bag_offsets), num_bags, n, _ptr(occ_offsets),
-                           _ptr(occ), _ptr(num_unique), cap, _ptr(unique_to_send), _ptr(grads), _ptr(ws), ws_bytes,
+    rc = lib.np_lookup_bwd(_ptr(dY), dy_dtype, dim, mode, max_len, _ptr(bag_offsets, torch.int32), num_bags, n, _ptr(occ_offsets, torch.int32),
+                           _ptr(occ, torch.int32), _ptr(num_unique, torch.int32), cap, _ptr(unique_to_send, torch.int32), _ptr(grads, torch.float32), _ptr(ws), ws_bytes,
                            _stream())
     _chk("np_lookup_bwd", rc)
     return grads
@@ -271,8 +276,8 @@ def np_lookup_bwd_adagrad(dY: torch.Tensor, mode: int, max_len: int, bag_offsets
         raise ValueError("dY must be fp32 or bf16")
     dy_dtype = BF16 if dY.dtype == torch.bfloat16 else F32
     ws, ws_bytes = _ws(np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode), ws, dY.device)
-    rc = lib.np_lookup_bwd_adagrad(_ptr(dY), dy_dtype, dim, mode, max_len, _ptr(bag_offsets), num_bags, n, _ptr(occ_offsets),
-                                   _ptr(occ), _ptr(unique), _ptr(num_unique), cap, _ptr(table), _ptr(state), num_rows, lr, eps,
+    rc = lib.np_lookup_bwd_adagrad(_ptr(dY), dy_dtype, dim, mode, max_len, _ptr(bag_offsets, torch.int32), num_bags, n, _ptr(occ_offsets, torch.int32),
+                                   _ptr(occ, torch.int32), _ptr(unique, torch.int64), _ptr(num_unique, torch.int32), cap, _ptr(table, torch.float32), _ptr(state, torch.float32), num_rows, lr, eps,
                                    _ptr(ws), ws_bytes, _stream())
     _chk("np_lookup_bwd_adagrad", rc)
 
@@ -288,8 +293,8 @@ def np_lookup_bwd_adagrad_t(dY: torch.Tensor, mode: int, max_len: int, bag_offse
         raise ValueError("dY must be fp32 or bf16")
     dy_dtype = BF16 if dY.dtype == torch.bfloat16 else F32
     ws, ws_bytes = _ws(np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode), ws, dY.device)
-    rc = lib.np_lookup_bwd_adagrad_t(_ptr(dY), dy_dtype, dim, mode, max_len, _ptr(bag_offsets), num_bags, n, _ptr(occ_offsets),
-                                     _ptr(occ), _ptr(unique), _ptr(num_unique), cap, _ptr(table), _table_dtype(table), _ptr(state),
+    rc = lib.np_lookup_bwd_adagrad_t(_ptr(dY), dy_dtype, dim, mode, max_len, _ptr(bag_offsets, torch.int32), num_bags, n, _ptr(occ_offsets, torch.int32),
+                                     _ptr(occ, torch.int32), _ptr(unique, torch.int64), _ptr(num_unique, torch.int32), cap, _ptr(table), _table_dtype(table), _ptr(state, torch.float32),
                                      num_rows, lr, eps, _ptr(ws), ws_bytes, _stream())
     _chk("np_lookup_bwd_adagrad_t", rc)
 
@@ -297,7 +302,7 @@ def np_lookup_bwd_adagrad_t(dY: torch.Tensor, mode: int, max_len: int, bag_offse
 def np_sparse_adagrad(table: torch.Tensor, state: torch.Tensor, list_keys: torch.Tensor, grads: torch.Tensor,
                       num_list: torch.Tensor, cap: int, lr: float, eps: float) -> None:
     num_rows, dim = table.shape
-    rc = lib.np_sparse_adagrad(_ptr(table), _ptr(state), num_rows, dim, _ptr(list_keys), _ptr(grads), _ptr(num_list), cap,
+    rc = lib.np_sparse_adagrad(_ptr(table, torch.float32), _ptr(state, torch.float32), num_rows, dim, _ptr(list_keys, torch.int64), _ptr(grads, torch.float32), _ptr(num_list, torch.int32), cap,
                                lr, eps, _stream())
     _chk("np_sparse_adagrad", rc)
 
@@ -305,8 +310,8 @@ def np_sparse_adagrad(table: torch.Tensor, state: torch.Tensor, list_keys: torch
 def np_sparse_adagrad_t(table: torch.Tensor, state: torch.Tensor, list_keys: torch.Tensor, grads: torch.Tensor,
                         num_list: torch.Tensor, cap: int, lr: float, eps: float) -> None:
     num_rows, dim = table.shape
-    rc = lib.np_sparse_adagrad_t(_ptr(table), _table_dtype(table), _ptr(state), num_rows, dim, _ptr(list_keys), _ptr(grads),
-                                 _ptr(num_list), cap, lr, eps, _stream())
+    rc = lib.np_sparse_adagrad_t(_ptr(table), _table_dtype(table), _ptr(state, torch.float32), num_rows, dim, _ptr(list_keys, torch.int64), _ptr(grads, torch.float32),
+                                 _ptr(num_list, torch.int32), cap, lr, eps, _stream())
     _chk("np_sparse_adagrad_t", rc)
 
 
@@ -319,8 +324,8 @@ def np_intersect(keys_a: torch.Tensor, num_a: torch.Tensor, cap_a: int, keys_b: 
         out = dict(idx_a=torch.empty(m, dtype=torch.int32, device=dev), idx_b=torch.empty(m, dtype=torch.int32, device=dev),
                    num_common=torch.empty(1, dtype=torch.int32, device=dev))
     ws, ws_bytes = _ws(int(lib.np_intersect_workspace_bytes(cap_b)), ws, dev)
-    rc = lib.np_intersect(_ptr(keys_a), _ptr(num_a), cap_a, _ptr(keys_b), _ptr(num_b), cap_b, _ptr(out["idx_a"]),
-                          _ptr(out["idx_b"]), _ptr(out["num_common"]), _ptr(ws), ws_bytes, _stream())
+    rc = lib.np_intersect(_ptr(keys_a, torch.int64), _ptr(num_a, torch.int32), cap_a, _ptr(keys_b, torch.int64), _ptr(num_b, torch.int32), cap_b, _ptr(out["idx_a"], torch.int32),
+                          _ptr(out["idx_b"], torch.int32), _ptr(out["num_common"], torch.int32), _ptr(ws), ws_bytes, _stream())
     _chk("np_intersect", rc)
     return out
 
@@ -328,20 +333,20 @@ def np_intersect(keys_a: torch.Tensor, num_a: torch.Tensor, cap_a: int, keys_b: 
 def np_sync_rows(src_rows: torch.Tensor, src_idx: torch.Tensor, dst_rows: torch.Tensor, dst_idx: torch.Tensor,
                  count: torch.Tensor, cap: int) -> None:
     dim = src_rows.shape[1]
-    rc = lib.np_sync_rows(_ptr(src_rows), _ptr(src_idx), _ptr(dst_rows), _ptr(dst_idx), _ptr(count), cap, dim, _stream())
+    rc = lib.np_sync_rows(_ptr(src_rows), _ptr(src_idx, torch.int32), _ptr(dst_rows), _ptr(dst_idx, torch.int32), _ptr(count, torch.int32), cap, dim, _stream())
     _chk("np_sync_rows", rc)
 
 
 def np_util_table_init(table: torch.Tensor, seed: int) -> None:
     num_rows, dim = table.shape
-    _chk("np_util_table_init", lib.np_util_table_init(_ptr(table), num_rows, dim, seed, _stream()))
+    _chk("np_util_table_init", lib.np_util_table_init(_ptr(table, torch.float32), num_rows, dim, seed, _stream()))
 
 
 def np_util_table_count_changed(table: torch.Tensor, seed: int) -> int:
     """Rows of ``table`` that differ from the initialiser (synchronises)."""
     num_rows, dim = table.shape
     cnt = torch.zeros(1, dtype=torch.int64, device=table.device)
-    _chk("np_util_table_count_changed", lib.np_util_table_count_changed(_ptr(table), num_rows, dim, seed, _ptr(cnt), _stream()))
+    _chk("np_util_table_count_changed", lib.np_util_table_count_changed(_ptr(table, torch.float32), num_rows, dim, seed, _ptr(cnt), _stream()))
     return int(cnt.item())
 
 
