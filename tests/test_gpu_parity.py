@@ -563,3 +563,20 @@ def test_stream_copy_yardstick_copies_every_word(H, words):
     torch.cuda.synchronize()
     assert torch.equal(dst[: words * 4], src[: words * 4])
     assert bool((dst[words * 4:] == -1).all())
+
+
+def test_binding_refuses_tensors_of_the_wrong_element_type(H):
+    import torch
+    B = H.B
+    keys32 = torch.arange(100, dtype=torch.int32, device="cuda")
+    with pytest.raises(TypeError):
+        B.np_dedup(keys32, 10)
+    table64 = torch.zeros((8, 4), dtype=torch.float64, device="cuda")
+    off = torch.tensor([0, 2], dtype=torch.int32, device="cuda")
+    keys = torch.tensor([1, 2], dtype=torch.int64, device="cuda")
+    with pytest.raises(TypeError):
+        B.np_lookup_fwd(table64, keys, None, off, 2, B.POOL_SUM)
+    with pytest.raises(TypeError):
+        B.np_lookup_fwd_t(table64, keys, None, off, 2, B.POOL_SUM)
+    with pytest.raises(ValueError):
+        B.np_dedup(torch.arange(100, dtype=torch.int64), 10)          # host tensor
