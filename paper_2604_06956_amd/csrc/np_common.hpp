@@ -103,7 +103,7 @@ __device__ __forceinline__ int wave_incl_scan(int v) {
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
         int t = __shfl_up(v, d, kWave);
-        if (__lane_id() >= d) v += t;
+        if (static_cast<int>(__lane_id()) >= d) v += t;
     }
     return v;
 }
