@@ -41,8 +41,8 @@ constexpr int kOrderBuckets = 1024;   // relative positions inside a long segmen
 #ifndef NP_ORDER_XCD_SPLIT
 #define NP_ORDER_XCD_SPLIT 1
 #endif
-constexpr int kOrderMinCount = NP_ORDER_MIN_COUNT;
-constexpr size_t kOrderMinDyBytes = size_t(256) << 20;  // the Infinity Cache: a dY that fits it is re-read from there anyway  // segments at least this long take part in the locality order
+constexpr int kOrderMinCount = NP_ORDER_MIN_COUNT;       // segments at least this long take part in the locality order
+constexpr size_t kOrderMinDyBytes = size_t(256) << 20;  // the Infinity Cache: a dY that fits it is re-read from there anyway
 
 // One entry per 64 consecutive lookups: where bags start inside the block and which bag the block begins in.
 // 16 bytes per 64 lookups (n/4 bytes in all), so the random reads of bwd_main mostly stay in L2 / Infinity Cache.
