@@ -48,7 +48,9 @@ def build_selftest(out: Optional[str] = None) -> str:
 def _load():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        # NP_ORACLE_LIB: load another build of np_oracle.c instead (the tests point it at deliberately broken copies
+        # to show that the pins notice them)
+        _lib = ctypes.CDLL(os.environ.get("NP_ORACLE_LIB") or build())
         _lib.np_ref_mix.restype = ctypes.c_uint64
         _lib.np_ref_mix.argtypes = [ctypes.c_uint64]
         _lib.np_ref_shard.restype = ctypes.c_int32

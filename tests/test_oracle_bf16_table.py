@@ -115,3 +115,16 @@ def test_adagrad_bf16_zero_gradient_keeps_bits_and_matches_fp32_rule(oracle):
     # and rounding the fp32 result again lands on the same pattern except where the fp32 value sits on a bf16 tie
     again = _bits(t32[keys])
     assert np.mean(again == tbits[keys]) > 0.99
+
+
+def test_adagrad_bf16_rounds_the_fp64_step_once(oracle):
+    """A step whose exact result lies just above the midpoint of two bf16 neighbours: rounding it to fp32 first lands on
+    the midpoint and the tie then goes to the even neighbour below; rounding once goes up.  old = 1, g = -1, state 0,
+    eps = 0, lr = 2^-8 + 2^-30 (exact in fp32) -> G = 1, new = 1 + 2^-8 + 2^-30 -> bf16 1 + 2^-7."""
+    table = np.array([[0x3F80]], dtype=np.uint16)                     # 1.0
+    state = np.zeros(1, np.float32)
+    lr = float(np.float32(2.0 ** -8 + 2.0 ** -30))
+    assert lr == 2.0 ** -8 + 2.0 ** -30
+    oracle.sparse_adagrad_bf16(table, state, [0], np.array([[-1.0]], np.float32), lr, 0.0)
+    assert state[0] == 1.0
+    assert table[0, 0] == 0x3F81                                       # 1 + 2^-7; the two-step rounding would give 0x3F80

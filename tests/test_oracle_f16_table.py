@@ -117,3 +117,15 @@ def test_adagrad_f16_closed_form_zero_gradient_and_fp32_rule(oracle):
     got = tb.view(np.float16).astype(np.float32)
     assert np.all(np.abs(got[keys] - t32[keys]) <= np.abs(t32[keys]) * (2.0 ** -11 + 2.0 ** -23) + 2.0 ** -25)
     assert np.mean(_bits(t32[keys]) == tb[keys]) > 0.99
+
+
+def test_adagrad_f16_rounds_the_fp64_step_once(oracle):
+    """old = 1, g = -1, state 0, eps = 0, lr = 2^-11 + 2^-30: the exact new value 1 + 2^-11 + 2^-30 lies just above the
+    midpoint of 1 and 1 + 2^-10; through fp32 it would become the midpoint and then the even neighbour 1."""
+    table = np.array([[0x3C00]], dtype=np.uint16)                     # 1.0
+    state = np.zeros(1, np.float32)
+    lr = float(np.float32(2.0 ** -11 + 2.0 ** -30))
+    assert lr == 2.0 ** -11 + 2.0 ** -30
+    oracle.sparse_adagrad_f16(table, state, [0], np.array([[-1.0]], np.float32), lr, 0.0)
+    assert state[0] == 1.0
+    assert table[0, 0] == 0x3C01                                       # 1 + 2^-10
