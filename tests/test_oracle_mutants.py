@@ -61,6 +61,18 @@ MUTANTS = [
      "w[d] = table_dtype == REF_BF16 ? np_ref_f32_to_bf16((float)upd) : np_ref_f64_to_f16((double)(float)upd);",
      ["test_oracle_bf16_table.py", "test_oracle_f16_table.py"]),
     ("fp16: one significant bit too few", "double r = ref_round_sig(a, 11, -24);", "double r = ref_round_sig(a, 10, -24);", ["test_oracle_f16_table.py"]),
+    ("bwd: tolerance scale inflated", "if (abs_out) abs_out[dst + d] += fabs(w * y);", "if (abs_out) abs_out[dst + d] += 16.0 * fabs(w * y);",
+     ["test_oracle_bwd.py"]),
+    ("fwd: tolerance scale inflated", "aab[d] += fabs(v);", "aab[d] += 16.0 * fabs(v);", ["test_oracle_fwd.py"]),
+    ("compose: the send permutation is not applied", "lookup_to_send[j] = unique_to_send[inverse[j]];", "lookup_to_send[j] = inverse[j];",
+     ["test_oracle_route.py"]),
+    ("fwd: rows_out copied by slot instead of by key", "memcpy(rows_out + (size_t)p * (size_t)dim, table + (size_t)row * (size_t)dim,",
+     "memcpy(rows_out + (size_t)p * (size_t)dim, table + (size_t)p * (size_t)dim,", ["test_oracle_fwd.py"]),
+    ("fp16 decoder: exponent bias off by one", "else v = ldexp(1.0 + (double)f / 1024.0, e - 15);", "else v = ldexp(1.0 + (double)f / 1024.0, e - 14);",
+     ["test_oracle_f16_table.py"]),
+    ("bf16 from fp64: subnormal spacing of the wrong format", "double r = ref_round_sig(a, 8, -133);", "double r = ref_round_sig(a, 8, -126);",
+     ["test_oracle_bf16_table.py"]),
+    ("dedup: empty batch leaves the count unset", "*num_unique = 0;\n        occ_offsets[0] = 0;", "occ_offsets[0] = 0;", ["test_oracle_dedup.py"]),
     ("intersect: indices of the second list off by one", "idx_b[c] = j;", "idx_b[c] = j > 0 ? j - 1 : 0;", ["test_oracle_dbsync.py"]),
     ("sync_rows: source and destination rows exchanged", "memcpy(dst + (size_t)dst_idx[i] * (size_t)dim, src + (size_t)src_idx[i] * (size_t)dim,",
      "memcpy(dst + (size_t)dst_idx[i] * (size_t)dim, src + (size_t)src_idx[count - 1 - i] * (size_t)dim,", ["test_oracle_dbsync.py"]),
