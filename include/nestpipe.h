@@ -274,6 +274,17 @@ int np_util_table_count_changed(const float* table, int64_t num_rows, int32_t di
 int np_util_table_count_changed_t(const void* table, int32_t table_dtype, int64_t num_rows, int32_t dim, uint64_t seed,
                                   unsigned long long* d_count, void* stream);
 
+/*
+ * Check the preconditions that the hot-path calls do not check on the device (a debugging aid: one pass over the
+ * batch).  d_errors (device, 4 x uint64) is overwritten with counts of
+ *   [0] keys outside [0, num_rows)            [1] positions b with bag_offsets[b+1] < bag_offsets[b]
+ *   [2] 1 if bag_offsets[0] != 0              [3] 1 if bag_offsets[num_bags] != n
+ * All four zero means the batch is well formed.  keys may be NULL (n = 0) and bag_offsets may be NULL (num_bags = 0):
+ * the corresponding checks are skipped.
+ */
+int np_util_check_batch(const int64_t* keys, int32_t n, int64_t num_rows, const int32_t* bag_offsets, int32_t num_bags,
+                        unsigned long long* d_errors, void* stream);
+
 /* Plain device copy of `bytes` (multiple of 16) with 16-byte loads and stores: the bandwidth yardstick. */
 int np_util_stream_copy(void* dst, const void* src, size_t bytes, void* stream);
 

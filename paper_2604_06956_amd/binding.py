@@ -83,6 +83,8 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.np_util_table_init.argtypes = [_vp, _i64, _i32, _u64, _vp]
     L.np_util_table_count_changed.restype = ctypes.c_int
     L.np_util_table_count_changed.argtypes = [_vp, _i64, _i32, _u64, _vp, _vp]
+    L.np_util_check_batch.restype = ctypes.c_int
+    L.np_util_check_batch.argtypes = [_vp, _i32, _i64, _vp, _i32, _vp, _vp]
     L.np_util_stream_copy.restype = ctypes.c_int
     L.np_util_stream_copy.argtypes = [_vp, _vp, _sz, _vp]
     L.np_prof_enable.restype = ctypes.c_int
@@ -362,6 +364,17 @@ def np_util_table_count_changed_t(table: torch.Tensor, seed: int) -> int:
     _chk("np_util_table_count_changed_t",
          lib.np_util_table_count_changed_t(_ptr(table), _table_dtype(table), num_rows, dim, seed, _ptr(cnt), _stream()))
     return int(cnt.item())
+
+
+def np_util_check_batch(keys: Optional[torch.Tensor], num_rows: int, bag_offsets: Optional[torch.Tensor]) -> Tuple[int, int, int, int]:
+    """Precondition check (synchronises): (keys out of range, decreasing offsets, offsets[0] != 0, offsets[-1] != n)."""
+    n = keys.numel() if keys is not None else 0
+    num_bags = bag_offsets.numel() - 1 if bag_offsets is not None else 0
+    dev = keys.device if keys is not None else bag_offsets.device
+    err = torch.empty(4, dtype=torch.int64, device=dev)
+    _chk("np_util_check_batch", lib.np_util_check_batch(_ptr(keys, torch.int64), n, num_rows, _ptr(bag_offsets, torch.int32), num_bags,
+                                                        _ptr(err), _stream()))
+    return tuple(int(v) for v in err.tolist())
 
 
 def np_util_stream_copy(dst: torch.Tensor, src: torch.Tensor) -> None:

@@ -580,3 +580,30 @@ def test_binding_refuses_tensors_of_the_wrong_element_type(H):
         B.np_lookup_fwd_t(table64, keys, None, off, 2, B.POOL_SUM)
     with pytest.raises(ValueError):
         B.np_dedup(torch.arange(100, dtype=torch.int64), 10)          # host tensor
+
+
+def test_batch_precondition_check(H):
+    import torch
+    B = H.B
+    rng = np.random.default_rng(77)
+    R, nb = 5000, 3000
+    lens = rng.integers(0, 9, nb)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    n = int(off[-1])
+    keys = rng.integers(0, R, n).astype(np.int64)
+    assert B.np_util_check_batch(H.dev(keys), R, H.dev(off)) == (0, 0, 0, 0)
+    bad = keys.copy()
+    bad[[5, 700, n - 1]] = [-1, R, R + 5]
+    assert B.np_util_check_batch(H.dev(bad), R, H.dev(off)) == (3, 0, 0, 0)
+    off2 = off.copy()
+    off2[100] = off2[101] + 1          # one decreasing step (off2[99] <= off2[100] still holds or not: count both ways)
+    want_steps = int(np.sum(np.diff(off2.astype(np.int64)) < 0))
+    assert want_steps >= 1
+    assert B.np_util_check_batch(H.dev(keys), R, H.dev(off2)) == (0, want_steps, 0, 0)
+    off3 = off.copy()
+    off3[0] = 1
+    off3[-1] = n + 2
+    got = B.np_util_check_batch(H.dev(keys), R, H.dev(off3))
+    assert got[2] == 1 and got[3] == 1
+    assert B.np_util_check_batch(None, R, H.dev(np.zeros(1, np.int32))) == (0, 0, 0, 0)
+    assert B.np_util_check_batch(H.dev(keys), R, None)[0] == 0
