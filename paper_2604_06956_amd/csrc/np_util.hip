@@ -164,7 +164,7 @@ __global__ void __launch_bounds__(256) stream_copy_kernel(float4* __restrict__ d
 
 extern "C" {
 
-int np_version(void) { return 10100; }  // 1.1.0: 16-bit tables, optional inverse map, np_prof_only
+int np_version(void) { return 10200; }  // 1.2.0: np_util_check_batch, wider loads of bf16 upstream gradients
 
 const char* np_status_string(int status) {
     switch (status) {
