@@ -114,3 +114,64 @@ def test_captured_step_replays_bit_exactly(H, name, row_div, batch_div):
         scratch.normal_()
         torch.cuda.synchronize()
         assert int(other["num_unique"].item()) <= 1000
+
+
+def test_two_steps_on_two_streams_do_not_interfere(H):
+    """Two independent steps (own tables, buffers and workspaces) enqueued alternately call by call on two streams give
+    the bits of the same steps run one after the other: the calls share no hidden state."""
+    import torch
+    wl, B = H.wl, H.B
+    cfgs = [wl.scaled(wl.config("skew"), 128, 16), wl.scaled(wl.config("dlrm"), 64, 16)]
+    work = []
+    for cfg in cfgs:
+        b = wl.make_batch(cfg, 0)
+        work.append(dict(cfg=cfg, keys=H.dev(b.keys), off=H.dev(b.bag_offsets), dY=H.dev(b.dY), n=b.n, cap=b.n, max_len=b.max_len))
+
+    def fresh(w):
+        cfg = w["cfg"]
+        table = torch.empty((cfg.num_rows, cfg.dim), dtype=torch.float32, device="cuda")
+        B.np_util_table_init(table, cfg.table_seed)
+        state = torch.zeros(cfg.num_rows, dtype=torch.float32, device="cuda")
+        return table, state, _buffers(H, cfg, w["n"], w["cap"], w["max_len"])
+
+    # one after the other on the current stream
+    ref = []
+    for w in work:
+        table, state, bufs = fresh(w)
+        for _ in range(2):
+            _step(H, w["cfg"], w["keys"], w["off"], w["dY"], w["n"], w["cap"], w["max_len"], table, state, bufs)
+        torch.cuda.synchronize()
+        ref.append(_snapshot(H, bufs, table, state))
+
+    # interleaved call by call on two streams
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    live = [fresh(w) for w in work]
+    torch.cuda.synchronize()
+
+    def calls(w, table, state, bufs):
+        cfg, n, cap, max_len = w["cfg"], w["n"], w["cap"], w["max_len"]
+        dd, rr, ws, out, grads = bufs
+        yield lambda: B.np_dedup(w["keys"], cfg.key_bits, out=dd, ws=ws["d"])
+        yield lambda: B.np_route(dd["unique"], dd["num_unique"], cap, cfg.num_shards, cfg.shard_fn, inverse=dd["inverse"], n=n, out=rr,
+                                 ws=ws["r"])
+        yield lambda: B.np_lookup_fwd(table, rr["send_keys"], rr["lookup_to_send"], w["off"], n, cfg.mode, max_len, B.F32,
+                                      num_list=dd["num_unique"], cap=cap, out=out)
+        yield lambda: B.np_lookup_bwd(w["dY"], cfg.dim, cfg.mode, max_len, w["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"],
+                                      cap, unique_to_send=rr["unique_to_send"], grads=grads, ws=ws["b"])
+        yield lambda: B.np_sparse_adagrad(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
+
+    for _ in range(2):
+        its = [calls(w, *lv) for w, lv in zip(work, live)]
+        for pair in zip(*its):
+            for st, call in zip(streams, pair):
+                with torch.cuda.stream(st):
+                    call()
+    torch.cuda.synchronize()
+    for w, lv, want in zip(work, live, ref):
+        table, state, bufs = lv
+        got = _snapshot(H, bufs, table, state)
+        for k, v in want.items():
+            if k == "U":
+                assert got["U"] == v
+            else:
+                assert got[k].tobytes() == v.tobytes(), f"{w['cfg'].name}: {k} differs when run beside another step"
