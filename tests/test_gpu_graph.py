@@ -175,3 +175,65 @@ def test_two_steps_on_two_streams_do_not_interfere(H):
                 assert got["U"] == v
             else:
                 assert got[k].tobytes() == v.tobytes(), f"{w['cfg'].name}: {k} differs when run beside another step"
+
+
+def test_two_host_threads_issue_steps_concurrently(H):
+    """The same two independent steps issued from two host threads at once, each on a stream of its own."""
+    import threading
+
+    import torch
+    wl, B = H.wl, H.B
+    cfgs = [wl.scaled(wl.config("skew"), 128, 16), wl.scaled(wl.config("large"), 2048, 64)]
+    work = []
+    for cfg in cfgs:
+        b = wl.make_batch(cfg, 0)
+        work.append(dict(cfg=cfg, keys=H.dev(b.keys), off=H.dev(b.bag_offsets), dY=H.dev(b.dY), n=b.n, cap=b.n, max_len=b.max_len))
+
+    def fresh(w):
+        cfg = w["cfg"]
+        table = torch.empty((cfg.num_rows, cfg.dim), dtype=torch.float32, device="cuda")
+        B.np_util_table_init(table, cfg.table_seed)
+        state = torch.zeros(cfg.num_rows, dtype=torch.float32, device="cuda")
+        return table, state, _buffers(H, cfg, w["n"], w["cap"], w["max_len"])
+
+    reps = 5
+    ref = []
+    for w in work:
+        table, state, bufs = fresh(w)
+        for _ in range(reps):
+            _step(H, w["cfg"], w["keys"], w["off"], w["dY"], w["n"], w["cap"], w["max_len"], table, state, bufs)
+        torch.cuda.synchronize()
+        ref.append(_snapshot(H, bufs, table, state))
+
+    live = [fresh(w) for w in work]
+    torch.cuda.synchronize()
+    errors = []
+    gate = threading.Barrier(2)
+
+    def run(w, lv):
+        try:
+            torch.cuda.set_device(0)
+            st = torch.cuda.Stream()
+            gate.wait(timeout=60)
+            with torch.cuda.stream(st):
+                for _ in range(reps):
+                    _step(H, w["cfg"], w["keys"], w["off"], w["dY"], w["n"], w["cap"], w["max_len"], *lv)
+            st.synchronize()
+        except Exception as e:  # noqa: BLE001  (reported by the main thread)
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=run, args=(w, lv)) for w, lv in zip(work, live)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=120)
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for w, lv, want in zip(work, live, ref):
+        table, state, bufs = lv
+        got = _snapshot(H, bufs, table, state)
+        for k, v in want.items():
+            if k == "U":
+                assert got["U"] == v
+            else:
+                assert got[k].tobytes() == v.tobytes(), f"{w['cfg'].name}: {k} differs when issued from a second thread"
