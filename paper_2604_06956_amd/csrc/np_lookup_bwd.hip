@@ -4,8 +4,9 @@
 //
 // A deterministic segmented reduction over np_dedup's occurrence lists, balanced under any skew:
 //
-//   bwd_bagmap     a bitmap of bag starts plus one bag index per 64 lookups: lookup -> bag in one 16-byte read
-//   bwd_tile_seg0  for every tile of 256 consecutive sorted positions, the key segment its first position is in
+//   bwd_prepare    two independent preparations in one launch:
+//                  the bag map, a bitmap of bag starts plus one bag index per 64 lookups (lookup -> bag in one 16-byte
+//                  read), and, for every tile of 256 consecutive sorted positions, the key segment its first position is in
 //   bwd_order      execution order of the tiles (it changes no result, only which dY rows are in cache): the lookups
 //                  of one key are spread evenly over the bags, so the tiles of all long segments are run sorted by
 //                  their relative position inside their segment, one contiguous range of relative positions per
@@ -52,9 +53,8 @@ struct __align__(16) BagMapEntry {
     int32_t start0;   // bag_offsets[bag0]
 };
 
-__global__ void __launch_bounds__(256)
-bwd_bagmap_kernel(const int32_t* __restrict__ bag_offsets, int num_bags, int n, BagMapEntry* __restrict__ map) {
-    const int w = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void bagmap_entry(int w, const int32_t* __restrict__ bag_offsets, int num_bags, int n,
+                                              BagMapEntry* __restrict__ map) {
     const int64_t base64 = static_cast<int64_t>(w) * 64;
     if (base64 >= n) return;
     const int base = static_cast<int>(base64);
@@ -97,10 +97,8 @@ __device__ __forceinline__ void bag_of_lookup(const BagMapEntry* __restrict__ ma
     }
 }
 
-__global__ void __launch_bounds__(256)
-bwd_tile_seg0_kernel(const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ d_num_unique, int num_tiles,
-                     int32_t* __restrict__ tile_seg0, int32_t* __restrict__ long_count) {
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void tile_first_segment(int t, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ d_num_unique,
+                                                   int num_tiles, int32_t* __restrict__ tile_seg0, int32_t* __restrict__ long_count) {
     if (t == 0) *long_count = 0;  // the list of long chains is rebuilt by every call
     if (t >= num_tiles) return;
     const int pos = t * kBwdTile;
@@ -111,6 +109,18 @@ bwd_tile_seg0_kernel(const int32_t* __restrict__ occ_offsets, const int32_t* __r
         else hi = mid;
     }
     tile_seg0[t] = lo;
+}
+
+// The two preparations that depend on nothing but the batch's index arrays, in one launch: the first map_blocks blocks
+// write the bag map (one entry per thread), the rest find the first segment of every tile (one tile per thread).
+__global__ void __launch_bounds__(256)
+bwd_prepare_kernel(const int32_t* __restrict__ bag_offsets, int num_bags, int n, BagMapEntry* __restrict__ map, int map_blocks,
+                   const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ d_num_unique, int num_tiles,
+                   int32_t* __restrict__ tile_seg0, int32_t* __restrict__ long_count) {
+    if (static_cast<int>(blockIdx.x) < map_blocks)
+        bagmap_entry(blockIdx.x * 256 + threadIdx.x, bag_offsets, num_bags, n, map);
+    else
+        tile_first_segment((blockIdx.x - map_blocks) * 256 + threadIdx.x, occ_offsets, d_num_unique, num_tiles, tile_seg0, long_count);
 }
 
 // Partition policy that sorts tiles by the bucket of their relative position inside a long segment; tiles that are
@@ -627,10 +637,9 @@ void bwd_launch(const BwdArgs& a) {
     uint32_t* oH = cur.take<uint32_t>(part_hist_elems(oplan, kOrderBuckets + 1));
     uint32_t* obin = cur.take<uint32_t>(kOrderBuckets + 1);
     const int seq = a.mode == NP_SEQ ? 1 : 0;
-    NP_LAUNCH("bwd_bagmap", bwd_bagmap_kernel, dim3((map_entries + 255) / 256), dim3(256), 0, a.stream, a.bag_offsets, a.num_bags,
-              a.n, bagmap);
-    NP_LAUNCH("bwd_tile_seg0", bwd_tile_seg0_kernel, dim3((L.num_tiles + 255) / 256), dim3(256), 0, a.stream, a.occ_offsets,
-              a.d_num_unique, L.num_tiles, tile_seg0, long_count);
+    const int map_blocks = (map_entries + 255) / 256, seg_blocks = (L.num_tiles + 255) / 256;
+    NP_LAUNCH("bwd_prepare", bwd_prepare_kernel, dim3(map_blocks + seg_blocks), dim3(256), 0, a.stream, a.bag_offsets, a.num_bags,
+              a.n, bagmap, map_blocks, a.occ_offsets, a.d_num_unique, L.num_tiles, tile_seg0, long_count);
     // The locality order pays when dY is larger than the last-level cache (2.42 -> 2.06 ms at 1.3 GB); below that it only
     // costs three launches (0.63 -> 0.57 ms per step at 109 MB).
     const size_t dy_bytes = static_cast<size_t>(a.num_bags) * (seq ? a.max_len : 1) * a.dim * (a.dy_dtype == NP_BF16 ? 2 : 4);
