@@ -283,6 +283,37 @@ def main() -> int:
         sharded_ms = (time.perf_counter() - ts) * 1e3 / args.steps
         del l2s, rows_buf
 
+    # ---- the backward in two parts: its index work (np_lookup_bwd_prepare) behind np_route on the second stream, beside
+    # the forward; the reduction (np_lookup_bwd_prepared) where np_lookup_bwd was.  Same bits; reported beside the headline.
+    dy_dtype_code = B.BF16 if seq else B.F32
+
+    def step_split(i: int) -> None:
+        bt = dbatch[i % 2]
+        n = bt["n"]
+        main_stream = torch.cuda.current_stream()
+        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
+        ev_dedup.record(main_stream)
+        side_stream.wait_event(ev_dedup)
+        with torch.cuda.stream(side_stream):
+            B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
+            B.np_lookup_bwd_prepare(dy_dtype_code, D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["num_unique"], ws_b)
+            ev_route.record(side_stream)
+        fwd_call(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
+                 num_list=dd["num_unique"], cap=cap, out=out)
+        main_stream.wait_event(ev_route)
+        B.np_lookup_bwd_prepared(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
+                                 ws_b, unique_to_send=rr["unique_to_send"], grads=grads)
+        adagrad_call(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
+
+    for i in range(2):
+        step_split(args.warmup + i)
+    torch.cuda.synchronize()
+    tsp = time.perf_counter()
+    for i in range(args.steps):
+        step_split(args.warmup + i)
+    torch.cuda.synchronize()
+    split_ms = (time.perf_counter() - tsp) * 1e3 / args.steps
+
     # ---- the same K steps without event recording (what the events cost)
     torch.cuda.synchronize()
     t2 = time.perf_counter()
@@ -449,6 +480,8 @@ def main() -> int:
                   for c in alg},
         "kernels": kernels,
         "streams": "np_route runs on a second stream beside np_lookup_fwd; its event times include that sharing",
+        "prepared_bwd_step": {"ms_per_step": split_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (split_ms * 1e-3 * args.steps),
+                              "what": "np_lookup_bwd_prepare behind np_route on the second stream, np_lookup_bwd_prepared after the forward"},
         "local_table_step": {"ms_per_step": local_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (local_ms * 1e-3 * args.steps),
                              "what": "np_dedup without the inverse map, forward over the raw keys; no events"},
         "sharded_flow_step": None if sharded_ms is None else {

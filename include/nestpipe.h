@@ -169,6 +169,27 @@ int np_lookup_bwd(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, i
 size_t np_lookup_bwd_workspace_bytes(int32_t num_bags, int32_t n, int32_t dim, int32_t mode);
 
 /*
+ * np_lookup_bwd in two parts, for callers that want the part that does not need dY out of the way early (the dense
+ * model runs between the forward and the backward; in that time the index work can already be done):
+ *
+ *   np_lookup_bwd_prepare   everything that depends on bag_offsets and occ_offsets alone (lookup -> bag map, first key
+ *                           segment of every tile, the order in which tiles run); written into ws.
+ *   np_lookup_bwd_prepared  the reduction itself; ws must be the buffer a np_lookup_bwd_prepare call with the same
+ *                           dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets and d_num_unique has
+ *                           completed on (order the two through the stream or an event), untouched in between.
+ *
+ * np_lookup_bwd_prepare followed by np_lookup_bwd_prepared gives the bits of np_lookup_bwd.  Arguments, errors and the
+ * workspace size are those of np_lookup_bwd.
+ */
+int np_lookup_bwd_prepare(int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len, const int32_t* bag_offsets,
+                          int32_t num_bags, int32_t n, const int32_t* occ_offsets, const int32_t* d_num_unique, void* ws,
+                          size_t ws_bytes, void* stream);
+int np_lookup_bwd_prepared(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
+                           const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
+                           const int32_t* occ, const int32_t* d_num_unique, int32_t cap, const int32_t* unique_to_send,
+                           float* grads, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * np_sparse_adagrad - Section IV-B: gradients are applied directly to the vectors held in HBM; Eq. (2):
  * keys outside the batch keep their vectors bit for bit.  The paper's update is plain SGD; this build's
  * benchmark definition asks for row-wise Adagrad, one fp32 accumulator per row:

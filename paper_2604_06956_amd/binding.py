@@ -54,6 +54,10 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.np_lookup_fwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
     L.np_lookup_bwd.restype = ctypes.c_int
     L.np_lookup_bwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
+    L.np_lookup_bwd_prepared.restype = ctypes.c_int
+    L.np_lookup_bwd_prepared.argtypes = L.np_lookup_bwd.argtypes
+    L.np_lookup_bwd_prepare.restype = ctypes.c_int
+    L.np_lookup_bwd_prepare.argtypes = [_i32, _i32, _i32, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]
     L.np_lookup_bwd_workspace_bytes.restype = _sz
     L.np_lookup_bwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
     L.np_lookup_bwd_adagrad.restype = ctypes.c_int
@@ -265,6 +269,34 @@ def np_lookup_bwd(dY: torch.Tensor, dim: int, mode: int, max_len: int, bag_offse
                            _ptr(occ, torch.int32), _ptr(num_unique, torch.int32), cap, _ptr(unique_to_send, torch.int32), _ptr(grads, torch.float32), _ptr(ws), ws_bytes,
                            _stream())
     _chk("np_lookup_bwd", rc)
+    return grads
+
+
+def np_lookup_bwd_prepare(dy_dtype: int, dim: int, mode: int, max_len: int, bag_offsets: torch.Tensor, n: int,
+                          occ_offsets: torch.Tensor, num_unique: torch.Tensor, ws: torch.Tensor) -> None:
+    """The part of np_lookup_bwd that needs no dY, written into ``ws`` (hand the same ``ws`` to np_lookup_bwd_prepared)."""
+    num_bags = bag_offsets.numel() - 1
+    rc = lib.np_lookup_bwd_prepare(dy_dtype, dim, mode, max_len, _ptr(bag_offsets, torch.int32), num_bags, n,
+                                   _ptr(occ_offsets, torch.int32), _ptr(num_unique, torch.int32), _ptr(ws),
+                                   ws.numel() * ws.element_size(), _stream())
+    _chk("np_lookup_bwd_prepare", rc)
+
+
+def np_lookup_bwd_prepared(dY: torch.Tensor, dim: int, mode: int, max_len: int, bag_offsets: torch.Tensor, n: int,
+                           occ_offsets: torch.Tensor, occ: torch.Tensor, num_unique: torch.Tensor, cap: int, ws: torch.Tensor,
+                           unique_to_send: Optional[torch.Tensor] = None, grads: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """np_lookup_bwd on a workspace that np_lookup_bwd_prepare has filled for the same batch."""
+    if dY.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("dY must be fp32 or bf16")
+    num_bags = bag_offsets.numel() - 1
+    dy_dtype = BF16 if dY.dtype == torch.bfloat16 else F32
+    if grads is None:
+        grads = torch.empty((max(cap, 1), dim), dtype=torch.float32, device=dY.device)
+    rc = lib.np_lookup_bwd_prepared(_ptr(dY), dy_dtype, dim, mode, max_len, _ptr(bag_offsets, torch.int32), num_bags, n,
+                                    _ptr(occ_offsets, torch.int32), _ptr(occ, torch.int32), _ptr(num_unique, torch.int32), cap,
+                                    _ptr(unique_to_send, torch.int32), _ptr(grads, torch.float32), _ptr(ws),
+                                    ws.numel() * ws.element_size(), _stream())
+    _chk("np_lookup_bwd_prepared", rc)
     return grads
 
 

@@ -617,42 +617,83 @@ struct BwdArgs {
     RowSink sink;
     void* ws;
     hipStream_t stream;
+    bool prepared;  // the workspace already holds what bwd_prepare_launch writes (np_lookup_bwd_prepare ran on it)
 };
+
+// Where everything lives in the caller's workspace, and whether the tile order is used.  A function of the sizes and
+// modes alone, so the preparing call and the reducing call agree on it.
+struct BwdPlan {
+    BagMapEntry* bagmap;
+    float* tile_left;
+    float* tile_right;
+    int32_t* tile_seg0;
+    int32_t* tile_rseg;
+    int32_t* order;
+    int32_t* long_tiles;
+    int32_t* long_count;
+    int32_t* order_offsets;
+    uint32_t* oH;
+    uint32_t* obin;
+    ChunkPlan oplan;
+    int num_tiles, map_entries;
+    bool ordered;
+};
+
+inline BwdPlan bwd_plan(const BwdArgs& a) {
+    const BwdWs L = bwd_ws_layout(a.n, a.dim);
+    WsCursor cur(a.ws);
+    BwdPlan P;
+    P.num_tiles = L.num_tiles;
+    P.map_entries = (a.n + 63) / 64;
+    P.bagmap = cur.take<BagMapEntry>(P.map_entries);
+    P.tile_left = cur.take<float>(static_cast<size_t>(L.num_tiles) * a.dim);
+    P.tile_right = cur.take<float>(static_cast<size_t>(L.num_tiles) * a.dim);
+    P.tile_seg0 = cur.take<int32_t>(L.num_tiles);
+    P.tile_rseg = cur.take<int32_t>(L.num_tiles);
+    P.order = cur.take<int32_t>(L.num_tiles);
+    P.long_tiles = cur.take<int32_t>(L.num_tiles);
+    P.long_count = cur.take<int32_t>(1);
+    P.order_offsets = cur.take<int32_t>(kOrderBuckets + 2);
+    P.oplan = make_chunk_plan(L.num_tiles);
+    P.oH = cur.take<uint32_t>(part_hist_elems(P.oplan, kOrderBuckets + 1));
+    P.obin = cur.take<uint32_t>(kOrderBuckets + 1);
+    const bool seq = a.mode == NP_SEQ;
+    // The locality order pays when dY is larger than the last-level cache (2.42 -> 2.06 ms at 1.3 GB); below that it only
+    // costs three launches (0.63 -> 0.57 ms per step at 109 MB).  In sequence mode every dY row is read exactly once, so
+    // there is nothing to share: the pass would cost more (0.04 ms) than the slightly friendlier read order returns
+    // (0.02 ms on configuration 3).
+    const size_t dy_bytes = static_cast<size_t>(a.num_bags) * (seq ? a.max_len : 1) * a.dim * (a.dy_dtype == NP_BF16 ? 2 : 4);
+    P.ordered = dy_bytes > kOrderMinDyBytes && !seq;
+    return P;
+}
+
+// Everything that depends on the batch's index arrays alone (bag offsets, occurrence offsets), not on dY.
+inline void bwd_prepare_launch(const BwdArgs& a, const BwdPlan& P) {
+    const int map_blocks = (P.map_entries + 255) / 256, seg_blocks = (P.num_tiles + 255) / 256;
+    NP_LAUNCH("bwd_prepare", bwd_prepare_kernel, dim3(map_blocks + seg_blocks), dim3(256), 0, a.stream, a.bag_offsets, a.num_bags,
+              a.n, P.bagmap, map_blocks, a.occ_offsets, a.d_num_unique, P.num_tiles, P.tile_seg0, P.long_count);
+    if (P.ordered) {
+        TileOrderPolicy pol{P.tile_seg0, a.occ_offsets, P.order, a.n};
+        run_partition_pass(pol, P.num_tiles, nullptr, kOrderBuckets + 1, 11, P.oplan, P.oH, P.obin, nullptr, P.order_offsets,
+                           a.stream, "bwd_order_hist", "bwd_order_colscan", "bwd_order_scatter");
+    }
+}
 
 template <int LPR, int NV, int FUSED>
 void bwd_launch(const BwdArgs& a) {
-    const BwdWs L = bwd_ws_layout(a.n, a.dim);
-    WsCursor cur(a.ws);
-    const int map_entries = (a.n + 63) / 64;
-    BagMapEntry* bagmap = cur.take<BagMapEntry>(map_entries);
-    float* tile_left = cur.take<float>(static_cast<size_t>(L.num_tiles) * a.dim);
-    float* tile_right = cur.take<float>(static_cast<size_t>(L.num_tiles) * a.dim);
-    int32_t* tile_seg0 = cur.take<int32_t>(L.num_tiles);
-    int32_t* tile_rseg = cur.take<int32_t>(L.num_tiles);
-    int32_t* order = cur.take<int32_t>(L.num_tiles);
-    int32_t* long_tiles = cur.take<int32_t>(L.num_tiles);
-    int32_t* long_count = cur.take<int32_t>(1);
-    int32_t* order_offsets = cur.take<int32_t>(kOrderBuckets + 2);
-    const ChunkPlan oplan = make_chunk_plan(L.num_tiles);
-    uint32_t* oH = cur.take<uint32_t>(part_hist_elems(oplan, kOrderBuckets + 1));
-    uint32_t* obin = cur.take<uint32_t>(kOrderBuckets + 1);
+    const BwdPlan P = bwd_plan(a);
+    if (!a.prepared) bwd_prepare_launch(a, P);
+    struct { int num_tiles; } L{P.num_tiles};
+    BagMapEntry* bagmap = P.bagmap;
+    float* tile_left = P.tile_left;
+    float* tile_right = P.tile_right;
+    int32_t* tile_seg0 = P.tile_seg0;
+    int32_t* tile_rseg = P.tile_rseg;
+    int32_t* order = P.ordered ? P.order : nullptr;  // no order: tiles run in index order
+    int32_t* order_offsets = P.ordered ? P.order_offsets : nullptr;
+    int32_t* long_tiles = P.long_tiles;
+    int32_t* long_count = P.long_count;
     const int seq = a.mode == NP_SEQ ? 1 : 0;
-    const int map_blocks = (map_entries + 255) / 256, seg_blocks = (L.num_tiles + 255) / 256;
-    NP_LAUNCH("bwd_prepare", bwd_prepare_kernel, dim3(map_blocks + seg_blocks), dim3(256), 0, a.stream, a.bag_offsets, a.num_bags,
-              a.n, bagmap, map_blocks, a.occ_offsets, a.d_num_unique, L.num_tiles, tile_seg0, long_count);
-    // The locality order pays when dY is larger than the last-level cache (2.42 -> 2.06 ms at 1.3 GB); below that it only
-    // costs three launches (0.63 -> 0.57 ms per step at 109 MB).
-    const size_t dy_bytes = static_cast<size_t>(a.num_bags) * (seq ? a.max_len : 1) * a.dim * (a.dy_dtype == NP_BF16 ? 2 : 4);
-    // In sequence mode every dY row is read exactly once, so there is nothing to share: the pass would cost more
-    // (0.04 ms) than the slightly friendlier read order returns (0.02 ms on configuration 3).
-    if (dy_bytes > kOrderMinDyBytes && !seq) {
-        TileOrderPolicy pol{tile_seg0, a.occ_offsets, order, a.n};
-        run_partition_pass(pol, L.num_tiles, nullptr, kOrderBuckets + 1, 11, oplan, oH, obin, nullptr, order_offsets, a.stream,
-                           "bwd_order_hist", "bwd_order_colscan", "bwd_order_scatter");
-    } else {
-        order = nullptr;
-        order_offsets = nullptr;
-    }
     const unsigned main_grid = static_cast<unsigned>((L.num_tiles + 2 * kNumXcd + kNumXcd - 1) / kNumXcd * kNumXcd);
     const bool mean = a.mode == NP_POOL_MEAN;
 #define NP_BWD_MAIN(L_, N_, M_, T_, P_)                                                                                        \
@@ -704,23 +745,53 @@ size_t np_lookup_bwd_workspace_bytes(int32_t num_bags, int32_t n, int32_t dim, i
     return np::bwd_ws_layout(n, dim).total;
 }
 
-int np_lookup_bwd(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
-                  const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
-                  const int32_t* occ, const int32_t* d_num_unique, int32_t cap, const int32_t* unique_to_send,
-                  float* grads, void* ws, size_t ws_bytes, void* stream) {
-    if (num_bags < 0 || n < 0 || cap < 0 || !d_num_unique) return NP_ERR_INVALID_ARG;
+// Argument checks shared by np_lookup_bwd_prepare (dY, occ and grads absent) and the reducing calls.
+static int bwd_check_common(int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len, const int32_t* bag_offsets,
+                            int32_t num_bags, int32_t n, const int32_t* occ_offsets, const int32_t* d_num_unique, int32_t dim_limit,
+                            const void* ws, size_t ws_bytes, bool* nothing_to_do) {
+    *nothing_to_do = false;
+    if (num_bags < 0 || n < 0 || !d_num_unique) return NP_ERR_INVALID_ARG;
     if (mode != NP_POOL_SUM && mode != NP_POOL_MEAN && mode != NP_SEQ) return NP_ERR_INVALID_ARG;
     if (dy_dtype != NP_F32 && dy_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
     if (mode == NP_SEQ && max_len < 1) return NP_ERR_INVALID_ARG;
-    if (dim < 4 || dim % 4 != 0 || dim > NP_MAX_DIM) return NP_ERR_UNSUPPORTED;
+    if (dim < 4 || dim % 4 != 0 || dim > dim_limit) return NP_ERR_UNSUPPORTED;
     if (mode == NP_SEQ && static_cast<int64_t>(num_bags) * max_len > INT32_MAX) return NP_ERR_UNSUPPORTED;
-    if (n == 0) return NP_OK;  // no lookups: no key receives a gradient, nothing to write
+    if (n == 0) {  // no lookups: no key receives a gradient, nothing to write
+        *nothing_to_do = true;
+        return NP_OK;
+    }
     if (n > INT32_MAX - (1 << 20)) return NP_ERR_UNSUPPORTED;  // tile-rounded positions must stay below 2^31
-    if (!dY || !bag_offsets || !occ_offsets || !occ || !grads || num_bags < 1) return NP_ERR_INVALID_ARG;
-    if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(grads, 16)) return NP_ERR_INVALID_ARG;
+    if (!bag_offsets || !occ_offsets || num_bags < 1) return NP_ERR_INVALID_ARG;
     if (!ws || !np::aligned(ws, 256) || ws_bytes < np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode)) return NP_ERR_WORKSPACE;
+    return NP_OK;
+}
+
+int np_lookup_bwd_prepare(int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len, const int32_t* bag_offsets,
+                          int32_t num_bags, int32_t n, const int32_t* occ_offsets, const int32_t* d_num_unique, void* ws,
+                          size_t ws_bytes, void* stream) {
+    bool nothing = false;
+    const int rc = bwd_check_common(dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, d_num_unique, NP_MAX_DIM, ws,
+                                    ws_bytes, &nothing);
+    if (rc != NP_OK || nothing) return rc;
+    np::BwdArgs a{nullptr, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, nullptr, d_num_unique, nullptr,
+                  np::RowSink{nullptr, nullptr, nullptr, nullptr, 0.f, 0.f, 0.f}, ws, static_cast<hipStream_t>(stream), false};
+    np::bwd_prepare_launch(a, np::bwd_plan(a));
+    return np::launch_status();
+}
+
+static int bwd_reduce(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len, const int32_t* bag_offsets,
+                      int32_t num_bags, int32_t n, const int32_t* occ_offsets, const int32_t* occ, const int32_t* d_num_unique,
+                      int32_t cap, const int32_t* unique_to_send, float* grads, void* ws, size_t ws_bytes, void* stream,
+                      bool prepared) {
+    if (cap < 0) return NP_ERR_INVALID_ARG;
+    bool nothing = false;
+    const int rc = bwd_check_common(dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, d_num_unique, NP_MAX_DIM, ws,
+                                    ws_bytes, &nothing);
+    if (rc != NP_OK || nothing) return rc;
+    if (!dY || !occ || !grads) return NP_ERR_INVALID_ARG;
+    if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(grads, 16)) return NP_ERR_INVALID_ARG;
     np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, unique_to_send,
-                  np::RowSink{grads, nullptr, nullptr, nullptr, 0.f, 0.f, 0.f}, ws, static_cast<hipStream_t>(stream)};
+                  np::RowSink{grads, nullptr, nullptr, nullptr, 0.f, 0.f, 0.f}, ws, static_cast<hipStream_t>(stream), prepared};
     const int words = dim / 4;
     if (words <= 4) np::bwd_launch<4, 1, np::kSinkGrads>(a);
     else if (words <= 8) np::bwd_launch<8, 1, np::kSinkGrads>(a);
@@ -730,6 +801,22 @@ int np_lookup_bwd(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, i
     else if (words <= 128) np::bwd_launch<64, 2, np::kSinkGrads>(a);
     else np::bwd_launch<64, 4, np::kSinkGrads>(a);
     return np::launch_status();
+}
+
+int np_lookup_bwd(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
+                  const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
+                  const int32_t* occ, const int32_t* d_num_unique, int32_t cap, const int32_t* unique_to_send,
+                  float* grads, void* ws, size_t ws_bytes, void* stream) {
+    return bwd_reduce(dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, cap, unique_to_send,
+                      grads, ws, ws_bytes, stream, false);
+}
+
+int np_lookup_bwd_prepared(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
+                           const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
+                           const int32_t* occ, const int32_t* d_num_unique, int32_t cap, const int32_t* unique_to_send,
+                           float* grads, void* ws, size_t ws_bytes, void* stream) {
+    return bwd_reduce(dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, cap, unique_to_send,
+                      grads, ws, ws_bytes, stream, true);
 }
 
 int np_lookup_bwd_adagrad_t(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
@@ -752,7 +839,7 @@ int np_lookup_bwd_adagrad_t(const void* dY, int32_t dy_dtype, int32_t dim, int32
     if (!ws || !np::aligned(ws, 256) || ws_bytes < np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode)) return NP_ERR_WORKSPACE;
     np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, nullptr,
                   np::RowSink{nullptr, table, state, unique, lr, eps, 1.0f / static_cast<float>(dim)}, ws,
-                  static_cast<hipStream_t>(stream)};
+                  static_cast<hipStream_t>(stream), false};
     const int words = dim / 4;
     if (table_dtype == NP_BF16) np::bwd_fused_dispatch<np::kSinkBf16>(a, words);
     else if (table_dtype == NP_F16) np::bwd_fused_dispatch<np::kSinkF16>(a, words);

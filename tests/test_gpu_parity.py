@@ -297,6 +297,12 @@ def test_bwd_with_an_upstream_gradient_larger_than_the_last_level_cache(H, dim, 
     grads2 = H.B.np_lookup_bwd(dYd, dim, mode, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], U)
     torch.cuda.synchronize()
     assert torch.equal(grads[:U], grads2[:U])
+    # the same in two parts: the index work first, the reduction on the prepared workspace
+    ws = torch.empty(H.B.np_lookup_bwd_workspace_bytes(Bn, n, dim, mode), dtype=torch.uint8, device="cuda")
+    H.B.np_lookup_bwd_prepare(H.B.F32, dim, mode, 1, H.dev(off), n, d["occ_offsets"], d["num_unique"], ws)
+    grads3 = H.B.np_lookup_bwd_prepared(dYd, dim, mode, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], U, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(grads[:U], grads3[:U])
 
 
 @pytest.mark.parametrize("dim,mode", [(16, 0), (64, 1), (256, 0), (20, 0), (24, 1), (40, 0), (136, 1)])
@@ -607,3 +613,56 @@ def test_batch_precondition_check(H):
     assert got[2] == 1 and got[3] == 1
     assert B.np_util_check_batch(None, R, H.dev(np.zeros(1, np.int32))) == (0, 0, 0, 0)
     assert B.np_util_check_batch(H.dev(keys), R, None)[0] == 0
+
+
+@pytest.mark.parametrize("dim,mode,bf16", [(4, 0, False), (16, 1, False), (64, 0, False), (64, 1, True), (128, 2, True), (24, 2, True),
+                                           (520, 0, False)])
+def test_bwd_in_two_parts_equals_the_single_call(H, dim, mode, bf16):
+    """np_lookup_bwd_prepare on a second stream, ordered by an event, then np_lookup_bwd_prepared: the bits of np_lookup_bwd,
+    also when the prepared workspace is used for two different gradients in a row."""
+    import torch
+    B = H.B
+    rng = np.random.default_rng(dim * 3 + mode)
+    Bn = 700
+    off, keys = _bags(rng, Bn, 40, 3000)
+    keys[rng.random(keys.shape[0]) < 0.4] = 11                       # one key with a long chain of tiles
+    n = keys.shape[0]
+    max_len = int(np.diff(off).max()) if mode == 2 else 1
+    shape = (Bn, max_len, dim) if mode == 2 else (Bn, dim)
+    g, d = H.gpu_dedup(keys, 12)
+    U = int(d["num_unique"].item())
+    offd = H.dev(off)
+    ws = torch.empty(B.np_lookup_bwd_workspace_bytes(Bn, n, dim, mode), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    ready = torch.cuda.Event()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.np_lookup_bwd_prepare(B.BF16 if bf16 else B.F32, dim, mode, max_len, offd, n, d["occ_offsets"], d["num_unique"], ws)
+        ready.record(side)
+    torch.cuda.current_stream().wait_event(ready)
+    for rep in range(2):
+        dY = torch.from_numpy(rng.standard_normal(shape).astype(np.float32)).cuda()
+        if bf16:
+            dY = dY.bfloat16()
+        want = B.np_lookup_bwd(dY, dim, mode, max_len, offd, n, d["occ_offsets"], d["occ"], d["num_unique"], n)
+        got = B.np_lookup_bwd_prepared(dY, dim, mode, max_len, offd, n, d["occ_offsets"], d["occ"], d["num_unique"], n, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(want[:U], got[:U]), rep
+
+
+def test_bwd_prepare_checks_its_arguments(H):
+    import torch
+    B, L = H.B, H.B.lib
+    off = torch.tensor([0, 2, 5], dtype=torch.int32, device="cuda")
+    oo = torch.tensor([0, 3, 5], dtype=torch.int32, device="cuda")
+    nu = torch.tensor([2], dtype=torch.int32, device="cuda")
+    need = B.np_lookup_bwd_workspace_bytes(2, 5, 8, 0)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == 0
+    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), nu.data_ptr(), ws.data_ptr(), need - 1, st) == -2
+    assert L.np_lookup_bwd_prepare(0, 6, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == -3
+    assert L.np_lookup_bwd_prepare(7, 8, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == -1
+    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, 0, 2, 5, oo.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == -1
+    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, off.data_ptr(), 2, 0, oo.data_ptr(), nu.data_ptr(), 0, 0, st) == 0     # no lookups
+    torch.cuda.synchronize()
