@@ -19,9 +19,9 @@
 //                  across the groups of the block in strip order; sums cut by a tile edge are parked in the
 //                  workspace as the tile's "left" (continues from an earlier tile) and "right" (continues
 //                  into later tiles) partials.
-//   bwd_fixup_*    the tile where a cut segment starts adds its right partial and the left partials of the
+//   bwd_fixup      the tile where a cut segment starts adds its right partial and the left partials of the
 //                  following tiles in tile order: one group per tile for short chains, one block per listed
-//                  long chain with a fixed split of the chain over the block.
+//                  long chain (bwd_main lists them) with a fixed split of the chain over the block.
 //
 // The order of every floating-point addition is a function of occ_offsets alone: no atomics, no dependence
 // on scheduling, so two runs give the same bits.  A hot key with millions of lookups costs the same per
@@ -31,6 +31,7 @@
 namespace np {
 
 constexpr int kBwdTile = 256;
+constexpr int kFixupShort = 8;  // chains of up to this many left partials are summed by one group, longer ones by a block
 #ifndef NP_BWD_UNROLL
 #define NP_BWD_UNROLL 8
 #endif
@@ -98,8 +99,7 @@ __device__ __forceinline__ void bag_of_lookup(const BagMapEntry* __restrict__ ma
 }
 
 __device__ __forceinline__ void tile_first_segment(int t, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ d_num_unique,
-                                                   int num_tiles, int32_t* __restrict__ tile_seg0, int32_t* __restrict__ long_count) {
-    if (t == 0) *long_count = 0;  // the list of long chains is rebuilt by every call
+                                                   int num_tiles, int32_t* __restrict__ tile_seg0) {
     if (t >= num_tiles) return;
     const int pos = t * kBwdTile;
     int lo = 0, hi = *d_num_unique;  // the answer is the last u in [lo, hi) with occ_offsets[u] <= pos
@@ -116,11 +116,11 @@ __device__ __forceinline__ void tile_first_segment(int t, const int32_t* __restr
 __global__ void __launch_bounds__(256)
 bwd_prepare_kernel(const int32_t* __restrict__ bag_offsets, int num_bags, int n, BagMapEntry* __restrict__ map, int map_blocks,
                    const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ d_num_unique, int num_tiles,
-                   int32_t* __restrict__ tile_seg0, int32_t* __restrict__ long_count) {
+                   int32_t* __restrict__ tile_seg0) {
     if (static_cast<int>(blockIdx.x) < map_blocks)
         bagmap_entry(blockIdx.x * 256 + threadIdx.x, bag_offsets, num_bags, n, map);
     else
-        tile_first_segment((blockIdx.x - map_blocks) * 256 + threadIdx.x, occ_offsets, d_num_unique, num_tiles, tile_seg0, long_count);
+        tile_first_segment((blockIdx.x - map_blocks) * 256 + threadIdx.x, occ_offsets, d_num_unique, num_tiles, tile_seg0);
 }
 
 // Partition policy that sorts tiles by the bucket of their relative position inside a long segment; tiles that are
@@ -317,7 +317,12 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     if (valid && t == min(n - tile_start, kBwdTile) - 1) {
         // the tile owns the segment that runs past its end only if that segment starts inside the tile
         const bool starts_here = seg > u0 || seg0_start == tile_start;
-        tile_rseg[tile] = (!is_tail && starts_here) ? seg : -1;
+        const bool owns = !is_tail && starts_here;
+        // -1: the tile owns no cut segment; seg >= 0: a chain of up to kFixupShort left partials follows (summed by one
+        // group); -2 - seg: a longer chain (summed by a whole block)
+        int code = -1;
+        if (owns) code = (occ_offsets[seg + 1] - 1) / kBwdTile - tile > kFixupShort ? -2 - seg : seg;
+        tile_rseg[tile] = code;
     }
 
     // ---- each group walks its strip of LPR positions ---------------------------------------------------
@@ -461,26 +466,20 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
 // summed by one LPR-lane group per tile; longer chains (a key with millions of lookups spans thousands of tiles)
 // are listed and summed by a whole block each, cut into one contiguous run per group with four loads in
 // flight per lane.  Either way the shape of the sum depends on the chain length alone.
-constexpr int kFixupShort = 8;
 constexpr int kFixupThreads = 1024;
+constexpr int kFixupLongBlocks = 512;  // blocks that walk the list of long chains
 
 template <int LPR, int NV, int FUSED>
-__global__ void __launch_bounds__(256)
-bwd_fixup_short_kernel(int dim, int num_tiles, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
-                       const float* __restrict__ tile_left, const float* __restrict__ tile_right,
-                       const int32_t* __restrict__ tile_rseg, RowSink sink, int32_t* __restrict__ long_count,
-                       int32_t* __restrict__ long_tiles) {
-    constexpr int GPB = 256 / LPR;
+__device__ __forceinline__ void fixup_short_part(int first_block_tile, int dim, int num_tiles, const int32_t* __restrict__ occ_offsets,
+                                                 const int32_t* __restrict__ unique_to_send, const float* __restrict__ tile_left,
+                                                 const float* __restrict__ tile_right, const int32_t* __restrict__ tile_rseg,
+                                                 const RowSink& sink) {
     const int r = threadIdx.x % LPR;
-    const int tile = blockIdx.x * GPB + threadIdx.x / LPR;
+    const int tile = first_block_tile + threadIdx.x / LPR;
     if (tile >= num_tiles) return;
     const int seg = tile_rseg[tile];
     if (seg < 0) return;
-    const int count = (occ_offsets[seg + 1] - 1) / kBwdTile - tile;  // left partials to add, >= 1
-    if (count > kFixupShort) {
-        if (r == 0) long_tiles[atomicAdd(long_count, 1)] = tile;  // list order is arbitrary; it decides no value
-        return;
-    }
+    const int count = (occ_offsets[seg + 1] - 1) / kBwdTile - tile;  // left partials to add, 1..kFixupShort (longer chains carry a code < -1)
     const int words = dim / 4;
     float4 acc[NV];
 #pragma unroll
@@ -515,21 +514,52 @@ bwd_fixup_short_kernel(int dim, int num_tiles, const int32_t* __restrict__ occ_o
     }
 }
 
+// One launch for both kinds of chain: the last short_blocks blocks take one tile per LPR-lane group (chains of up to
+// kFixupShort partials), the blocks before them take the long chains, one chain per block at a time.
+// Threads per block: 1024, or 512 for the widest rows (NV = 4), so that the block's partial rows stay within 32 KB of LDS.
+template <int NV>
+constexpr int fixup_threads() {
+    return NV >= 4 ? kFixupThreads / 2 : kFixupThreads;
+}
+
 template <int LPR, int NV, int FUSED>
 __global__ void __launch_bounds__(kFixupThreads)
-bwd_fixup_long_kernel(int dim, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ unique_to_send,
-                      const float* __restrict__ tile_left, const float* __restrict__ tile_right,
-                      const int32_t* __restrict__ tile_rseg, RowSink sink, const int32_t* __restrict__ long_count,
-                      const int32_t* __restrict__ long_tiles) {
-    constexpr int GPB = kFixupThreads / LPR;
+bwd_fixup_kernel(int dim, int num_tiles, int short_blocks, const int32_t* __restrict__ occ_offsets,
+                 const int32_t* __restrict__ unique_to_send, const float* __restrict__ tile_left, const float* __restrict__ tile_right,
+                 const int32_t* __restrict__ tile_rseg, RowSink sink) {
+    constexpr int FT = fixup_threads<NV>();
+    constexpr int GPB = FT / LPR;
     constexpr int ROWW = LPR * NV;
     __shared__ float4 part[GPB * ROWW];
+    // the blocks of the long chains come first in the grid: the longest chain is the critical path of the launch and
+    // should start at once, the short chains fill the rest of the GPU beside it
+    const int long_blocks = gridDim.x - short_blocks;
+    if (static_cast<int>(blockIdx.x) >= long_blocks) {  // uniform per block
+        fixup_short_part<LPR, NV, FUSED>((blockIdx.x - long_blocks) * GPB, dim, num_tiles, occ_offsets, unique_to_send, tile_left,
+                                         tile_right, tile_rseg, sink);
+        return;
+    }
+    // Long chains: block b of this part owns the tiles b, b + long_blocks, ...; every round all threads look at one owned
+    // tile each, those that start a long chain are collected in LDS (in arbitrary order: it decides no value), then the
+    // whole block sums the collected chains one after the other.
+    __shared__ int found[FT];
+    __shared__ int num_found;
     const int g = threadIdx.x / LPR, r = threadIdx.x % LPR;
     const int words = dim / 4;
-    const int num_long = *long_count;
-    for (int li = blockIdx.x; li < num_long; li += gridDim.x) {
-        const int tile = long_tiles[li];
-        const int seg = tile_rseg[tile];
+    const int64_t round_span = static_cast<int64_t>(long_blocks) * FT;
+    for (int64_t base = blockIdx.x; base < num_tiles; base += round_span) {
+      __syncthreads();  // found[] and num_found of the previous round are no longer read
+      if (threadIdx.x == 0) num_found = 0;
+      __syncthreads();
+      {
+          const int64_t cand = base + static_cast<int64_t>(threadIdx.x) * long_blocks;
+          if (cand < num_tiles && tile_rseg[cand] < -1) found[atomicAdd(&num_found, 1)] = static_cast<int>(cand);
+      }
+      __syncthreads();
+      const int nf = num_found;
+      for (int li = 0; li < nf; ++li) {
+        const int tile = found[li];
+        const int seg = -2 - tile_rseg[tile];
         const int count = (occ_offsets[seg + 1] - 1) / kBwdTile - tile;
         const int per = (count + GPB - 1) / GPB;
         const int c0 = g * per;
@@ -584,6 +614,7 @@ bwd_fixup_long_kernel(int dim, const int32_t* __restrict__ occ_offsets, const in
             if (FUSED) sink_row<LPR, FUSED>(sink, dst, dim, t, words, s);
             else if (t < words) store_stream(reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dst) * dim) + t, s);
         }
+      }
     }
 }
 
@@ -597,8 +628,7 @@ inline BwdWs bwd_ws_layout(int32_t n, int32_t dim) {
     w.num_tiles = (n + kBwdTile - 1) / kBwdTile;
     w.total = align_up(sizeof(BagMapEntry) * ((static_cast<size_t>(n) + 63) / 64), 256)  // bag map
               + 2 * align_up(4 * static_cast<size_t>(w.num_tiles) * dim, 256)        // tile_left, tile_right
-              + 4 * align_up(4 * static_cast<size_t>(w.num_tiles), 256)              // tile_seg0, tile_rseg, order, long chains
-              + 256                                                                   // number of long chains
+              + 3 * align_up(4 * static_cast<size_t>(w.num_tiles), 256)              // tile_seg0, tile_rseg, order
               + align_up(4 * static_cast<size_t>(kOrderBuckets + 2), 256)             // bucket offsets of the order
               + align_up(4 * part_hist_elems(make_chunk_plan(w.num_tiles), kOrderBuckets + 1), 256)
               + align_up(4 * static_cast<size_t>(kOrderBuckets + 1), 256);
@@ -629,8 +659,6 @@ struct BwdPlan {
     int32_t* tile_seg0;
     int32_t* tile_rseg;
     int32_t* order;
-    int32_t* long_tiles;
-    int32_t* long_count;
     int32_t* order_offsets;
     uint32_t* oH;
     uint32_t* obin;
@@ -651,8 +679,6 @@ inline BwdPlan bwd_plan(const BwdArgs& a) {
     P.tile_seg0 = cur.take<int32_t>(L.num_tiles);
     P.tile_rseg = cur.take<int32_t>(L.num_tiles);
     P.order = cur.take<int32_t>(L.num_tiles);
-    P.long_tiles = cur.take<int32_t>(L.num_tiles);
-    P.long_count = cur.take<int32_t>(1);
     P.order_offsets = cur.take<int32_t>(kOrderBuckets + 2);
     P.oplan = make_chunk_plan(L.num_tiles);
     P.oH = cur.take<uint32_t>(part_hist_elems(P.oplan, kOrderBuckets + 1));
@@ -671,7 +697,7 @@ inline BwdPlan bwd_plan(const BwdArgs& a) {
 inline void bwd_prepare_launch(const BwdArgs& a, const BwdPlan& P) {
     const int map_blocks = (P.map_entries + 255) / 256, seg_blocks = (P.num_tiles + 255) / 256;
     NP_LAUNCH("bwd_prepare", bwd_prepare_kernel, dim3(map_blocks + seg_blocks), dim3(256), 0, a.stream, a.bag_offsets, a.num_bags,
-              a.n, P.bagmap, map_blocks, a.occ_offsets, a.d_num_unique, P.num_tiles, P.tile_seg0, P.long_count);
+              a.n, P.bagmap, map_blocks, a.occ_offsets, a.d_num_unique, P.num_tiles, P.tile_seg0);
     if (P.ordered) {
         TileOrderPolicy pol{P.tile_seg0, a.occ_offsets, P.order, a.n};
         run_partition_pass(pol, P.num_tiles, nullptr, kOrderBuckets + 1, 11, P.oplan, P.oH, P.obin, nullptr, P.order_offsets,
@@ -691,8 +717,6 @@ void bwd_launch(const BwdArgs& a) {
     int32_t* tile_rseg = P.tile_rseg;
     int32_t* order = P.ordered ? P.order : nullptr;  // no order: tiles run in index order
     int32_t* order_offsets = P.ordered ? P.order_offsets : nullptr;
-    int32_t* long_tiles = P.long_tiles;
-    int32_t* long_count = P.long_count;
     const int seq = a.mode == NP_SEQ ? 1 : 0;
     const unsigned main_grid = static_cast<unsigned>((L.num_tiles + 2 * kNumXcd + kNumXcd - 1) / kNumXcd * kNumXcd);
     const bool mean = a.mode == NP_POOL_MEAN;
@@ -718,11 +742,10 @@ void bwd_launch(const BwdArgs& a) {
         else NP_BWD_MAIN(LPR, NV, false, float, false);
     }
 #undef NP_BWD_MAIN
-    constexpr int GPB = 256 / LPR;
-    NP_LAUNCH("bwd_fixup_short", (bwd_fixup_short_kernel<LPR, NV, FUSED>), dim3((L.num_tiles + GPB - 1) / GPB), dim3(256), 0, a.stream, a.dim,
-              L.num_tiles, a.occ_offsets, a.unique_to_send, tile_left, tile_right, tile_rseg, a.sink, long_count, long_tiles);
-    NP_LAUNCH("bwd_fixup_long", (bwd_fixup_long_kernel<LPR, NV, FUSED>), dim3(512), dim3(kFixupThreads), 0, a.stream, a.dim, a.occ_offsets,
-              a.unique_to_send, tile_left, tile_right, tile_rseg, a.sink, long_count, long_tiles);
+    constexpr int kFixGPB = fixup_threads<NV>() / LPR;
+    const int short_blocks = (L.num_tiles + kFixGPB - 1) / kFixGPB;
+    NP_LAUNCH("bwd_fixup", (bwd_fixup_kernel<LPR, NV, FUSED>), dim3(short_blocks + kFixupLongBlocks), dim3(fixup_threads<NV>()), 0, a.stream,
+              a.dim, L.num_tiles, short_blocks, a.occ_offsets, a.unique_to_send, tile_left, tile_right, tile_rseg, a.sink);
 }
 
 template <int FUSED>
