@@ -15,11 +15,11 @@ constexpr int64_t kAdagradMaxGrid = NP_ADAGRAD_MAX_GRID;
 template <int LPR, int NV, typename TabT>
 __global__ void __launch_bounds__(256)
 adagrad_kernel(TabT* __restrict__ table, float* __restrict__ state, int dim, const int64_t* __restrict__ list_keys,
-               const float* __restrict__ grads, const int32_t* __restrict__ d_num_list, float lr, float eps, float inv_dim) {
+               const float* __restrict__ grads, const int32_t* __restrict__ d_num_list, int cap, float lr, float eps, float inv_dim) {
     constexpr int GPB = 256 / LPR;
     const int r = threadIdx.x % LPR;
     const int words = dim / 4;
-    const int L = *d_num_list;
+    const int L = device_count(d_num_list, cap);
     for (int64_t p = static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR; p < L; p += static_cast<int64_t>(gridDim.x) * GPB) {
         const int64_t key = list_keys[p];
         const float4* gsrc = reinterpret_cast<const float4*>(grads + static_cast<size_t>(p) * dim);
@@ -61,7 +61,7 @@ void adagrad_launch(TabT* table, float* state, int dim, const int64_t* list_keys
     int64_t want = (static_cast<int64_t>(cap) + GPB - 1) / GPB;
     const unsigned grid = static_cast<unsigned>(want < kAdagradMaxGrid ? want : kAdagradMaxGrid);
     NP_LAUNCH("sparse_adagrad", (adagrad_kernel<LPR, NV, TabT>), dim3(grid), dim3(256), 0, stream, table, state, dim, list_keys,
-              grads, d_num_list, lr, eps, 1.0f / static_cast<float>(dim));
+              grads, d_num_list, cap, lr, eps, 1.0f / static_cast<float>(dim));
 }
 
 template <typename TabT>

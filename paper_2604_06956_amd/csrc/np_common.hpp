@@ -59,6 +59,13 @@ __device__ __forceinline__ uint64_t lanemask_lt() {
     return l == 0 ? 0ull : (~0ull >> (64 - l));
 }
 
+// A count the device holds (distinct keys, list entries, pairs), never more than the host bound `cap` that the buffers and
+// the grid were sized for and never negative: a stale or corrupt count must not make a kernel walk past its buffers.
+__device__ __forceinline__ int device_count(const int32_t* __restrict__ d_count, int cap) {
+    const int v = *d_count;
+    return v < 0 ? 0 : (v < cap ? v : cap);
+}
+
 // Routing hash (a bijection of 64-bit words): odd multiplier, xor-shift, twice.
 __host__ __device__ __forceinline__ uint64_t mix64(uint64_t k) {
     const uint64_t C = 0x9E3779B97F4A7C15ull;

@@ -52,11 +52,12 @@ __device__ __forceinline__ int lower_bound_keys(const int64_t* __restrict__ keys
 // in place.  The slice boundaries of up to kIsTileBatch tiles are found together, one thread each.
 __global__ void __launch_bounds__(kIsThreads)
 intersect_probe_kernel(const int64_t* __restrict__ keys_a, const int32_t* __restrict__ d_num_a, const int64_t* __restrict__ keys_b,
-                       const int32_t* __restrict__ d_num_b, int chunk_items, int32_t* __restrict__ found, int32_t* __restrict__ chunk_hits) {
+                       const int32_t* __restrict__ d_num_b, int cap_a, int cap_b, int chunk_items, int32_t* __restrict__ found,
+                       int32_t* __restrict__ chunk_hits) {
     __shared__ int64_t sa[kIsStage];
     __shared__ int bound[kIsTileBatch + 1];
     __shared__ int wsum[kIsThreads / kWave];
-    const int na = *d_num_a, nb = *d_num_b;
+    const int na = device_count(d_num_a, cap_a), nb = device_count(d_num_b, cap_b);
     const int64_t lo = static_cast<int64_t>(blockIdx.x) * chunk_items;
     int64_t hi = lo + chunk_items;
     if (hi > nb) hi = nb;
@@ -114,13 +115,13 @@ intersect_probe_kernel(const int64_t* __restrict__ keys_a, const int32_t* __rest
 }
 
 __global__ void __launch_bounds__(kIsThreads)
-intersect_emit_kernel(const int32_t* __restrict__ d_num_b, int chunk_items, int num_chunks, const int32_t* __restrict__ found,
+intersect_emit_kernel(const int32_t* __restrict__ d_num_b, int cap_b, int chunk_items, int num_chunks, const int32_t* __restrict__ found,
                       const int32_t* __restrict__ chunk_hits, int32_t* __restrict__ idx_a, int32_t* __restrict__ idx_b,
                       int32_t* __restrict__ d_num_common) {
     __shared__ int scan_tmp[16];
     __shared__ int red[2][kIsThreads / kWave];
     const int c = blockIdx.x;
-    const int nb = *d_num_b;
+    const int nb = device_count(d_num_b, cap_b);
     int before = 0, all = 0;
     for (int i = threadIdx.x; i < num_chunks; i += kIsThreads) {
         const int h = chunk_hits[i];
@@ -174,11 +175,11 @@ intersect_emit_kernel(const int32_t* __restrict__ d_num_b, int chunk_items, int 
 template <int LPR, int NV>
 __global__ void __launch_bounds__(256)
 sync_rows_kernel(const float* __restrict__ src, const int32_t* __restrict__ src_idx, float* __restrict__ dst,
-                 const int32_t* __restrict__ dst_idx, const int32_t* __restrict__ d_count, int dim) {
+                 const int32_t* __restrict__ dst_idx, const int32_t* __restrict__ d_count, int cap, int dim) {
     constexpr int GPB = 256 / LPR;
     const int r = threadIdx.x % LPR;
     const int words = dim / 4;
-    const int count = *d_count;
+    const int count = device_count(d_count, cap);
     for (int64_t p = static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR; p < count; p += static_cast<int64_t>(gridDim.x) * GPB) {
         const float4* s = reinterpret_cast<const float4*>(src + static_cast<size_t>(src_idx[p]) * dim);
         float4* d = reinterpret_cast<float4*>(dst + static_cast<size_t>(dst_idx[p]) * dim);
@@ -196,7 +197,7 @@ void sync_rows_launch(const float* src, const int32_t* src_idx, float* dst, cons
     constexpr int GPB = 256 / LPR;
     int64_t want = (static_cast<int64_t>(cap) + GPB - 1) / GPB;
     const unsigned grid = static_cast<unsigned>(want < 32768 ? want : 32768);
-    NP_LAUNCH("sync_rows", (sync_rows_kernel<LPR, NV>), dim3(grid), dim3(256), 0, stream, src, src_idx, dst, dst_idx, d_count, dim);
+    NP_LAUNCH("sync_rows", (sync_rows_kernel<LPR, NV>), dim3(grid), dim3(256), 0, stream, src, src_idx, dst, dst_idx, d_count, cap, dim);
 }
 
 }  // namespace np
@@ -221,8 +222,8 @@ int np_intersect(const int64_t* keys_a, const int32_t* d_num_a, int32_t cap_a, c
     int32_t* found = cur.take<int32_t>(cap_b > 0 ? cap_b : 1);
     int32_t* chunk_hits = cur.take<int32_t>(np::kIsMaxChunks);
     NP_LAUNCH("intersect_probe", np::intersect_probe_kernel, dim3(plan.num_chunks), dim3(np::kIsThreads), 0, s, keys_a, d_num_a, keys_b,
-              d_num_b, plan.chunk_items, found, chunk_hits);
-    NP_LAUNCH("intersect_emit", np::intersect_emit_kernel, dim3(plan.num_chunks), dim3(np::kIsThreads), 0, s, d_num_b, plan.chunk_items,
+              d_num_b, cap_a, cap_b, plan.chunk_items, found, chunk_hits);
+    NP_LAUNCH("intersect_emit", np::intersect_emit_kernel, dim3(plan.num_chunks), dim3(np::kIsThreads), 0, s, d_num_b, cap_b, plan.chunk_items,
               plan.num_chunks, found, chunk_hits, idx_a, idx_b, d_num_common);
     return np::launch_status();
 }

@@ -223,8 +223,8 @@ dedup_emit_kernel(const K* __restrict__ sorted, const int32_t* __restrict__ occ,
 }
 
 __global__ void __launch_bounds__(256)
-dedup_counts_kernel(const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ d_num_unique, int32_t* __restrict__ counts) {
-    const int U = *d_num_unique;
+dedup_counts_kernel(const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ d_num_unique, int n, int32_t* __restrict__ counts) {
+    const int U = device_count(d_num_unique, n);
     for (int u = blockIdx.x * blockDim.x + threadIdx.x; u < U; u += gridDim.x * blockDim.x)
         counts[u] = occ_offsets[u + 1] - occ_offsets[u];
 }
@@ -299,7 +299,7 @@ int dedup_impl(const int64_t* keys, int32_t n, int32_t key_bits, int64_t* unique
               num_tiles, num_chunks, chunk_heads, unique, inverse, occ_offsets, d_num_unique);
     int cgrid = (n + 255) / 256;
     if (cgrid > 4096) cgrid = 4096;
-    NP_LAUNCH("dedup_counts", dedup_counts_kernel, dim3(cgrid), dim3(256), 0, stream, occ_offsets, d_num_unique, counts);
+    NP_LAUNCH("dedup_counts", dedup_counts_kernel, dim3(cgrid), dim3(256), 0, stream, occ_offsets, d_num_unique, n, counts);
     return launch_status();
 }
 

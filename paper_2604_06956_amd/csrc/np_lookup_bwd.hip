@@ -99,10 +99,10 @@ __device__ __forceinline__ void bag_of_lookup(const BagMapEntry* __restrict__ ma
 }
 
 __device__ __forceinline__ void tile_first_segment(int t, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ d_num_unique,
-                                                   int num_tiles, int32_t* __restrict__ tile_seg0) {
+                                                   int n, int num_tiles, int32_t* __restrict__ tile_seg0) {
     if (t >= num_tiles) return;
     const int pos = t * kBwdTile;
-    int lo = 0, hi = *d_num_unique;  // the answer is the last u in [lo, hi) with occ_offsets[u] <= pos
+    int lo = 0, hi = device_count(d_num_unique, n);  // U <= n; the answer is the last u in [lo, hi) with occ_offsets[u] <= pos
     while (hi - lo > 1) {
         const int mid = lo + (hi - lo) / 2;
         if (occ_offsets[mid] <= pos) lo = mid;
@@ -120,7 +120,7 @@ bwd_prepare_kernel(const int32_t* __restrict__ bag_offsets, int num_bags, int n,
     if (static_cast<int>(blockIdx.x) < map_blocks)
         bagmap_entry(blockIdx.x * 256 + threadIdx.x, bag_offsets, num_bags, n, map);
     else
-        tile_first_segment((blockIdx.x - map_blocks) * 256 + threadIdx.x, occ_offsets, d_num_unique, num_tiles, tile_seg0);
+        tile_first_segment((blockIdx.x - map_blocks) * 256 + threadIdx.x, occ_offsets, d_num_unique, n, num_tiles, tile_seg0);
 }
 
 // Partition policy that sorts tiles by the bucket of their relative position inside a long segment; tiles that are
@@ -240,7 +240,7 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                 const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ occ, const int32_t* __restrict__ d_num_unique,
                 const int32_t* __restrict__ unique_to_send, const BagMapEntry* __restrict__ bagmap,
                 const int32_t* __restrict__ tile_seg0, const int32_t* __restrict__ order, const int32_t* __restrict__ order_offsets,
-                int num_tiles, RowSink sink, float* __restrict__ tile_left, float* __restrict__ tile_right,
+                int num_tiles, int ucap, RowSink sink, float* __restrict__ tile_left, float* __restrict__ tile_right,
                 int32_t* __restrict__ tile_rseg) {
     static_assert(!PAIR || (NV == 2 && FUSED == kSinkGrads), "the pair layout is two words per lane, plain sink");
     constexpr int GPB = 256 / LPR;
@@ -277,8 +277,9 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     const int tile_start = tile * kBwdTile;
     const int i = tile_start + t;
     const bool valid = i < n;
-    const int U = *d_num_unique;
-    const int u0 = tile_seg0[tile];
+    const int U = device_count(d_num_unique, ucap);  // ucap = min(n, cap): rows of grads / entries of unique_to_send
+    int u0 = tile_seg0[tile];
+    if (u0 >= U) u0 = U > 0 ? U - 1 : 0;  // only with a count above the caller's bound (a broken precondition): stay inside the lists
     const int words = dim / 4;
     const int g = t / LPR, r = t % LPR;
     const int wv_id = t / kWave;
@@ -643,6 +644,7 @@ struct BwdArgs {
     const int32_t* occ_offsets;
     const int32_t* occ;
     const int32_t* d_num_unique;
+    int cap;
     const int32_t* unique_to_send;
     RowSink sink;
     void* ws;
@@ -723,7 +725,7 @@ void bwd_launch(const BwdArgs& a) {
 #define NP_BWD_MAIN(L_, N_, M_, T_, P_)                                                                                        \
     NP_LAUNCH("bwd_main", (bwd_main_kernel<L_, N_, M_, T_, FUSED, P_>), dim3(main_grid), dim3(256), 0, a.stream,                 \
               static_cast<const T_*>(a.dY), a.dim, seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique,     \
-              a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.sink, tile_left, tile_right, tile_rseg)
+              a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.cap < a.n ? a.cap : a.n, a.sink, tile_left, tile_right, tile_rseg)
     bool launched = false;
     if constexpr (FUSED == kSinkGrads && NV == 1 && LPR >= 8) {
         // bf16 rows a multiple of 8 elements wide: half the lanes per row, 16-byte loads (words 2r, 2r + 1 per lane)
@@ -796,7 +798,7 @@ int np_lookup_bwd_prepare(int32_t dy_dtype, int32_t dim, int32_t mode, int32_t m
     const int rc = bwd_check_common(dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, d_num_unique, NP_MAX_DIM, ws,
                                     ws_bytes, &nothing);
     if (rc != NP_OK || nothing) return rc;
-    np::BwdArgs a{nullptr, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, nullptr, d_num_unique, nullptr,
+    np::BwdArgs a{nullptr, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, nullptr, d_num_unique, n, nullptr,
                   np::RowSink{nullptr, nullptr, nullptr, nullptr, 0.f, 0.f, 0.f}, ws, static_cast<hipStream_t>(stream), false};
     np::bwd_prepare_launch(a, np::bwd_plan(a));
     return np::launch_status();
@@ -813,7 +815,7 @@ static int bwd_reduce(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mod
     if (rc != NP_OK || nothing) return rc;
     if (!dY || !occ || !grads) return NP_ERR_INVALID_ARG;
     if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(grads, 16)) return NP_ERR_INVALID_ARG;
-    np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, unique_to_send,
+    np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, cap, unique_to_send,
                   np::RowSink{grads, nullptr, nullptr, nullptr, 0.f, 0.f, 0.f}, ws, static_cast<hipStream_t>(stream), prepared};
     const int words = dim / 4;
     if (words <= 4) np::bwd_launch<4, 1, np::kSinkGrads>(a);
@@ -860,7 +862,7 @@ int np_lookup_bwd_adagrad_t(const void* dY, int32_t dy_dtype, int32_t dim, int32
     if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(table, table_dtype == NP_F32 ? 16 : 8))
         return NP_ERR_INVALID_ARG;
     if (!ws || !np::aligned(ws, 256) || ws_bytes < np_lookup_bwd_workspace_bytes(num_bags, n, dim, mode)) return NP_ERR_WORKSPACE;
-    np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, nullptr,
+    np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, cap, nullptr,
                   np::RowSink{nullptr, table, state, unique, lr, eps, 1.0f / static_cast<float>(dim)}, ws,
                   static_cast<hipStream_t>(stream), false};
     const int words = dim / 4;

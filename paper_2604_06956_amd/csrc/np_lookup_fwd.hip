@@ -372,11 +372,11 @@ void fwd_seq_bf16x8_launch(const float* table, int dim, const int64_t* list_keys
 template <int LPR, int NV, typename TabT>
 __global__ void __launch_bounds__(256)
 fwd_rows_kernel(const TabT* __restrict__ table, int dim, const int64_t* __restrict__ list_keys,
-                const int32_t* __restrict__ d_num_list, TabT* __restrict__ rows_out) {
+                const int32_t* __restrict__ d_num_list, int cap, TabT* __restrict__ rows_out) {
     constexpr int GPB = 256 / LPR;
     const int r = threadIdx.x % LPR;
     const int words = dim / 4;
-    const int L = *d_num_list;
+    const int L = device_count(d_num_list, cap);
     for (int64_t p = static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR; p < L; p += static_cast<int64_t>(gridDim.x) * GPB) {
         const TabT* src = table + static_cast<size_t>(list_keys[p]) * dim;
         TabT* dst = rows_out + static_cast<size_t>(p) * dim;
@@ -442,7 +442,7 @@ void fwd_launch(const FwdArgs& a) {
         int64_t want = (static_cast<int64_t>(a.cap) + GPB - 1) / GPB;
         const unsigned grid = static_cast<unsigned>(want < 16384 ? want : 16384);
         NP_LAUNCH("fwd_rows", (fwd_rows_kernel<LPR, NV, TabT>), dim3(grid), dim3(256), 0, a.stream, table, a.dim, a.list_keys,
-                  a.d_num_list, static_cast<TabT*>(a.rows_out));
+                  a.d_num_list, a.cap, static_cast<TabT*>(a.rows_out));
     }
 }
 

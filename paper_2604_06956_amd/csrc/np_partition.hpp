@@ -65,9 +65,15 @@ __host__ __device__ __forceinline__ int64_t chunk_begin(const ChunkPlan& p, int 
 // requirement grows monotonically with the input size (the chunk count itself does not).
 inline size_t part_hist_elems(const ChunkPlan&, int bins) { return static_cast<size_t>(kTargetChunks) * bins; }
 
+// gofs, binstart, btot (one word per bin each) and 16 words of scan scratch, rounded up so that the staging area
+// behind them is 16-byte aligned for any bin count (64-bit keys are staged there).
+__host__ __device__ __forceinline__ size_t part_fixed_lds_bytes(int bins) {
+    return (3 * sizeof(uint32_t) * static_cast<size_t>(bins) + 64 + 15) / 16 * 16;
+}
+
 template <typename KeyT>
 inline size_t part_scatter_lds_bytes(int bins, bool stage_digit) {
-    const size_t fixed = 3 * sizeof(uint32_t) * bins + 64;  // gofs, binstart, btot, scan scratch
+    const size_t fixed = part_fixed_lds_bytes(bins);
     const size_t cnt = align_up(sizeof(uint16_t) * kPartWaves * bins, 16);  // a wave ranks kPartIPT * 64 <= 65535 items
     size_t stage = (sizeof(KeyT) + sizeof(uint32_t)) * kPartTile;
     if (stage_digit) stage += sizeof(uint16_t) * kPartTile;
@@ -85,6 +91,12 @@ __device__ __forceinline__ uint64_t match_any(uint32_t d, int nbits, bool valid)
     return peers;
 }
 
+// The item count the kernels work on: the device-side count when one is given, never more than the host bound the
+// buffers and the grid were sized for (a stale or corrupt count must not walk past them).
+__device__ __forceinline__ int64_t part_count(int n_host, const int* __restrict__ d_n) {
+    return d_n ? device_count(d_n, n_host) : n_host;
+}
+
 // A policy supplies:
 //   using KeyT; static constexpr bool kStageDigit;
 //   __device__ void load(int64_t i, KeyT& k, uint32_t& v) const;   item i of the input
@@ -100,7 +112,7 @@ __global__ void __launch_bounds__(kHistThreads)
 part_hist_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, ChunkPlan plan, uint32_t* __restrict__ H) {
     extern __shared__ uint32_t lh[];
     const int c = blockIdx.x;
-    const int64_t n = d_n ? *d_n : n_host;
+    const int64_t n = part_count(n_host, d_n);
     for (int b = threadIdx.x; b < bins; b += kHistThreads) lh[b] = 0;
     __syncthreads();
     const int64_t lo = chunk_begin(plan, c);
@@ -196,7 +208,7 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
     uint32_t* binstart = gofs + bins;
     uint32_t* btot = binstart + bins;
     int* scan_tmp = reinterpret_cast<int*>(btot + bins);  // 16 ints
-    unsigned char* un = reinterpret_cast<unsigned char*>(scan_tmp + 16);
+    unsigned char* un = smem_raw + part_fixed_lds_bytes(bins);
     volatile uint16_t* cnt = reinterpret_cast<volatile uint16_t*>(un);  // [waves][bins], aliased with the staging area
     KeyT* skey = reinterpret_cast<KeyT*>(un);
     uint32_t* sval = reinterpret_cast<uint32_t*>(skey + kPartTile);
@@ -204,7 +216,7 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
 
     const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
     const int c = xcd_remap(blockIdx.x, gridDim.x);
-    const int64_t n = d_n ? *d_n : n_host;
+    const int64_t n = part_count(n_host, d_n);
     const int bpt = (bins + kPartThreads - 1) / kPartThreads;
     const int b0 = tid * bpt;
     const int b1 = b0 + bpt < bins ? b0 + bpt : bins;
@@ -329,7 +341,8 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
     }
 }
 
-// Enqueue one partition pass.  H needs part_hist_elems() words, bin_total needs `bins` words.
+// Enqueue one partition pass over n_host items, or over min(*d_n, n_host) items when d_n is given.  H needs
+// part_hist_elems() words, bin_total needs `bins` words.
 template <class P>
 inline void run_partition_pass(const P& pol, int n_host, const int* d_n, int bins, int nbits, const ChunkPlan& plan,
                                uint32_t* H, uint32_t* bin_total, int32_t* totals_out, int32_t* offsets_out,

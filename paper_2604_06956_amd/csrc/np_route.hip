@@ -39,6 +39,39 @@ route_compose_kernel(const int32_t* __restrict__ inverse, int n, const int32_t* 
         lookup_to_send[j] = unique_to_send[inverse[j]];
 }
 
+static int route_check(const int64_t* unique, const int32_t* d_num_unique, int32_t cap, int32_t num_shards, int32_t shard_fn,
+                       int64_t* send_keys, int32_t* splits, int32_t* send_offsets, int32_t* send_from_unique,
+                       int32_t* unique_to_send, const int32_t* inverse, int32_t n, int32_t* lookup_to_send, int32_t max_shards) {
+    if (cap < 0 || num_shards < 1 || !d_num_unique || !splits || !send_offsets) return NP_ERR_INVALID_ARG;
+    if (shard_fn != NP_SHARD_MOD && shard_fn != NP_SHARD_HASH) return NP_ERR_INVALID_ARG;
+    if (cap > 0 && (!unique || !send_keys || !send_from_unique || !unique_to_send)) return NP_ERR_INVALID_ARG;
+    if ((inverse == nullptr) != (lookup_to_send == nullptr) || n < 0) return NP_ERR_INVALID_ARG;
+    if (num_shards > max_shards) return NP_ERR_UNSUPPORTED;
+    if (!aligned(unique, 8) || !aligned(send_keys, 8)) return NP_ERR_INVALID_ARG;
+    return NP_OK;
+}
+
+// Enqueues the pass; H holds part_hist_elems() words, bin_total num_shards words.  Both are fully written before they
+// are read (every chunk writes every bin of its histogram row), so neither has to be cleared.
+static int route_enqueue(const int64_t* unique, const int32_t* d_num_unique, int32_t cap, int32_t num_shards, int32_t shard_fn,
+                         int64_t* send_keys, int32_t* splits, int32_t* send_offsets, int32_t* send_from_unique,
+                         int32_t* unique_to_send, const int32_t* inverse, int32_t n, int32_t* lookup_to_send, uint32_t* H,
+                         uint32_t* bin_total, hipStream_t s) {
+    const ChunkPlan plan = make_chunk_plan(cap);
+    int nbits = 0;
+    while ((1 << nbits) < num_shards) ++nbits;
+    RoutePolicy pol{unique, send_keys, send_from_unique, unique_to_send, make_fastmod(static_cast<uint32_t>(num_shards)),
+                    shard_fn == NP_SHARD_HASH ? 1 : 0};
+    run_partition_pass(pol, cap, d_num_unique, num_shards, nbits, plan, H, bin_total, splits, send_offsets, s, "route_hist",
+                       "route_colscan", "route_scatter");
+    if (inverse && n > 0) {
+        int grid = (n + 255) / 256;
+        if (grid > 8192) grid = 8192;
+        NP_LAUNCH("route_compose", route_compose_kernel, dim3(grid), dim3(256), 0, s, inverse, n, unique_to_send, lookup_to_send);
+    }
+    return launch_status();
+}
+
 }  // namespace np
 
 extern "C" {
@@ -53,31 +86,15 @@ int np_route(const int64_t* unique, const int32_t* d_num_unique, int32_t cap, in
              int64_t* send_keys, int32_t* splits, int32_t* send_offsets, int32_t* send_from_unique,
              int32_t* unique_to_send, const int32_t* inverse, int32_t n, int32_t* lookup_to_send, void* ws,
              size_t ws_bytes, void* stream) {
-    if (cap < 0 || num_shards < 1 || !d_num_unique || !splits || !send_offsets) return NP_ERR_INVALID_ARG;
-    if (shard_fn != NP_SHARD_MOD && shard_fn != NP_SHARD_HASH) return NP_ERR_INVALID_ARG;
-    if (cap > 0 && (!unique || !send_keys || !send_from_unique || !unique_to_send)) return NP_ERR_INVALID_ARG;
-    if ((inverse == nullptr) != (lookup_to_send == nullptr) || n < 0) return NP_ERR_INVALID_ARG;
-    if (num_shards > NP_MAX_SHARDS) return NP_ERR_UNSUPPORTED;
-    if (!np::aligned(unique, 8) || !np::aligned(send_keys, 8)) return NP_ERR_INVALID_ARG;
+    const int rc = np::route_check(unique, d_num_unique, cap, num_shards, shard_fn, send_keys, splits, send_offsets, send_from_unique,
+                                   unique_to_send, inverse, n, lookup_to_send, NP_MAX_SHARDS);
+    if (rc != NP_OK) return rc;
     if (!ws || !np::aligned(ws, 256) || ws_bytes < np_route_workspace_bytes(cap, num_shards)) return NP_ERR_WORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const np::ChunkPlan plan = np::make_chunk_plan(cap);
     np::WsCursor cur(ws);
-    uint32_t* H = cur.take<uint32_t>(np::part_hist_elems(plan, num_shards));
+    uint32_t* H = cur.take<uint32_t>(np::part_hist_elems(np::make_chunk_plan(cap), num_shards));
     uint32_t* bin_total = cur.take<uint32_t>(num_shards);
-    int nbits = 0;
-    while ((1 << nbits) < num_shards) ++nbits;
-    np::RoutePolicy pol{unique, send_keys, send_from_unique, unique_to_send, np::make_fastmod(static_cast<uint32_t>(num_shards)),
-                        shard_fn == NP_SHARD_HASH ? 1 : 0};
-    np::run_partition_pass(pol, 0, d_num_unique, num_shards, nbits, plan, H, bin_total, splits, send_offsets, s,
-                           "route_hist", "route_colscan", "route_scatter");
-    if (inverse && n > 0) {
-        int grid = (n + 255) / 256;
-        if (grid > 8192) grid = 8192;
-        NP_LAUNCH("route_compose", np::route_compose_kernel, dim3(grid), dim3(256), 0, s, inverse, n, unique_to_send,
-                  lookup_to_send);
-    }
-    return np::launch_status();
+    return np::route_enqueue(unique, d_num_unique, cap, num_shards, shard_fn, send_keys, splits, send_offsets, send_from_unique,
+                             unique_to_send, inverse, n, lookup_to_send, H, bin_total, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -115,7 +115,7 @@ def test_dedup_without_inverse(H):
 
 # ------------------------------------------------------------------------------------------ route
 
-@pytest.mark.parametrize("S,fn", [(1, 0), (8, 0), (8, 1), (64, 1), (1000, 0), (1536, 1), (4096, 1)])
+@pytest.mark.parametrize("S,fn", [(1, 0), (3, 1), (7, 0), (8, 0), (8, 1), (64, 1), (1000, 0), (1535, 1), (1536, 1), (4095, 0), (4096, 1)])
 @pytest.mark.parametrize("U", [1, 4097, 300000])
 def test_route_bit_exact(H, S, fn, U):
     import torch
