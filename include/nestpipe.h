@@ -61,6 +61,7 @@ enum { NP_POOL_SUM = 0, NP_POOL_MEAN = 1, NP_SEQ = 2 };
 enum { NP_F32 = 0, NP_BF16 = 1, NP_F16 = 2 };  /* NP_F16 (IEEE binary16) is a table dtype only */
 
 #define NP_MAX_SHARDS 4096
+#define NP_ROUTE_STATIC_MAX_SHARDS 2048 /* np_route_static: shards its built-in scratch is sized for */
 #define NP_MAX_DIM 1024
 
 /* Library version (major * 10000 + minor * 100 + patch).  Host function. */
@@ -114,6 +115,25 @@ int np_route(const int64_t* unique, const int32_t* d_num_unique, int32_t cap, in
              int32_t* unique_to_send, const int32_t* inverse, int32_t n, int32_t* lookup_to_send, void* ws,
              size_t ws_bytes, void* stream);
 size_t np_route_workspace_bytes(int32_t cap, int32_t num_shards);
+
+/*
+ * np_route_static - np_route for callers that cannot allocate or hand over a workspace: code recorded under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus ws / ws_bytes), same
+ * kernels and bit-identical outputs; the scratch of the pass (the 512 x num_shards histogram matrix and the
+ * per-shard totals) lives in a device array built into the library, 4 MiB + 8 KiB per GPU the library runs on,
+ * held until the process ends.  The call allocates and frees nothing; the first call on a device looks the
+ * array's address up (hipGetSymbolAddress) and keeps it.
+ *
+ *   num_shards > NP_ROUTE_STATIC_MAX_SHARDS  ->  NP_ERR_UNSUPPORTED (nothing enqueued); cap is not limited.
+ *   The address lookup failing               ->  NP_ERR_HIP.
+ *
+ * Every call on one GPU uses that GPU's one array: calls that may overlap there (different streams, or host
+ * threads enqueueing on different streams) race on it and must be ordered by the caller.  Nothing in the array has
+ * to start at zero (each pass writes every word it later reads), so calls in a row need no clearing in between.
+ */
+int np_route_static(const int64_t* unique, const int32_t* d_num_unique, int32_t cap, int32_t num_shards, int32_t shard_fn,
+                    int64_t* send_keys, int32_t* splits, int32_t* send_offsets, int32_t* send_from_unique,
+                    int32_t* unique_to_send, const int32_t* inverse, int32_t n, int32_t* lookup_to_send, void* stream);
 
 /*
  * np_lookup_fwd - Section IV-A, "Embedding Retrieval" (the owner reads the vectors of the deduplicated

@@ -28,6 +28,7 @@ SHARD_MOD, SHARD_HASH = 0, 1
 POOL_SUM, POOL_MEAN, SEQ = 0, 1, 2
 F32, BF16, F16 = 0, 1, 2
 MAX_SHARDS = 4096
+ROUTE_STATIC_MAX_SHARDS = 2048
 
 _vp, _i32, _i64, _sz, _f32, _u64 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float,
                                     ctypes.c_uint64)
@@ -45,6 +46,8 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.np_dedup_workspace_bytes.argtypes = [_i32, _i32]
     L.np_route.restype = ctypes.c_int
     L.np_route.argtypes = [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
+    L.np_route_static.restype = ctypes.c_int
+    L.np_route_static.argtypes = [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
     L.np_route_workspace_bytes.restype = _sz
     L.np_route_workspace_bytes.argtypes = [_i32, _i32]
     L.np_lookup_fwd.restype = ctypes.c_int
@@ -196,6 +199,19 @@ def np_route(unique: torch.Tensor, num_unique: torch.Tensor, cap: int, num_shard
                       _ptr(out["unique_to_send"], torch.int32), _ptr(inverse, torch.int32), n if inverse is not None else 0,
                       _ptr(out.get("lookup_to_send"), torch.int32) if inverse is not None else 0, _ptr(ws), ws_bytes, _stream())
     _chk("np_route", rc)
+    return out
+
+
+def np_route_static(unique: torch.Tensor, num_unique: torch.Tensor, cap: int, num_shards: int, shard_fn: int,
+                    out: Dict[str, torch.Tensor], inverse: Optional[torch.Tensor] = None, n: int = 0) -> Dict[str, torch.Tensor]:
+    """np_route on the library's built-in scratch.  Nothing is allocated on the way, here or in the library: the caller
+    brings every output tensor in ``out`` (the keys np_route returns; ``lookup_to_send`` too when ``inverse`` is given)."""
+    rc = lib.np_route_static(_ptr(unique, torch.int64), _ptr(num_unique, torch.int32), cap, num_shards, shard_fn,
+                             _ptr(out["send_keys"], torch.int64), _ptr(out["splits"], torch.int32), _ptr(out["send_offsets"], torch.int32),
+                             _ptr(out["send_from_unique"], torch.int32), _ptr(out["unique_to_send"], torch.int32), _ptr(inverse, torch.int32),
+                             n if inverse is not None else 0, _ptr(out["lookup_to_send"], torch.int32) if inverse is not None else 0,
+                             _stream())
+    _chk("np_route_static", rc)
     return out
 
 

@@ -39,6 +39,32 @@ route_compose_kernel(const int32_t* __restrict__ inverse, int n, const int32_t* 
         lookup_to_send[j] = unique_to_send[inverse[j]];
 }
 
+// The allocation-free variant keeps its scratch (the chunk x shard histogram matrix and the per-shard totals) in this
+// file-scope device array instead of a caller workspace.  In host code the array's name is only a handle: its device
+// address is asked for once per device with hipGetSymbolAddress and kept in route_scratch_ptr.
+constexpr size_t kRouteStaticHistBytes = sizeof(uint32_t) * static_cast<size_t>(kTargetChunks) * NP_ROUTE_STATIC_MAX_SHARDS;
+constexpr size_t kRouteStaticBytes = kRouteStaticHistBytes + sizeof(uint32_t) * NP_ROUTE_STATIC_MAX_SHARDS;
+static __device__ __align__(256) unsigned char scratch[kRouteStaticBytes];
+
+static std::atomic<unsigned char*> route_scratch_ptr[kMaxDevices];
+
+// Device address of this device's copy of `scratch` (nullptr on failure).  The calling thread's current device decides
+// which copy; racing first calls ask twice and store the same address.
+static unsigned char* route_scratch_for_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    unsigned char* p = route_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    p = static_cast<unsigned char*>(sym);
+    route_scratch_ptr[dev].store(p, std::memory_order_release);
+    return p;
+}
+
 static int route_check(const int64_t* unique, const int32_t* d_num_unique, int32_t cap, int32_t num_shards, int32_t shard_fn,
                        int64_t* send_keys, int32_t* splits, int32_t* send_offsets, int32_t* send_from_unique,
                        int32_t* unique_to_send, const int32_t* inverse, int32_t n, int32_t* lookup_to_send, int32_t max_shards) {
@@ -93,6 +119,20 @@ int np_route(const int64_t* unique, const int32_t* d_num_unique, int32_t cap, in
     np::WsCursor cur(ws);
     uint32_t* H = cur.take<uint32_t>(np::part_hist_elems(np::make_chunk_plan(cap), num_shards));
     uint32_t* bin_total = cur.take<uint32_t>(num_shards);
+    return np::route_enqueue(unique, d_num_unique, cap, num_shards, shard_fn, send_keys, splits, send_offsets, send_from_unique,
+                             unique_to_send, inverse, n, lookup_to_send, H, bin_total, static_cast<hipStream_t>(stream));
+}
+
+int np_route_static(const int64_t* unique, const int32_t* d_num_unique, int32_t cap, int32_t num_shards, int32_t shard_fn,
+                    int64_t* send_keys, int32_t* splits, int32_t* send_offsets, int32_t* send_from_unique,
+                    int32_t* unique_to_send, const int32_t* inverse, int32_t n, int32_t* lookup_to_send, void* stream) {
+    const int rc = np::route_check(unique, d_num_unique, cap, num_shards, shard_fn, send_keys, splits, send_offsets, send_from_unique,
+                                   unique_to_send, inverse, n, lookup_to_send, NP_ROUTE_STATIC_MAX_SHARDS);
+    if (rc != NP_OK) return rc;
+    unsigned char* base = np::route_scratch_for_current_device();
+    if (!base) return NP_ERR_HIP;
+    uint32_t* H = reinterpret_cast<uint32_t*>(base);
+    uint32_t* bin_total = reinterpret_cast<uint32_t*>(base + np::kRouteStaticHistBytes);
     return np::route_enqueue(unique, d_num_unique, cap, num_shards, shard_fn, send_keys, splits, send_offsets, send_from_unique,
                              unique_to_send, inverse, n, lookup_to_send, H, bin_total, static_cast<hipStream_t>(stream));
 }

@@ -86,6 +86,10 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.np_route(8, 8, 10, 8, 7, 8, 8, 8, 8, 8, None, 0, None, 256, 1 << 20, None) == -1      # bad rule
     assert lib.np_route(8, 8, 10, 5000, 0, 8, 8, 8, 8, 8, None, 0, None, 256, 1 << 20, None) == -3   # too many shards
     assert lib.np_route(8, 8, 10, 8, 0, 8, 8, 8, 8, 8, 8, 5, None, 256, 1 << 20, None) == -1         # inverse without output
+    lib.np_route_static.restype = ctypes.c_int
+    lib.np_route_static.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp]
+    assert lib.np_route_static(8, 8, 10, 2049, 0, 8, 8, 8, 8, 8, None, 0, None, None) == -3   # beyond the built-in scratch
+    assert lib.np_route_static(8, 8, 10, 0, 0, 8, 8, 8, 8, 8, None, 0, None, None) == -1      # no shards
     lib.np_lookup_fwd.restype = ctypes.c_int
     lib.np_lookup_fwd.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, vp, vp, ctypes.c_int32, vp, vp, ctypes.c_int32,
                                   ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
