@@ -14,18 +14,8 @@ RTOL_BF16 = 1e-2
 
 
 def progress(msg: str) -> None:
-    """A timestamped line in a progress log beside the test outputs: long full-size tests stay visibly alive while
-    pytest captures stdout."""
-    import os
-    import time
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    d = os.path.join(root, "gpurun_out")
-    try:
-        os.makedirs(d, exist_ok=True)
-        with open(os.path.join(d, "test_progress.log"), "a") as f:
-            f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
-    except OSError:
-        pass
+    """A flushed line on stdout (shown with pytest -s, kept in the captured output otherwise): names the case before a
+    long GPU step starts, so that the tail of a run that dies still says where it was."""
     print(msg, flush=True)
 
 

@@ -35,13 +35,24 @@ def _split(batch, cfg, N, rng):
     return out
 
 
-def _microbatch_grads(H, cfg, batch, dY, N, seed):
+def _split_by_samples(batch, cfg, assign, N):
+    """Micro-batches of whole samples (all the bags of a sample go together), e.g. the clustering's result."""
+    from paper_2604_06956_amd import clustering as C
+    out = []
+    for i in range(N):
+        pos, off, bags = C.micro_batch_lookups(batch.bag_offsets, cfg.batch, cfg.features, assign, i)
+        out.append((bags, off, batch.keys[pos]))
+    return out
+
+
+def _microbatch_grads(H, cfg, batch, dY, N, seed, parts=None):
     """-> merged unique keys, merged gradient rows (numpy), sum of micro-batch unique counts."""
     import torch
     B = H.B
     D = cfg.dim
     rng = np.random.default_rng(seed)
-    parts = _split(batch, cfg, N, rng)
+    if parts is None:
+        parts = _split(batch, cfg, N, rng)
     key_lists, grad_lists, total_u = [], [], 0
     for bags, off, keys in parts:
         if keys.size == 0:
@@ -110,3 +121,25 @@ def test_partition_invariance_and_single_update(H):
     rest = np.ones(R, bool)
     rest[unique] = False
     assert H.host(table)[rest].tobytes() == before[rest].tobytes()
+
+
+@pytest.mark.parametrize("name,N", [("tiny", 2), ("tiny", 8), ("scaled_large", 4), ("scaled_large", 32)])
+def test_clustered_micro_batches_give_the_whole_batch_gradient(H, name, N):
+    """Key-centric sample clustering (Section V-C) changes which samples share a micro-batch, nothing else: with integer
+    upstream gradients the accumulated gradient equals the whole-batch one bit for bit (Proposition 2), and the number
+    of vectors crossing the All2All, sum(U_i), does not exceed that of the consecutive split."""
+    from paper_2604_06956_amd import clustering as C
+    wl = H.wl
+    cfg = wl.config("tiny") if name == "tiny" else wl.scaled(wl.config("large"), 400, 32)
+    batch = wl.make_batch(cfg, 0)
+    rng = np.random.default_rng(N)
+    dY = rng.integers(-8, 9, size=(cfg.num_bags, cfg.dim)).astype(np.float32)
+    unique, inverse, counts, *_ = H.O.dedup(batch.keys)
+    whole, _ = H.O.lookup_bwd(dY, H.O.F32, cfg.dim, 0, 1, batch.bag_offsets, inverse, unique.size)
+    totals = {}
+    for kind, assign in (("clustered", C.cluster_samples(batch.keys, batch.bag_offsets, cfg.batch, N, inverse=inverse, counts=counts)),
+                         ("consecutive", C.consecutive_split(cfg.batch, N))):
+        keys, grads, totals[kind] = _microbatch_grads(H, cfg, batch, dY, N, seed=0, parts=_split_by_samples(batch, cfg, assign, N))
+        assert np.array_equal(keys, unique), kind
+        assert grads.tobytes() == whole.tobytes(), kind
+    assert unique.size <= totals["clustered"] <= totals["consecutive"]
