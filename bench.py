@@ -8,10 +8,11 @@ np_sparse_adagrad) over one synthetic batch, inputs already resident in HBM.  Co
 between two batches (the second built with 30 % distinct-key overlap where the configuration asks for it),
 and the Adagrad update stays live between steps.  Prints ONE JSON line:
 
-  value       lookups per second over the whole five-call step
+  value       lookups per second over the whole five-call step (np_dedup and np_route included)
+  fwd_bwd_update  the subset the metric's name speaks of: np_lookup_fwd + np_lookup_bwd + np_sparse_adagrad
   roofline    the longest-running kernel: algorithmic bytes per launch / its mean duration (HIP events
-              recorded by the library around every launch, on the launch stream) against 8 TB/s
-  cpu_baseline  the CPU oracle timed on a bounded sample of the same batch on the host cores
+              recorded by the library around the launches, on the launch stream) against 8 TB/s
+  cpu_baseline  the CPU oracle on batch 0 on the host's cores (one thread, and one process per core)
 """
 from __future__ import annotations
 
@@ -27,6 +28,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "measured_traffic.json")
+GPU_BOX_CPU_SHARE = 16    # worker processes the CPU leg may use on a one-GPU machine, whatever os.cpu_count() shows
 
 
 def algorithmic_bytes(n: int, U: int, B: int, D: int, S: int, mode: int, max_len: int, table_elem: int = 4) -> dict:
@@ -45,14 +48,27 @@ def algorithmic_bytes(n: int, U: int, B: int, D: int, S: int, mode: int, max_len
     }
 
 
-# HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the copy-kernel
-# calibration; see profiles/large_step_kernels.txt), keyed by (workload, kernel).  Static: bench.py cannot run
-# the profiler on itself.
-MEASURED_TRAFFIC = {("large", "bwd_main"): 14.59e9, ("large", "fwd_pool"): 9.52e9, ("large", "sparse_adagrad"): 8.38e9}
+def measured_traffic(workload: str, kernel: str, table_dtype: str):
+    """HBM-side bytes per launch of `kernel` from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs kept under profiles/
+    (scaled by the copy-kernel calibration; the file is rewritten by `python -m paper_2604_06956_amd.profile_summary`
+    together with the text summaries).  None when no profile of this workload / table type is on file."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            table = json.load(f)
+    except (OSError, ValueError):
+        return None
+    rec = table.get(f"{workload}/{table_dtype}", {}).get(kernel)
+    return None if rec is None else float(rec["fetch_bytes"]) + float(rec["write_bytes"])
+
 
 # the kernel that carries (nearly all of) each call's algorithmic bytes
 KERNEL_OF_CALL = {"sparse_adagrad": "np_sparse_adagrad", "bwd_main": "np_lookup_bwd", "fwd_pool": "np_lookup_fwd",
                   "fwd_seq": "np_lookup_fwd"}
+
+
+def call_of_kernel(k: str) -> str:
+    return ("np_dedup" if k.startswith("dedup") else "np_route" if k.startswith("route") else
+            "np_lookup_fwd" if k.startswith("fwd") else "np_lookup_bwd" if k.startswith("bwd") else "np_sparse_adagrad")
 
 
 def main() -> int:
@@ -64,24 +80,18 @@ def main() -> int:
     ap.add_argument("--table-dtype", choices=("f32", "bf16", "f16"), default="f32",
                     help="storage type of the table; bf16 / f16 run np_lookup_fwd_t / np_sparse_adagrad_t (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-div", type=int, default=2)
-    ap.add_argument("--fwp-report", action="store_true",
-                    help="also dedup batch 0 split into N micro-batches of consecutive samples and report sum(U_i)/U")
+    ap.add_argument("--cpu-sample-div", type=int, default=1, help="the CPU legs run on the first 1/div of batch 0's bags")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the headline step and its per-kernel table (what a profiler run wants)")
+    ap.add_argument("--cluster-only-8", action="store_true",
+                    help="key-centric sample clustering for N = 8 only instead of every N of the micro-batch table (it runs on the host)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives are built; "
               "the All2All exchanges are represented by np_route's send buffer).", file=sys.stderr)
         return 2
 
-    import torch
-    from paper_2604_06956_amd import binding as B
     from paper_2604_06956_amd import workloads as wl
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 3
-    torch.cuda.set_device(0)
-    dev = torch.device("cuda:0")
 
     cfg = wl.config(args.workload)
     t_gen = time.time()
@@ -91,15 +101,30 @@ def main() -> int:
     stats = [wl.batch_stats(b.keys) for b in batches]
     K0, K1 = np.unique(b0.keys), np.unique(b1.keys)
     overlap = float(np.intersect1d(K0, K1, assume_unique=True).size / K1.size)
+    del K0, K1
     gen_s = time.time() - t_gen
+
+    # ---- the oracle on the host's cores, before this process touches the GPU (its worker processes are forked)
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, b0, wl, args.cpu_sample_div, args.table_dtype)
+
+    import torch
+    from paper_2604_06956_amd import binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
 
     R, D, S = cfg.num_rows, cfg.dim, cfg.num_shards
     seq = cfg.mode == wl.SEQ
-    bf16_table = args.table_dtype != "f32"     # a 16-bit table, bf16 or fp16
+    lowp_table = args.table_dtype != "f32"     # a 16-bit table, bf16 or fp16
     table = torch.empty((R, D), dtype={"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[args.table_dtype],
                         device=dev)
     state = torch.zeros(R, dtype=torch.float32, device=dev)
-    if bf16_table:
+    if lowp_table:
         B.np_util_table_init_t(table, cfg.table_seed)
         fwd_call, adagrad_call = B.np_lookup_fwd_t, B.np_sparse_adagrad_t
     else:
@@ -120,9 +145,13 @@ def main() -> int:
         dbatch.append(dict(keys=torch.from_numpy(b.keys).to(dev), off=torch.from_numpy(b.bag_offsets).to(dev), dY=dY, n=b.n))
 
     i32, i64 = torch.int32, torch.int64
-    dd = dict(unique=torch.empty(n_max, dtype=i64, device=dev), inverse=torch.empty(n_max, dtype=i32, device=dev),
-              counts=torch.empty(n_max, dtype=i32, device=dev), occ_offsets=torch.empty(n_max + 1, dtype=i32, device=dev),
-              occ=torch.empty(n_max, dtype=i32, device=dev), num_unique=torch.zeros(1, dtype=i32, device=dev))
+
+    def dedup_buffers():
+        return dict(unique=torch.empty(n_max, dtype=i64, device=dev), inverse=torch.empty(n_max, dtype=i32, device=dev),
+                    counts=torch.empty(n_max, dtype=i32, device=dev), occ_offsets=torch.empty(n_max + 1, dtype=i32, device=dev),
+                    occ=torch.empty(n_max, dtype=i32, device=dev), num_unique=torch.zeros(1, dtype=i32, device=dev))
+
+    dd = dedup_buffers()
     # the unique-key count is known on the host for these synthetic batches, so U-sized buffers use cap, not n
     rr = dict(send_keys=torch.empty(cap, dtype=i64, device=dev), splits=torch.empty(S, dtype=i32, device=dev),
               send_offsets=torch.empty(S + 1, dtype=i32, device=dev), send_from_unique=torch.empty(cap, dtype=i32, device=dev),
@@ -141,24 +170,43 @@ def main() -> int:
     ev_dedup = torch.cuda.Event()
     ev_route = torch.cuda.Event()
 
-    def step(i: int) -> None:
+    def step(i: int, fwd_by: str = "keys", want_inverse: bool = True) -> None:
+        """The five calls on one batch.  The table is local to this worker, so the forward reads it by key (list_keys = the
+        batch's keys, idx = NULL); np_dedup still produces all of its outputs.  Gradients are reduced into send order and
+        applied with the send-ordered keys (the layout of the gradient All2All).  fwd_by = "inverse" is the requester-side
+        form of the forward, through (unique, inverse)."""
         bt = dbatch[i % 2]
         n = bt["n"]
         main_stream = torch.cuda.current_stream()   # the recording stream while a graph is being captured
-        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
+        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d, want_inverse=want_inverse)
         ev_dedup.record(main_stream)
         side_stream.wait_event(ev_dedup)
         with torch.cuda.stream(side_stream):
             B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
             ev_route.record(side_stream)
-        # the table is local, so the forward reads it through the requester-side list (unique keys, inverse map);
-        # gradients are produced in send order and applied with the send-ordered keys
-        fwd_call(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
-                 num_list=dd["num_unique"], cap=cap, out=out)
+        if fwd_by == "keys":
+            fwd_call(table, bt["keys"], None, bt["off"], n, cfg.mode, max_len, out_dtype, out=out)
+        else:
+            fwd_call(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
+                     num_list=dd["num_unique"], cap=cap, out=out)
         main_stream.wait_event(ev_route)
         B.np_lookup_bwd(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
                         unique_to_send=rr["unique_to_send"], grads=grads, ws=ws_b)
         adagrad_call(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
+
+    def timed_loop(fn, reps: int, warm: int = 2) -> float:
+        """Mean wall milliseconds of fn(step index) over `reps` calls, bracketed by device synchronisations."""
+        for i in range(warm):
+            fn(args.warmup + i)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(reps):
+            fn(args.warmup + i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / reps
+
+    def rate(ms: float) -> float:
+        return n_steps_lookups(dbatch, args) / (ms * 1e-3 * args.steps)
 
     for i in range(args.warmup):
         step(i)
@@ -179,6 +227,8 @@ def main() -> int:
     B.np_prof_enable(False)
     B.np_prof_only(None)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    lookups = n_steps_lookups(dbatch, args)
+    value = lookups / (t1 - t0)
 
     # ---- the same K steps again, untimed for the headline, with events around every launch: the per-kernel table
     B.np_prof_enable(True)
@@ -190,164 +240,6 @@ def main() -> int:
     ms_per_step_all_events = (time.perf_counter() - ta) * 1e3 / args.steps
     records = B.np_prof_collect(65536)
     B.np_prof_enable(False)
-    lookups = sum(dbatch[(args.warmup + i) % 2]["n"] for i in range(args.steps))
-    value = lookups / (t1 - t0)
-
-    # ---- the variant with backward and update fused (np_lookup_bwd_adagrad): not the headline, reported beside it
-    def step_fused(i: int) -> None:
-        bt = dbatch[i % 2]
-        n = bt["n"]
-        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
-        B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
-        fwd_call(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
-                 num_list=dd["num_unique"], cap=cap, out=out)
-        (B.np_lookup_bwd_adagrad_t if bf16_table else B.np_lookup_bwd_adagrad)(
-            bt["dY"], cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["unique"], dd["num_unique"], cap, table,
-            state, cfg.lr, cfg.eps, ws=ws_b)
-
-    fused = None
-    if D <= 256:
-        step_fused(0)
-        B.np_prof_enable(True)
-        torch.cuda.synchronize()
-        tf0 = time.perf_counter()
-        for i in range(args.steps):
-            step_fused(args.warmup + i)
-        torch.cuda.synchronize()
-        fused_ms = (time.perf_counter() - tf0) * 1e3 / args.steps
-        frec = B.np_prof_collect(65536)
-        B.np_prof_enable(False)
-        fk = {}
-        for name, ms in frec:
-            fk[name] = fk.get(name, 0.0) + ms / args.steps
-        fused = {"ms_per_step": fused_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (fused_ms * 1e-3 * args.steps),
-                 "bwd_update_ms": sum(v for k, v in fk.items() if k.startswith("bwd")),
-                 "kernels_ms": {k: v for k, v in fk.items() if k.startswith("bwd")}}
-
-    # ---- a worker that reads its own table by key needs no inverse map: np_dedup without it, forward over the raw
-    # keys (idx = NULL); reported beside the headline, whose forward goes through (unique, inverse)
-    def step_local(i: int) -> None:
-        bt = dbatch[i % 2]
-        n = bt["n"]
-        main_stream = torch.cuda.current_stream()
-        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d, want_inverse=False)
-        ev_dedup.record(main_stream)
-        side_stream.wait_event(ev_dedup)
-        with torch.cuda.stream(side_stream):
-            B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
-            ev_route.record(side_stream)
-        fwd_call(table, bt["keys"], None, bt["off"], n, cfg.mode, max_len, out_dtype, out=out)
-        main_stream.wait_event(ev_route)
-        B.np_lookup_bwd(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
-                        unique_to_send=rr["unique_to_send"], grads=grads, ws=ws_b)
-        adagrad_call(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
-
-    for i in range(2):
-        step_local(args.warmup + i)
-    torch.cuda.synchronize()
-    tl = time.perf_counter()
-    for i in range(args.steps):
-        step_local(args.warmup + i)
-    torch.cuda.synchronize()
-    local_ms = (time.perf_counter() - tl) * 1e3 / args.steps
-
-    # ---- both sides of the sharded flow on the one GPU (what every GPU does around the three All2Alls): the owner
-    # gathers the rows of the routed keys into the send buffer, the requester pools straight from that buffer through
-    # lookup_to_send; backward and update as in the headline.  fp32 tables only.
-    sharded_ms = None
-    if not bf16_table:
-        l2s = torch.empty(n_max, dtype=i32, device=dev)
-        rows_buf = torch.empty((cap, D), dtype=torch.float32, device=dev)
-        no_bags = torch.zeros(1, dtype=i32, device=dev)
-        rr_full = dict(rr, lookup_to_send=l2s)
-
-        def step_sharded(i: int) -> None:
-            bt = dbatch[i % 2]
-            n = bt["n"]
-            B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
-            B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, inverse=dd["inverse"], n=n, out=rr_full, ws=ws_r)
-            B.np_lookup_fwd(table, rr["send_keys"], None, no_bags, 0, cfg.mode, max_len, out_dtype, num_list=dd["num_unique"],
-                            cap=cap, out=out, rows_out=rows_buf)
-            B.np_lookup_fwd(rows_buf, None, l2s, bt["off"], n, cfg.mode, max_len, out_dtype, out=out)
-            B.np_lookup_bwd(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
-                            unique_to_send=rr["unique_to_send"], grads=grads, ws=ws_b)
-            B.np_sparse_adagrad(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
-
-        for i in range(2):
-            step_sharded(args.warmup + i)
-        torch.cuda.synchronize()
-        ts = time.perf_counter()
-        for i in range(args.steps):
-            step_sharded(args.warmup + i)
-        torch.cuda.synchronize()
-        sharded_ms = (time.perf_counter() - ts) * 1e3 / args.steps
-        del l2s, rows_buf
-
-    # ---- the backward in two parts: its index work (np_lookup_bwd_prepare) behind np_route on the second stream, beside
-    # the forward; the reduction (np_lookup_bwd_prepared) where np_lookup_bwd was.  Same bits; reported beside the headline.
-    dy_dtype_code = B.BF16 if seq else B.F32
-
-    def step_split(i: int) -> None:
-        bt = dbatch[i % 2]
-        n = bt["n"]
-        main_stream = torch.cuda.current_stream()
-        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
-        ev_dedup.record(main_stream)
-        side_stream.wait_event(ev_dedup)
-        with torch.cuda.stream(side_stream):
-            B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
-            B.np_lookup_bwd_prepare(dy_dtype_code, D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["num_unique"], ws_b)
-            ev_route.record(side_stream)
-        fwd_call(table, dd["unique"], dd["inverse"], bt["off"], n, cfg.mode, max_len, out_dtype,
-                 num_list=dd["num_unique"], cap=cap, out=out)
-        main_stream.wait_event(ev_route)
-        B.np_lookup_bwd_prepared(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
-                                 ws_b, unique_to_send=rr["unique_to_send"], grads=grads)
-        adagrad_call(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
-
-    for i in range(2):
-        step_split(args.warmup + i)
-    torch.cuda.synchronize()
-    tsp = time.perf_counter()
-    for i in range(args.steps):
-        step_split(args.warmup + i)
-    torch.cuda.synchronize()
-    split_ms = (time.perf_counter() - tsp) * 1e3 / args.steps
-
-    # ---- the same K steps without event recording (what the events cost)
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    torch.cuda.synchronize()
-    ms_per_step_noevents = (time.perf_counter() - t2) * 1e3 / args.steps
-
-    # ---- and once more with one event pair per step: the spread over the steps (the two batches differ a little)
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    marks[0].record()
-    for i in range(args.steps):
-        step(args.warmup + i)
-        marks[i + 1].record()
-    torch.cuda.synchronize()
-    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
-    step_spread = {"min_ms": per_step[0], "median_ms": per_step[len(per_step) // 2], "max_ms": per_step[-1]}
-
-    # ---- the same step recorded into one HIP graph per batch and replayed (the library only enqueues kernels, so a
-    # caller can do this; the launch-bound small workloads gain, configuration 5 does not)
-    graphs = []
-    for b in range(2):
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            step(b)
-        graphs.append(g)
-    for i in range(2):
-        graphs[(args.warmup + i) % 2].replay()
-    torch.cuda.synchronize()
-    t3 = time.perf_counter()
-    for i in range(args.steps):
-        graphs[(args.warmup + i) % 2].replay()
-    torch.cuda.synchronize()
-    graph_ms = (time.perf_counter() - t3) * 1e3 / args.steps
 
     kern = {}
     for name, ms in records:
@@ -358,13 +250,11 @@ def main() -> int:
                for k, v in kern.items()}
     call_ms = {}
     for k, v in kernels.items():
-        call = ("np_dedup" if k.startswith("dedup") else "np_route" if k.startswith("route") else
-                "np_lookup_fwd" if k.startswith("fwd") else "np_lookup_bwd" if k.startswith("bwd") else "np_sparse_adagrad")
-        call_ms[call] = call_ms.get(call, 0.0) + v["ms_per_step"]
+        call_ms[call_of_kernel(k)] = call_ms.get(call_of_kernel(k), 0.0) + v["ms_per_step"]
 
     n_avg = float(np.mean([s["n"] for s in stats]))
     U_avg = float(np.mean([s["U"] for s in stats]))
-    alg = algorithmic_bytes(int(n_avg), int(U_avg), cfg.num_bags, D, S, cfg.mode, max_len, 2 if bf16_table else 4)
+    alg = algorithmic_bytes(int(n_avg), int(U_avg), cfg.num_bags, D, S, cfg.mode, max_len, 2 if lowp_table else 4)
     # the dominant kernel and its mean duration come from the events of the timed region
     timed = {}
     for name, ms in timed_records:
@@ -378,79 +268,24 @@ def main() -> int:
     fbu_ms = sum(call_ms.get(c, 0.0) for c in ("np_lookup_fwd", "np_lookup_bwd", "np_sparse_adagrad"))
     fbu_bytes = alg["np_lookup_fwd"] + alg["np_lookup_bwd"] + alg["np_sparse_adagrad"]
 
-    # ---- bandwidth yardstick: a plain 16-byte copy kernel, 2 GiB each way
-    words = 2 ** 31
-    src = torch.empty(words, dtype=torch.uint8, device=dev)
-    dst = torch.empty(words, dtype=torch.uint8, device=dev)
-    B.np_util_stream_copy(dst, src)
+    # ---- np_route on its own (in the step it shares the GPU with the forward, so its event times there are not its cost)
+    B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(5):
-        B.np_util_stream_copy(dst, src)
-    e1.record()
+    r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    r0.record()
+    for _ in range(10):
+        B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
+    r1.record()
     torch.cuda.synchronize()
-    copy_gbs = 2 * words * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del src, dst
-
-    # ---- dual-buffer synchronisation of the two batches (Section IV-B), timed on its own: key-set intersection
-    # plus the copy of the common rows from an active to a prefetch row buffer
-    B.np_dedup(dbatch[0]["keys"], cfg.key_bits, out=dd, ws=ws_d)
-    ua, na_ = dd["unique"][:cap].clone(), dd["num_unique"].clone()
-    B.np_dedup(dbatch[1]["keys"], cfg.key_bits, out=dd, ws=ws_d)
-    ub, nb_ = dd["unique"][:cap], dd["num_unique"]
-    active = torch.empty((cap, D), dtype=torch.float32, device=dev)
-    prefetch = torch.empty((cap, D), dtype=torch.float32, device=dev)
-    isec = B.np_intersect(ua, na_, cap, ub, nb_, cap)
-    B.np_sync_rows(active, isec["idx_a"], prefetch, isec["idx_b"], isec["num_common"], cap)
-    torch.cuda.synchronize()
-    B.np_prof_enable(True)
-    reps = 5
-    for _ in range(reps):
-        B.np_intersect(ua, na_, cap, ub, nb_, cap, out=isec)
-        B.np_sync_rows(active, isec["idx_a"], prefetch, isec["idx_b"], isec["num_common"], cap)
-    torch.cuda.synchronize()
-    sync_rec = B.np_prof_collect(1024)
-    B.np_prof_enable(False)
-    common = int(isec["num_common"].item())
-    sync_k = {}
-    for name, ms in sync_rec:
-        sync_k[name] = sync_k.get(name, 0.0) + ms / reps
-    dbsync = {"common_keys": common, "ms": sum(sync_k.values()), "kernels_ms": sync_k,
-              "row_copy_GBps": 2 * common * 4 * D / (sync_k.get("sync_rows", 1e9) * 1e-3) / 1e9}
-    del active, prefetch, ua
-
-    fwp = None
-    if args.fwp_report:
-        # frozen-window micro-batching (Section V): keys are deduplicated inside each micro-batch only, so the
-        # vectors crossing the All2All inflate from U to sum(U_i)
-        fwp = {}
-        keys0, off0 = dbatch[0]["keys"], batches[0].bag_offsets
-        for N in (1, 2, 4, 8, 16, 32):
-            tot, ms = 0, 0.0
-            for i in range(N):
-                s0, s1 = cfg.batch * i // N, cfg.batch * (i + 1) // N
-                sl = [keys0[int(off0[f * cfg.batch + s0]):int(off0[f * cfg.batch + s1])] for f in range(cfg.features)]
-                mk = torch.cat(sl).contiguous()
-                if mk.numel() == 0:
-                    continue
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                B.np_dedup(mk, cfg.key_bits, out=dd, ws=ws_d)
-                e1.record()
-                torch.cuda.synchronize()
-                tot += int(dd["num_unique"].item())
-                ms += e0.elapsed_time(e1)
-            fwp[str(N)] = {"sum_unique": tot, "inflation": tot / stats[0]["U"], "dedup_ms_total": ms}
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, b0, wl, args.cpu_sample_div, args.table_dtype)
+    route_alone_ms = r0.elapsed_time(r1) / 10
 
     line = {
         "metric": "embedding lookups/sec (fwd+bwd+update) and achieved HBM GB/s on 1 MI355X",
         "value": value,
         "unit": "lookups/s",
+        "value_is": "lookups per second over the WHOLE five-call step (np_dedup + np_route + np_lookup_fwd + np_lookup_bwd + "
+                    "np_sparse_adagrad), the conservative reading of the metric; fwd_bwd_update.lookups_per_s is the three-call "
+                    "subset the metric's name speaks of",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -468,91 +303,415 @@ def main() -> int:
                    "num_bags": cfg.num_bags, "max_len": max_len},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if bf16_table else MEASURED_TRAFFIC.get((cfg.name, dominant)),
+                     "traffic": measured_traffic(cfg.name, dominant, args.table_dtype),
                      "algorithmic_bytes_per_launch": alg[dom_call], "avg_launch_ms": dom_avg_ms,
                      "launches_timed": timed[dominant][0]},
         "cpu_baseline": cpu,
         "fwd_bwd_update": {"ms_per_step": fbu_ms, "lookups_per_s": n_avg / (fbu_ms * 1e-3) if fbu_ms > 0 else None,
                            "algorithmic_GBps": fbu_bytes / (fbu_ms * 1e-3) / 1e9 if fbu_ms > 0 else None,
-                           "frac_of_peak": fbu_bytes / (fbu_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if fbu_ms > 0 else None},
+                           "frac_of_peak": fbu_bytes / (fbu_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if fbu_ms > 0 else None,
+                           "what": "sum of the HIP-event durations of the kernels of the three calls, per step"},
         "calls": {c: {"ms_per_step": call_ms.get(c, 0.0), "algorithmic_bytes": alg[c],
                       "algorithmic_GBps": alg[c] / (call_ms[c] * 1e-3) / 1e9 if call_ms.get(c, 0.0) > 0 else None}
                   for c in alg},
         "kernels": kernels,
-        "streams": "np_route runs on a second stream beside np_lookup_fwd; its event times include that sharing",
-        "prepared_bwd_step": {"ms_per_step": split_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (split_ms * 1e-3 * args.steps),
-                              "what": "np_lookup_bwd_prepare behind np_route on the second stream, np_lookup_bwd_prepared after the forward"},
-        "local_table_step": {"ms_per_step": local_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (local_ms * 1e-3 * args.steps),
-                             "what": "np_dedup without the inverse map, forward over the raw keys; no events"},
-        "sharded_flow_step": None if sharded_ms is None else {
-            "ms_per_step": sharded_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (sharded_ms * 1e-3 * args.steps),
-            "what": "owner-side row gather into the send buffer + requester-side pooling from it through lookup_to_send "
-                    "(np_route with the composed map); backward and update as in the headline; no events"},
-        "fused_bwd_update_step": fused,
-        "dual_buffer_sync": dbsync,
-        "frozen_window_dedup": fwp,
-        "ms_per_step_without_events": ms_per_step_noevents,
-        "step_time_spread": step_spread,
+        "streams": "np_route runs on a second stream beside np_lookup_fwd; its event times in `kernels` / `calls` include "
+                   "that sharing, calls.np_route.alone_ms is its time with the GPU to itself",
         "ms_per_step_with_events_on_every_launch": ms_per_step_all_events,
-        "hip_graph_replay": {"ms_per_step": graph_ms, "lookups_per_s": n_steps_lookups(dbatch, args) / (graph_ms * 1e-3 * args.steps)},
-        "stream_copy_GBps": copy_gbs,
         "input_generation_s": gen_s,
     }
+    line["calls"]["np_route"]["alone_ms"] = route_alone_ms
+    line["calls"]["np_route"]["alone_algorithmic_GBps"] = alg["np_route"] / (route_alone_ms * 1e-3) / 1e9
+    for k in timed:   # every row kernel that was timed in the headline region, against its own call's algorithmic bytes
+        line.setdefault("row_kernels", {})[k] = {
+            "avg_launch_ms": timed[k][1] / timed[k][0], "algorithmic_bytes_per_launch": alg[KERNEL_OF_CALL[k]],
+            "frac": alg[KERNEL_OF_CALL[k]] / (timed[k][1] / timed[k][0] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "traffic": measured_traffic(cfg.name, k, args.table_dtype)}
+
+    if not args.no_extras:
+        extras(line, args, cfg, wl, B, torch, dev, batches, stats, dbatch, dd, rr, dedup_buffers, table, state, out, grads,
+               ws_d, ws_r, ws_b, cap, n_max, max_len, out_dtype, fwd_call, adagrad_call, lowp_table, step, timed_loop, rate, alg,
+               side_stream, ev_dedup, ev_route)
     print(json.dumps(line))
     return 0
+
+
+def extras(line, args, cfg, wl, B, torch, dev, batches, stats, dbatch, dd, rr, dedup_buffers, table, state, out, grads, ws_d,
+           ws_r, ws_b, cap, n_max, max_len, out_dtype, fwd_call, adagrad_call, lowp_table, step, timed_loop, rate, alg, side_stream,
+           ev_dedup, ev_route) -> None:
+    """Everything reported beside the headline: other forms of the step, the next-row features, yardsticks."""
+    R, D, S = cfg.num_rows, cfg.dim, cfg.num_shards
+    seq = cfg.mode == wl.SEQ
+    i32, i64 = torch.int32, torch.int64
+    K = args.steps
+
+    # ---- the requester-side form of the forward: through (unique, inverse) instead of the raw keys
+    inv_ms = timed_loop(lambda i: step(i, fwd_by="inverse"), K)
+    line["forward_through_inverse_step"] = {
+        "ms_per_step": inv_ms, "lookups_per_s": rate(inv_ms),
+        "what": "np_lookup_fwd(list_keys = unique, idx = inverse): what a requester does with the owners' answers; no events"}
+
+    # ---- a worker that reads its own table by key needs no inverse map at all: np_dedup without it
+    local_ms = timed_loop(lambda i: step(i, want_inverse=False), K)
+    line["local_table_step"] = {"ms_per_step": local_ms, "lookups_per_s": rate(local_ms),
+                                "what": "as the headline, np_dedup called with inverse = NULL; no events"}
+
+    # ---- backward and update fused (np_lookup_bwd_adagrad): its own byte model, U*row less written and read again
+    def step_fused(i: int) -> None:
+        bt = dbatch[i % 2]
+        n = bt["n"]
+        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
+        B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
+        fwd_call(table, bt["keys"], None, bt["off"], n, cfg.mode, max_len, out_dtype, out=out)
+        (B.np_lookup_bwd_adagrad_t if lowp_table else B.np_lookup_bwd_adagrad)(
+            bt["dY"], cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["unique"], dd["num_unique"], cap, table,
+            state, cfg.lr, cfg.eps, ws=ws_b)
+
+    step_fused(0)
+    B.np_prof_enable(True)
+    fused_ms = timed_loop(step_fused, K, warm=0)
+    frec = B.np_prof_collect(65536)
+    B.np_prof_enable(False)
+    fk = {}
+    for name, ms in frec:
+        fk[name] = fk.get(name, 0.0) + ms / K
+    fused_bytes = alg["np_lookup_bwd"] + alg["np_sparse_adagrad"] - 2 * int(np.mean([s["U"] for s in stats])) * 4 * D
+    bu_ms = sum(v for k, v in fk.items() if k.startswith("bwd"))
+    fwd_ms = sum(v for k, v in fk.items() if k.startswith("fwd"))
+    line["fused_bwd_update_step"] = {
+        "ms_per_step": fused_ms, "lookups_per_s": rate(fused_ms), "bwd_update_ms": bu_ms,
+        "kernels_ms": {k: v for k, v in fk.items() if k.startswith("bwd")},
+        "algorithmic_bytes_bwd_update": fused_bytes,
+        "bwd_update_algorithmic_GBps": fused_bytes / (bu_ms * 1e-3) / 1e9 if bu_ms > 0 else None,
+        "fwd_bwd_update_frac_of_peak": ((alg["np_lookup_fwd"] + fused_bytes) / ((fwd_ms + bu_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS
+                                        if fwd_ms + bu_ms > 0 else None),
+        "what": "np_lookup_bwd_adagrad instead of np_lookup_bwd + np_sparse_adagrad (a worker that owns the rows it reduces): "
+                "the gradient rows are never written, so its byte model is the two calls' minus 2*U*row; events on every launch"}
+
+    # ---- both sides of the sharded flow on the one GPU (what every GPU does around the three All2Alls): the owner
+    # gathers the rows of the routed keys into the send buffer, the requester pools straight from that buffer through
+    # lookup_to_send; backward and update as in the headline.  fp32 tables only.
+    if not lowp_table:
+        l2s = torch.empty(n_max, dtype=i32, device=dev)
+        rows_buf = torch.empty((cap, D), dtype=torch.float32, device=dev)
+        no_bags = torch.zeros(1, dtype=i32, device=dev)
+        rr_full = dict(rr, lookup_to_send=l2s)
+
+        def step_sharded(i: int) -> None:
+            bt = dbatch[i % 2]
+            n = bt["n"]
+            B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
+            B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, inverse=dd["inverse"], n=n, out=rr_full, ws=ws_r)
+            B.np_lookup_fwd(table, rr["send_keys"], None, no_bags, 0, cfg.mode, max_len, out_dtype, num_list=dd["num_unique"],
+                            cap=cap, out=out, rows_out=rows_buf)
+            B.np_lookup_fwd(rows_buf, None, l2s, bt["off"], n, cfg.mode, max_len, out_dtype, out=out)
+            B.np_lookup_bwd(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
+                            unique_to_send=rr["unique_to_send"], grads=grads, ws=ws_b)
+            B.np_sparse_adagrad(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
+
+        sharded_ms = timed_loop(step_sharded, K)
+        line["sharded_flow_step"] = {
+            "ms_per_step": sharded_ms, "lookups_per_s": rate(sharded_ms),
+            "what": "owner-side row gather into the send buffer + requester-side pooling from it through lookup_to_send "
+                    "(np_route with the composed map); backward and update as in the headline; no events"}
+        del l2s, rows_buf
+
+    # ---- the backward in two parts: its index work (np_lookup_bwd_prepare) behind np_route on the second stream, beside
+    # the forward; the reduction (np_lookup_bwd_prepared) where np_lookup_bwd was.  Same bits.
+    dy_dtype_code = B.BF16 if seq else B.F32
+
+    def step_split(i: int) -> None:
+        bt = dbatch[i % 2]
+        n = bt["n"]
+        main_stream = torch.cuda.current_stream()
+        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
+        ev_dedup.record(main_stream)
+        side_stream.wait_event(ev_dedup)
+        with torch.cuda.stream(side_stream):
+            B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
+            B.np_lookup_bwd_prepare(dy_dtype_code, D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["num_unique"], ws_b)
+            ev_route.record(side_stream)
+        fwd_call(table, bt["keys"], None, bt["off"], n, cfg.mode, max_len, out_dtype, out=out)
+        main_stream.wait_event(ev_route)
+        B.np_lookup_bwd_prepared(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
+                                 ws_b, unique_to_send=rr["unique_to_send"], grads=grads)
+        adagrad_call(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
+
+    split_ms = timed_loop(step_split, K)
+    line["prepared_bwd_step"] = {"ms_per_step": split_ms, "lookups_per_s": rate(split_ms),
+                                 "what": "np_lookup_bwd_prepare behind np_route on the second stream, np_lookup_bwd_prepared after the forward"}
+
+    # ---- the headline step without event recording (what the events cost), and its spread over single steps
+    line["ms_per_step_without_events"] = timed_loop(step, K, warm=0)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    marks[0].record()
+    for i in range(K):
+        step(args.warmup + i)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(K))
+    line["step_time_spread"] = {"min_ms": per_step[0], "median_ms": per_step[len(per_step) // 2], "max_ms": per_step[-1]}
+
+    # ---- the same step recorded into one HIP graph per batch and replayed (the library only enqueues kernels, so a
+    # caller can do this; the launch-bound small workloads gain, configuration 5 does not)
+    graphs = []
+    for b in range(2):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step(b)
+        graphs.append(g)
+    graph_ms = timed_loop(lambda i: graphs[i % 2].replay(), K)
+    line["hip_graph_replay"] = {"ms_per_step": graph_ms, "lookups_per_s": rate(graph_ms)}
+    del graphs
+
+    # ---- bandwidth yardstick: a plain 16-byte copy kernel, 2 GiB each way
+    words = 2 ** 31
+    src = torch.empty(words, dtype=torch.uint8, device=dev)
+    dst = torch.empty(words, dtype=torch.uint8, device=dev)
+    B.np_util_stream_copy(dst, src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        B.np_util_stream_copy(dst, src)
+    e1.record()
+    torch.cuda.synchronize()
+    line["stream_copy_GBps"] = 2 * words * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+
+    if not lowp_table and not seq:
+        line["dual_buffer"] = dual_buffer(args, cfg, B, torch, dev, dbatch, dd, dedup_buffers, table, state, out, grads, ws_d, ws_b,
+                                          cap, n_max, max_len, out_dtype)
+    line["frozen_window_dedup"] = frozen_window(args, cfg, B, torch, batches, stats, dbatch, dd, ws_d)
+
+
+def dual_buffer(args, cfg, B, torch, dev, dbatch, dd1, dedup_buffers, table, state, out, grads, ws_d, ws_b, cap, n_max, max_len,
+                out_dtype) -> dict:
+    """Section IV-B on the two batches: the synchronisation on its own, and the inter-batch pipeline (B_t's prefetch on a
+    second stream before B_{t-1}'s update, then intersect + row copy, then B_t's forward from the prefetch buffer) against
+    the plain sequential order (B_{t-1}'s backward and update on the table, then B_t's forward from the table).  Timed from
+    the point where both batches are deduplicated."""
+    D = cfg.dim
+    i32, i64 = torch.int32, torch.int64
+    dd2 = dedup_buffers()
+    B.np_dedup(dbatch[0]["keys"], cfg.key_bits, out=dd1, ws=ws_d)
+    B.np_dedup(dbatch[1]["keys"], cfg.key_bits, out=dd2, ws=ws_d)
+    active = torch.empty((cap, D), dtype=torch.float32, device=dev)
+    prefetch = torch.empty((cap, D), dtype=torch.float32, device=dev)
+    astate = torch.zeros(cap, dtype=torch.float32, device=dev)
+    iota = torch.arange(cap, dtype=i64, device=dev)
+    no_bags = torch.zeros(1, dtype=i32, device=dev)
+    isec = dict(idx_a=torch.empty(cap, dtype=i32, device=dev), idx_b=torch.empty(cap, dtype=i32, device=dev),
+                num_common=torch.zeros(1, dtype=i32, device=dev))
+    ws_i = torch.empty(max(int(B.lib.np_intersect_workspace_bytes(cap)), 256), dtype=torch.uint8, device=dev)
+    b1, b2 = dbatch[0], dbatch[1]
+    # the synchronisation alone, per kernel
+    B.np_intersect(dd1["unique"], dd1["num_unique"], cap, dd2["unique"], dd2["num_unique"], cap, out=isec, ws=ws_i)
+    B.np_sync_rows(active, isec["idx_a"], prefetch, isec["idx_b"], isec["num_common"], cap)
+    torch.cuda.synchronize()
+    B.np_prof_enable(True)
+    reps = 5
+    for _ in range(reps):
+        B.np_intersect(dd1["unique"], dd1["num_unique"], cap, dd2["unique"], dd2["num_unique"], cap, out=isec, ws=ws_i)
+        B.np_sync_rows(active, isec["idx_a"], prefetch, isec["idx_b"], isec["num_common"], cap)
+    torch.cuda.synchronize()
+    sync_rec = B.np_prof_collect(1024)
+    B.np_prof_enable(False)
+    common = int(isec["num_common"].item())
+    sync_k = {}
+    for name, ms in sync_rec:
+        sync_k[name] = sync_k.get(name, 0.0) + ms / reps
+
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    ev_go, ev_prefetched = torch.cuda.Event(), torch.cuda.Event()
+
+    def sequential() -> None:
+        B.np_lookup_bwd(b1["dY"], D, cfg.mode, max_len, b1["off"], b1["n"], dd1["occ_offsets"], dd1["occ"], dd1["num_unique"], cap,
+                        grads=grads, ws=ws_b)
+        B.np_sparse_adagrad(table, state, dd1["unique"], grads, dd1["num_unique"], cap, cfg.lr, cfg.eps)
+        B.np_lookup_fwd(table, dd2["unique"], dd2["inverse"], b2["off"], b2["n"], cfg.mode, max_len, out_dtype,
+                        num_list=dd2["num_unique"], cap=cap, out=out)
+
+    def pipelined() -> None:
+        ev_go.record(main)
+        side.wait_event(ev_go)
+        with torch.cuda.stream(side):   # B_t's prefetch: its rows as the table holds them now (W_t)
+            B.np_lookup_fwd(table, dd2["unique"], None, no_bags, 0, cfg.mode, max_len, out_dtype, num_list=dd2["num_unique"], cap=cap,
+                            out=out, rows_out=prefetch)
+            ev_prefetched.record(side)
+        B.np_lookup_bwd(b1["dY"], D, cfg.mode, max_len, b1["off"], b1["n"], dd1["occ_offsets"], dd1["occ"], dd1["num_unique"], cap,
+                        grads=grads, ws=ws_b)
+        B.np_sparse_adagrad(active, astate, iota, grads, dd1["num_unique"], cap, cfg.lr, cfg.eps)   # the update, on the active buffer
+        B.np_intersect(dd1["unique"], dd1["num_unique"], cap, dd2["unique"], dd2["num_unique"], cap, out=isec, ws=ws_i)
+        main.wait_event(ev_prefetched)
+        B.np_sync_rows(active, isec["idx_a"], prefetch, isec["idx_b"], isec["num_common"], cap)
+        B.np_lookup_fwd(prefetch, iota, dd2["inverse"], b2["off"], b2["n"], cfg.mode, max_len, out_dtype,
+                        num_list=dd2["num_unique"], cap=cap, out=out)
+
+    def wall(fn) -> float:
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / reps
+
+    # B_{t-1}'s rows are in the active buffer (its own prefetch)
+    B.np_lookup_fwd(table, dd1["unique"], None, no_bags, 0, cfg.mode, max_len, out_dtype, num_list=dd1["num_unique"], cap=cap, out=out,
+                    rows_out=active)
+    seq_ms = wall(sequential)
+    pipe_ms = wall(pipelined)
+    return {"common_keys": common, "sync_ms": sum(sync_k.values()), "sync_kernels_ms": sync_k,
+            "row_copy_GBps": 2 * common * 4 * D / (sync_k.get("sync_rows", 1e9) * 1e-3) / 1e9,
+            "two_batch_sequential_ms": seq_ms, "two_batch_pipelined_ms": pipe_ms,
+            "what": "sequential = bwd(B1), adagrad on the table, fwd(B2) from the table, one stream; pipelined = prefetch of B2's rows "
+                    "on a second stream beside bwd(B1) + adagrad on the active row buffer, then np_intersect + np_sync_rows, then "
+                    "fwd(B2) from the prefetch buffer.  With the table in HBM the prefetch has no slower tier to hide: it is extra "
+                    "traffic on the one memory system, so the pipelined order is not expected to win here"}
+
+
+def frozen_window(args, cfg, B, torch, batches, stats, dbatch, dd, ws_d) -> dict:
+    """Frozen-window micro-batching (Section V): keys are deduplicated inside each micro-batch only, so the vectors crossing
+    the All2All inflate from U to sum(U_i).  Batch 0 split into N micro-batches of consecutive samples and by the key-centric sample clustering of Section V-C; every micro-batch goes through np_dedup."""
+    from paper_2604_06956_amd import clustering as C
+    b0 = batches[0]
+    keys_dev = dbatch[0]["keys"]
+    B.np_dedup(keys_dev, cfg.key_bits, out=dd, ws=ws_d)
+    torch.cuda.synchronize()
+    U = int(dd["num_unique"].item())
+    inverse = dd["inverse"][:b0.n].cpu().numpy()
+    counts = dd["counts"][:U].cpu().numpy()
+    table = {}
+
+    def sum_u(assign, N):
+        tot = 0
+        for m in range(N):
+            pos, _, _ = C.micro_batch_lookups(b0.bag_offsets, cfg.batch, cfg.features, assign, m)
+            if pos.size == 0:
+                continue
+            mk = keys_dev[torch.from_numpy(pos).to(keys_dev.device)].contiguous()
+            B.np_dedup(mk, cfg.key_bits, out=dd, ws=ws_d)
+            torch.cuda.synchronize()
+            tot += int(dd["num_unique"].item())
+        return tot
+
+    for N in (1, 2, 4, 8, 16, 32):
+        if cfg.batch < N:
+            continue
+        rec = {"consecutive": sum_u(C.consecutive_split(cfg.batch, N), N) / stats[0]["U"]}
+        if N > 1 and (N == 8 or not args.cluster_only_8):
+            t = time.perf_counter()
+            assign = C.cluster_samples(b0.keys, b0.bag_offsets, cfg.batch, N, inverse=inverse, counts=counts)
+            rec["clustering_host_s"] = time.perf_counter() - t
+            rec["clustered"] = sum_u(assign, N) / stats[0]["U"]
+        table[str(N)] = rec
+    table["what"] = "sum over micro-batches of their distinct-key counts / the whole batch's U (batch 0)"
+    return table
 
 
 def n_steps_lookups(dbatch, args) -> int:
     return sum(dbatch[(args.warmup + i) % 2]["n"] for i in range(args.steps))
 
 
-def cpu_baseline(cfg, batch, wl, div: int, table_dtype: str = "f32"):
-    """The CPU oracle, as it stands, on the first 1/div of the batch's bags: the five steps on a table that holds
-    only the rows the sample touches (keys renumbered in order, which changes no result of the path)."""
+def _oracle_leg(cfg_tuple, keys, off, max_len, table_seed, table_dtype, wl_module_name="paper_2604_06956_amd.workloads"):
+    """The five oracle steps on one slice of bags (its own little batch), timed; runs in the calling process."""
+    import importlib
+    wl = importlib.import_module(wl_module_name)
     from oracle import np_oracle as O
-    O.build()
-    nb = max(1, cfg.num_bags // div)
-    off = batch.bag_offsets[:nb + 1].astype(np.int32)
+    dim, mode, num_shards, shard_fn, lr, eps = cfg_tuple
+    nb = off.shape[0] - 1
     n = int(off[-1])
-    keys = batch.keys[:n]
     touched = np.unique(keys)
     local = np.searchsorted(touched, keys).astype(np.int64)
-    table = wl.table_init_rows(touched, cfg.dim, cfg.table_seed)
+    table = wl.table_init_rows(touched, dim, table_seed)
     if table_dtype == "bf16":
-        import torch
-        table = torch.from_numpy(table).bfloat16().view(torch.int16).numpy().view(np.uint16).copy()
+        table = O.f32_to_bf16_bits(table) if table.size < 1 << 16 else (
+            ((table.view(np.uint32) + 0x7FFF + ((table.view(np.uint32) >> 16) & 1)) >> 16).astype(np.uint16))
     elif table_dtype == "f16":
         table = table.astype(np.float16)
     state = np.zeros(touched.shape[0], np.float32)
     rng = np.random.default_rng(1)
-    seq = cfg.mode == wl.SEQ
+    seq = mode == 2
     if seq:
-        dY = (rng.standard_normal((nb, batch.max_len, cfg.dim)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+        dY = (rng.standard_normal((nb, max_len, dim)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
     else:
-        dY = rng.standard_normal((nb, cfg.dim)).astype(np.float32)
+        dY = rng.standard_normal((nb, dim)).astype(np.float32)
     t0 = time.perf_counter()
     unique, inverse, counts, occ_offsets, occ = O.dedup(local)
     t1 = time.perf_counter()
-    send_keys, splits, send_offsets, sfu, uts = O.route(touched[unique], cfg.num_shards, cfg.shard_fn)
+    send_keys, splits, send_offsets, sfu, uts = O.route(touched[unique], num_shards, shard_fn)
     l2s = O.compose(inverse, uts)
     t2 = time.perf_counter()
-    O.lookup_fwd(table, unique[sfu], l2s, off, cfg.mode, batch.max_len, O.BF16 if seq else O.F32)
+    O.lookup_fwd(table, unique[sfu], l2s, off, mode, max_len, O.BF16 if seq else O.F32)
     t3 = time.perf_counter()
-    grads, _ = O.lookup_bwd(dY, O.BF16 if seq else O.F32, cfg.dim, cfg.mode, batch.max_len, off, inverse, unique.shape[0], uts)
+    grads, _ = O.lookup_bwd(dY, O.BF16 if seq else O.F32, dim, mode, max_len, off, inverse, unique.shape[0], uts)
     t4 = time.perf_counter()
     if table_dtype == "bf16":
-        O.sparse_adagrad_bf16(table, state, unique[sfu], grads, cfg.lr, cfg.eps)
+        O.sparse_adagrad_bf16(table, state, unique[sfu], grads, lr, eps)
     elif table_dtype == "f16":
-        O.sparse_adagrad_f16(table.view(np.uint16), state, unique[sfu], grads, cfg.lr, cfg.eps)
+        O.sparse_adagrad_f16(table.view(np.uint16), state, unique[sfu], grads, lr, eps)
     else:
-        O.sparse_adagrad(table, state, unique[sfu], grads, cfg.lr, cfg.eps)
+        O.sparse_adagrad(table, state, unique[sfu], grads, lr, eps)
     t5 = time.perf_counter()
-    total = t5 - t0
-    return {"value": n / total, "unit": "lookups/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {nb} of {cfg.num_bags} bags of batch 0 ({n} lookups, {touched.shape[0]} distinct keys), all five "
-                      f"steps, table holding only the touched rows; single-threaded C, fp64 accumulation",
-            "seconds": total,
-            "seconds_per_call": {"dedup": t1 - t0, "route": t2 - t1, "fwd": t3 - t2, "bwd": t4 - t3, "adagrad": t5 - t4}}
+    return n, touched.shape[0], (t1 - t0, t2 - t1, t3 - t2, t4 - t3, t5 - t4)
+
+
+_FORK_STATE = {}
+
+
+def _oracle_worker(w: int):
+    st = _FORK_STATE
+    lo, hi = st["cuts"][w], st["cuts"][w + 1]
+    off = st["off"][lo:hi + 1]
+    keys = st["keys"][int(off[0]):int(off[-1])]
+    t = time.perf_counter()
+    n, u, per = _oracle_leg(st["cfg_tuple"], keys, (off - off[0]).astype(np.int32), st["max_len"], st["table_seed"], st["table_dtype"])
+    return n, u, per, time.perf_counter() - t
+
+
+def cpu_baseline(cfg, batch, wl, div: int, table_dtype: str = "f32"):
+    """The CPU oracle, as it stands, on (the first 1/div of) batch 0: all five steps on a table that holds only the rows the
+    sample touches (keys renumbered in order, which changes no result of the path).  Two legs: one thread over the whole
+    sample; and one worker process per core, each running the same five steps on its own contiguous share of the bags (the
+    oracle is single-threaded C, so this is how it uses the cores; per-share deduplication, as N workers would)."""
+    import multiprocessing as mp
+    from oracle import np_oracle as O
+    O.build()
+    nb = max(1, cfg.num_bags // max(div, 1))
+    off = batch.bag_offsets[:nb + 1].astype(np.int64)
+    n = int(off[-1])
+    keys = batch.keys[:n]
+    cfg_tuple = (cfg.dim, cfg.mode, cfg.num_shards, cfg.shard_fn, cfg.lr, cfg.eps)
+    host_cores = os.cpu_count() or 1
+    procs = max(1, min(host_cores, GPU_BOX_CPU_SHARE, nb))
+    # ---- all cores: fork the workers before anything else in this process holds threads or a GPU context
+    _FORK_STATE.update(cuts=[nb * w // procs for w in range(procs + 1)], off=off, keys=keys, cfg_tuple=cfg_tuple,
+                       max_len=batch.max_len, table_seed=cfg.table_seed, table_dtype=table_dtype)
+    t = time.perf_counter()
+    if procs > 1:
+        with mp.get_context("fork").Pool(procs) as pool:
+            res = pool.map(_oracle_worker, range(procs))
+    else:
+        res = [_oracle_worker(0)]
+    wall_all = time.perf_counter() - t
+    busy = max(r[3] for r in res)
+    # ---- one thread over the whole sample
+    t = time.perf_counter()
+    n1, u1, per1 = _oracle_leg(cfg_tuple, keys, off.astype(np.int32), batch.max_len, cfg.table_seed, table_dtype)
+    wall_one = time.perf_counter() - t
+    _FORK_STATE.clear()
+    total1 = sum(per1)
+    names = ("dedup", "route", "fwd", "bwd", "adagrad")
+    return {"value": n / busy, "unit": "lookups/s", "cores": procs, "host_cores": host_cores, "kind": "oracle",
+            "sample": f"first {nb} of {cfg.num_bags} bags of batch 0 ({n} lookups), all five steps, table holding only the touched "
+                      f"rows; {procs} worker processes (one per core, at most {GPU_BOX_CPU_SHARE} on a one-GPU box), each the "
+                      f"single-threaded C oracle (fp64 accumulation) on its contiguous share of the bags; value = lookups / the "
+                      f"slowest worker's time, inputs in memory",
+            "seconds": busy, "wall_seconds_with_process_start": wall_all,
+            "one_thread": {"value": n1 / total1, "unit": "lookups/s", "cores": 1, "seconds": total1, "distinct_keys": u1,
+                           "seconds_per_call": dict(zip(names, per1)), "wall_seconds_with_table_setup": wall_one}}
 
 
 if __name__ == "__main__":
