@@ -429,7 +429,7 @@ def extras(line, args, cfg, wl, B, torch, dev, batches, stats, dbatch, dd, rr, d
         side_stream.wait_event(ev_dedup)
         with torch.cuda.stream(side_stream):
             B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
-            B.np_lookup_bwd_prepare(dy_dtype_code, D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["num_unique"], ws_b)
+            B.np_lookup_bwd_prepare(dy_dtype_code, D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], ws_b)
             ev_route.record(side_stream)
         fwd_call(table, bt["keys"], None, bt["off"], n, cfg.mode, max_len, out_dtype, out=out)
         main_stream.wait_event(ev_route)
@@ -440,6 +440,23 @@ def extras(line, args, cfg, wl, B, torch, dev, batches, stats, dbatch, dd, rr, d
     split_ms = timed_loop(step_split, K)
     line["prepared_bwd_step"] = {"ms_per_step": split_ms, "lookups_per_s": rate(split_ms),
                                  "what": "np_lookup_bwd_prepare behind np_route on the second stream, np_lookup_bwd_prepared after the forward"}
+    # the two alternatives of the backward that np_tune_set switches on (same bits, see include/nestpipe.h)
+    tuned = {}
+    for knob, fn in (("bwd_row_index", step_split), ("bwd_row_index", step), ("bwd_singles_by_bag", step)):
+        old_v = B.np_tune_get(knob)
+        B.np_tune_set(knob, 1)
+        B.np_prof_enable(True)
+        ms = timed_loop(fn, K)
+        rec = B.np_prof_collect(65536)
+        B.np_prof_enable(False)
+        B.np_tune_set(knob, old_v)
+        per = {}
+        for name, t_ms in rec:
+            if name.startswith("bwd"):
+                per[name] = per.get(name, 0.0) + t_ms / (K + 2)
+        tuned[knob + ("/prepared_on_second_stream" if fn is step_split else "")] = {
+            "ms_per_step_with_events": ms, "bwd_kernels_ms": per, "bwd_ms": sum(per.values())}
+    line["backward_variants"] = tuned
 
     # ---- the headline step without event recording (what the events cost), and its spread over single steps
     line["ms_per_step_without_events"] = timed_loop(step, K, warm=0)
@@ -478,6 +495,27 @@ def extras(line, args, cfg, wl, B, torch, dev, batches, stats, dbatch, dd, rr, d
     torch.cuda.synchronize()
     line["stream_copy_GBps"] = 2 * words * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del src, dst
+
+    # ---- gather yardstick: random 256-byte row reads with the row kernels' access pattern, by working-set size (what L2,
+    # the last-level cache and HBM deliver to a gather on this GPU; the table itself is the source)
+    if not lowp_table and table.numel() >= 64 * 4096:
+        flat = table.view(-1)
+        rows_total = flat.numel() // 64
+        n_g = 32 << 20
+        sink = torch.empty((n_g // 64, 64), dtype=torch.float32, device=dev)
+        gy = {}
+        for label, rows in (("2MB_L2", 8192), ("128MB_last_level_cache", 1 << 19), ("1GB", 1 << 22), ("whole_table_HBM", rows_total)):
+            rows = min(rows, rows_total, (1 << 32) - 1)
+            B.np_util_gather_rate(flat, rows, n_g, 1, sink)
+            torch.cuda.synchronize()
+            e0.record()
+            for rep in range(3):
+                B.np_util_gather_rate(flat, rows, n_g, 2 + rep, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            gy[label] = {"working_set_bytes": rows * 256, "GBps": 3 * n_g * 256 / (e0.elapsed_time(e1) * 1e-3) / 1e9}
+        line["row_gather_GBps"] = gy
+        del sink
 
     if not lowp_table and not seq:
         line["dual_buffer"] = dual_buffer(args, cfg, B, torch, dev, dbatch, dd, dedup_buffers, table, state, out, grads, ws_d, ws_b,

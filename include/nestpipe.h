@@ -192,18 +192,19 @@ size_t np_lookup_bwd_workspace_bytes(int32_t num_bags, int32_t n, int32_t dim, i
  * np_lookup_bwd in two parts, for callers that want the part that does not need dY out of the way early (the dense
  * model runs between the forward and the backward; in that time the index work can already be done):
  *
- *   np_lookup_bwd_prepare   everything that depends on bag_offsets and occ_offsets alone (lookup -> bag map, first key
- *                           segment of every tile, the order in which tiles run); written into ws.
+ *   np_lookup_bwd_prepare   everything that depends on the index arrays alone: bag_offsets, occ_offsets, occ (lookup -> bag
+ *                           map, first key segment of every tile, the order in which tiles run, the upstream-gradient row
+ *                           of every sorted lookup); written into ws.
  *   np_lookup_bwd_prepared  the reduction itself; ws must be the buffer a np_lookup_bwd_prepare call with the same
- *                           dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets and d_num_unique has
+ *                           dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ and d_num_unique has
  *                           completed on (order the two through the stream or an event), untouched in between.
  *
  * np_lookup_bwd_prepare followed by np_lookup_bwd_prepared gives the bits of np_lookup_bwd.  Arguments, errors and the
  * workspace size are those of np_lookup_bwd.
  */
 int np_lookup_bwd_prepare(int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len, const int32_t* bag_offsets,
-                          int32_t num_bags, int32_t n, const int32_t* occ_offsets, const int32_t* d_num_unique, void* ws,
-                          size_t ws_bytes, void* stream);
+                          int32_t num_bags, int32_t n, const int32_t* occ_offsets, const int32_t* occ, const int32_t* d_num_unique,
+                          void* ws, size_t ws_bytes, void* stream);
 int np_lookup_bwd_prepared(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len,
                            const int32_t* bag_offsets, int32_t num_bags, int32_t n, const int32_t* occ_offsets,
                            const int32_t* occ, const int32_t* d_num_unique, int32_t cap, const int32_t* unique_to_send,
@@ -248,7 +249,7 @@ int np_sparse_adagrad_t(void* table, int32_t table_dtype, float* state, int64_t 
  * reduces (no gradient All2All in between): every finished gradient row is applied on the spot to
  * table[unique[u], :] with the row-wise Adagrad rule above and is never written to HBM (Section IV-B: gradients
  * are applied directly to the vectors of the active buffer).  Same sums, same order, same update arithmetic as
- * the two separate calls: the table and state come out bit-identical.  dim <= 256.
+ * the two separate calls: the table and state come out bit-identical.  Every dim the separate calls take.
  *
  *   unique [cap] in  np_dedup's distinct keys (pairwise distinct, so every row is updated exactly once)
  *   other arguments as in np_lookup_bwd / np_sparse_adagrad; workspace as np_lookup_bwd_workspace_bytes.
@@ -326,8 +327,43 @@ int np_util_table_count_changed_t(const void* table, int32_t table_dtype, int64_
 int np_util_check_batch(const int64_t* keys, int32_t n, int64_t num_rows, const int32_t* bag_offsets, int32_t num_bags,
                         unsigned long long* d_errors, void* stream);
 
+/*
+ * Tunables: thresholds that decide which of two code paths with IDENTICAL results a call takes; they change speed, never
+ * a bit of any output.  Process-wide, host functions, safe to call from any thread; a call reads them when it is
+ * enqueued (np_lookup_bwd_prepare and np_lookup_bwd_prepared of one batch must see the same values).
+ *
+ *   "emit_order_min_n"        np_dedup writes the inverse map in a cache-friendly tile order from this many lookups on
+ *                             (initially 4194304; smaller batches take fewer launches instead)
+ *   "bwd_order_min_dy_bytes"  np_lookup_bwd runs its tiles locality-ordered when the upstream gradient exceeds this many
+ *                             bytes (initially 268435456, the last-level cache of an MI355X)
+ *   "bwd_row_index"           1: the index part of np_lookup_bwd also resolves the upstream-gradient row of every sorted
+ *                             lookup, laid out block by block (one more launch, 4 to 8 bytes per lookup written and read
+ *                             again); the reduction then starts its row loads at once.  0 (initially): the reduction
+ *                             resolves the rows itself.  On an MI355X the reduction gets 6 % faster and the extra pass
+ *                             costs three times that, so it pays only where the index part runs ahead of time, out of
+ *                             the way (np_lookup_bwd_prepare while the dense model computes)
+ *   "bwd_singles_by_bag"      1: keys with a single lookup (their gradient row is a copy of one upstream row) are served
+ *                             bag by bag by a copy kernel, the reduction skips them (pooled modes, fp32 gradients).
+ *                             0 (initially).  Measured slower on an MI355X: the reduction drops from 2.0 to 1.4 ms on
+ *                             42 M lookups, the three extra passes take 0.8 ms
+ *
+ * np_tune_set: NP_OK, or NP_ERR_INVALID_ARG for an unknown name or a value outside the knob's range.  np_tune_get: the value, -1 for an
+ * unknown name.
+ */
+int np_tune_set(const char* name /* host */, int64_t value);
+int64_t np_tune_get(const char* name /* host */);
+
 /* Plain device copy of `bytes` (multiple of 16) with 16-byte loads and stores: the bandwidth yardstick. */
 int np_util_stream_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+/*
+ * The gather yardstick: n random reads of whole 256-byte rows (64 floats) from the first num_rows rows of `src`, with the
+ * access pattern of the row kernels (16 lanes x 16 bytes per row, eight rows in flight per lane group), summed in groups
+ * of 64 into out [n/64, 64] fp32.  Row i read = hash(i, seed) mod num_rows, so num_rows sets the working set: a few
+ * thousand rows stay in L2, half a million in the last-level cache, a whole table means HBM.  n a multiple of 64,
+ * num_rows < 2^32; src and out 16-byte aligned.  Timing it (HIP events) gives what a gather can reach on this GPU.
+ */
+int np_util_gather_rate(const float* src, int64_t num_rows, int64_t n, uint32_t seed, float* out, void* stream);
 
 /*
  * Per-kernel timing with HIP events on the caller's stream.  np_prof_enable(1) makes every kernel launch

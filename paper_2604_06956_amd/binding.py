@@ -60,7 +60,7 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.np_lookup_bwd_prepared.restype = ctypes.c_int
     L.np_lookup_bwd_prepared.argtypes = L.np_lookup_bwd.argtypes
     L.np_lookup_bwd_prepare.restype = ctypes.c_int
-    L.np_lookup_bwd_prepare.argtypes = [_i32, _i32, _i32, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]
+    L.np_lookup_bwd_prepare.argtypes = [_i32, _i32, _i32, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]
     L.np_lookup_bwd_workspace_bytes.restype = _sz
     L.np_lookup_bwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
     L.np_lookup_bwd_adagrad.restype = ctypes.c_int
@@ -92,8 +92,14 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.np_util_table_count_changed.argtypes = [_vp, _i64, _i32, _u64, _vp, _vp]
     L.np_util_check_batch.restype = ctypes.c_int
     L.np_util_check_batch.argtypes = [_vp, _i32, _i64, _vp, _i32, _vp, _vp]
+    L.np_util_gather_rate.restype = ctypes.c_int
+    L.np_util_gather_rate.argtypes = [_vp, _i64, _i64, ctypes.c_uint32, _vp, _vp]
     L.np_util_stream_copy.restype = ctypes.c_int
     L.np_util_stream_copy.argtypes = [_vp, _vp, _sz, _vp]
+    L.np_tune_set.restype = ctypes.c_int
+    L.np_tune_set.argtypes = [ctypes.c_char_p, _i64]
+    L.np_tune_get.restype = _i64
+    L.np_tune_get.argtypes = [ctypes.c_char_p]
     L.np_prof_enable.restype = ctypes.c_int
     L.np_prof_enable.argtypes = [ctypes.c_int]
     L.np_prof_only.restype = ctypes.c_int
@@ -289,11 +295,11 @@ def np_lookup_bwd(dY: torch.Tensor, dim: int, mode: int, max_len: int, bag_offse
 
 
 def np_lookup_bwd_prepare(dy_dtype: int, dim: int, mode: int, max_len: int, bag_offsets: torch.Tensor, n: int,
-                          occ_offsets: torch.Tensor, num_unique: torch.Tensor, ws: torch.Tensor) -> None:
+                          occ_offsets: torch.Tensor, occ: torch.Tensor, num_unique: torch.Tensor, ws: torch.Tensor) -> None:
     """The part of np_lookup_bwd that needs no dY, written into ``ws`` (hand the same ``ws`` to np_lookup_bwd_prepared)."""
     num_bags = bag_offsets.numel() - 1
     rc = lib.np_lookup_bwd_prepare(dy_dtype, dim, mode, max_len, _ptr(bag_offsets, torch.int32), num_bags, n,
-                                   _ptr(occ_offsets, torch.int32), _ptr(num_unique, torch.int32), _ptr(ws),
+                                   _ptr(occ_offsets, torch.int32), _ptr(occ, torch.int32), _ptr(num_unique, torch.int32), _ptr(ws),
                                    ws.numel() * ws.element_size(), _stream())
     _chk("np_lookup_bwd_prepare", rc)
 
@@ -428,6 +434,19 @@ def np_util_check_batch(keys: Optional[torch.Tensor], num_rows: int, bag_offsets
 def np_util_stream_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
     nbytes = src.numel() * src.element_size()
     _chk("np_util_stream_copy", lib.np_util_stream_copy(_ptr(dst), _ptr(src), nbytes, _stream()))
+
+
+def np_tune_set(name: str, value: int) -> None:
+    _chk("np_tune_set", lib.np_tune_set(name.encode(), int(value)))
+
+
+def np_tune_get(name: str) -> int:
+    return int(lib.np_tune_get(name.encode()))
+
+
+def np_util_gather_rate(src: torch.Tensor, num_rows: int, n: int, seed: int, out: torch.Tensor) -> None:
+    """n hashed reads of 256-byte rows from the first num_rows rows of ``src`` (fp32, row width 64), summed 64 at a time into out."""
+    _chk("np_util_gather_rate", lib.np_util_gather_rate(_ptr(src, torch.float32), num_rows, n, seed, _ptr(out, torch.float32), _stream()))
 
 
 def np_prof_enable(on: bool) -> None:

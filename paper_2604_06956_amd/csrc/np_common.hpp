@@ -15,6 +15,10 @@ constexpr int kNumXcd = 8;  // MI355X: 8 accelerator dies, workgroup i is dispat
 
 // ---------------------------------------------------------------- host side -----------------------
 
+// Thresholds that choose between two code paths with identical results (np_tune_set / np_tune_get at the C boundary).
+enum Tunable { kTuneEmitOrderMinN = 0, kTuneBwdOrderMinDyBytes = 1, kTuneBwdRowIndex = 2, kTuneBwdSinglesByBag = 3, kTuneCount = 4 };
+int64_t tune_get(Tunable which);
+
 void prof_begin(const char* name, hipStream_t stream);
 void prof_end(hipStream_t stream);
 
@@ -105,6 +109,9 @@ __device__ __forceinline__ uint32_t fastmod64(uint64_t x, const FastMod& f) {
 // Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS traffic, not for global loads
 // still in flight (a plain __syncthreads drains those too, which serialises every prefetch behind the barrier).
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Keeps the compiler from moving memory accesses across this point; emits no instruction.
+__device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
 
 __device__ __forceinline__ int wave_incl_scan(int v) {
 #pragma unroll

@@ -23,6 +23,11 @@
 //                  following tiles in tile order: one group per tile for short chains, one block per listed
 //                  long chain (bwd_main lists them) with a fixed split of the chain over the block.
 //
+// Two alternatives sit behind np_tune_set, off unless asked for (both measured slower in one call on an MI355X, both give
+// the same bits): "bwd_row_index" (bwd_rows resolves the upstream-gradient row of every sorted position ahead of the
+// reduction, which then requests its first rows before it knows its tile) and "bwd_singles_by_bag" (keys with one lookup
+// are copied bag by bag, bwd_main skips them).
+//
 // The order of every floating-point addition is a function of occ_offsets alone: no atomics, no dependence
 // on scheduling, so two runs give the same bits.  A hot key with millions of lookups costs the same per
 // lookup as a cold one.
@@ -47,7 +52,6 @@ constexpr int kOrderBuckets = 1024;   // relative positions inside a long segmen
 #define NP_ORDER_INTERLEAVE 0  // measured on 42 M lookups, dim 64: the two kinds of tiles interleaved 2.03 ms, one after the other 1.97 ms
 #endif
 constexpr int kOrderMinCount = NP_ORDER_MIN_COUNT;       // segments at least this long take part in the locality order
-constexpr size_t kOrderMinDyBytes = size_t(256) << 20;  // the Infinity Cache: a dY that fits it is re-read from there anyway
 
 // One entry per 64 consecutive lookups: where bags start inside the block and which bag the block begins in.
 // 16 bytes per 64 lookups (n/4 bytes in all), so the random reads of bwd_main mostly stay in L2 / Infinity Cache.
@@ -85,10 +89,8 @@ __device__ __forceinline__ void bagmap_entry(int w, const int32_t* __restrict__ 
     map[w] = e;
 }
 
-// Bag of lookup j and the first lookup of that bag.
-__device__ __forceinline__ void bag_of_lookup(const BagMapEntry* __restrict__ map, const int32_t* __restrict__ bag_offsets, int j,
-                                              int& bag, int& start) {
-    const BagMapEntry e = map[j >> 6];
+// Bag of lookup j and the first lookup of that bag, from the map entry of j's block of 64 lookups.
+__device__ __forceinline__ void bag_from_entry(const BagMapEntry& e, const int32_t* __restrict__ bag_offsets, int j, int& bag, int& start) {
     const int k = j & 63;
     const uint64_t m = e.starts & ((2ull << k) - 1ull);  // starts at or before j (bit 0 is never set)
     bag = (e.bag0 & 0x7FFFFFFF) + __popcll(m);
@@ -99,6 +101,11 @@ __device__ __forceinline__ void bag_of_lookup(const BagMapEntry* __restrict__ ma
         bag = b;
         start = bag_offsets[b];
     }
+}
+
+__device__ __forceinline__ void bag_of_lookup(const BagMapEntry* __restrict__ map, const int32_t* __restrict__ bag_offsets, int j,
+                                              int& bag, int& start) {
+    bag_from_entry(map[j >> 6], bag_offsets, j, bag, start);
 }
 
 __device__ __forceinline__ void tile_first_segment(int t, const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ d_num_unique,
@@ -124,6 +131,78 @@ bwd_prepare_kernel(const int32_t* __restrict__ bag_offsets, int num_bags, int n,
         bagmap_entry(blockIdx.x * 256 + threadIdx.x, bag_offsets, num_bags, n, map);
     else
         tile_first_segment((blockIdx.x - map_blocks) * 256 + threadIdx.x, occ_offsets, d_num_unique, n, num_tiles, tile_seg0);
+}
+
+// Block -> tile of bwd_main: die x (blocks x, x + 8, ...) first runs its contiguous share of the locality-ordered tiles,
+// then every 8th of the remaining ones; without an order the tiles run in index order.  -1: the block has no tile.
+__device__ __forceinline__ int bwd_tile_of_block(int b, int num_tiles, const int32_t* __restrict__ order,
+                                                 const int32_t* __restrict__ order_offsets) {
+    const int nh = order ? order_offsets[kOrderBuckets] : 0;
+    const int nc = num_tiles - nh;
+    const int hc = (nh + kNumXcd - 1) / kNumXcd;
+    const int x = b % kNumXcd, sl = b / kNumXcd;
+    int k;
+    if (!NP_ORDER_XCD_SPLIT) {
+        k = b;
+        if (k >= num_tiles) return -1;
+    } else if (sl < hc) {
+        k = x * hc + sl;
+        if (k >= nh) return -1;
+    } else {
+        const int kc = (sl - hc) * kNumXcd + x;
+        if (kc >= nc) return -1;
+        k = nh + kc;
+    }
+    return order ? order[k] : k;
+}
+
+// Row index (tunable "bwd_row_index"): the upstream-gradient row (and the mean-pooling weight) of every sorted position,
+// resolved once and laid out in the order in which bwd_main's blocks run: block b finds the rows of its 256 positions at
+// srow[256 b ..] with one coalesced load that depends on nothing, and can request its first rows while it is still
+// finding out which tile it has and where the segments lie.  -1 marks a position past the end.  Every thread resolves
+// kRowsSlots positions at once (all loads unconditional, from clamped positions, so that the chains overlap).
+constexpr int kRowsSlots = 8;
+
+template <bool MEAN>
+__global__ void __launch_bounds__(256)
+bwd_rows_kernel(const int32_t* __restrict__ occ, int n, const BagMapEntry* __restrict__ map, const int32_t* __restrict__ bag_offsets,
+                int seq, int max_len, int num_tiles, const int32_t* __restrict__ order, const int32_t* __restrict__ order_offsets,
+                const int32_t* __restrict__ tile_seg0, int num_slots, int32_t* __restrict__ srow, float* __restrict__ sweight,
+                int2* __restrict__ slot_info) {
+    const int t = threadIdx.x;
+    int tile[kRowsSlots], j[kRowsSlots];
+    bool ok[kRowsSlots];
+    // lane q of every wave maps slot q (block-uniform code, one slot after the other, would be eight dependent scalar
+    // loads in a row), then the wave shares the eight tiles.  The kernel's time (0.36 ms for 42 M positions) is that of
+    // its 42 M reads of 16 bytes scattered over the 10 MB bag map: the rate at which L2 misses of single lines are served.
+    int my_tile = -1;
+    {
+        const int q = __lane_id() % kRowsSlots;
+        const int s = blockIdx.x * kRowsSlots + q;
+        if (s < num_slots) my_tile = bwd_tile_of_block(s, num_tiles, order, order_offsets);
+    }
+#pragma unroll
+    for (int q = 0; q < kRowsSlots; ++q) tile[q] = __shfl(my_tile, q, kWave);
+#pragma unroll
+    for (int q = 0; q < kRowsSlots; ++q) {
+        const int64_t i = static_cast<int64_t>(tile[q]) * kBwdTile + t;
+        ok[q] = tile[q] >= 0 && i < n;
+        j[q] = occ[ok[q] ? i : 0];
+    }
+    BagMapEntry e[kRowsSlots];
+#pragma unroll
+    for (int q = 0; q < kRowsSlots; ++q) e[q] = map[j[q] >> 6];
+#pragma unroll
+    for (int q = 0; q < kRowsSlots; ++q) {
+        const int s = blockIdx.x * kRowsSlots + q;
+        if (s >= num_slots) continue;
+        int bag, start;
+        bag_from_entry(e[q], bag_offsets, j[q], bag, start);
+        const int64_t at = static_cast<int64_t>(s) * kBwdTile + t;
+        srow[at] = ok[q] ? (seq ? bag * max_len + (j[q] - start) : bag) : -1;
+        if (MEAN) sweight[at] = ok[q] ? 1.f / static_cast<float>(bag_offsets[bag + 1] - start) : 0.f;
+        if (t == 0) slot_info[s] = make_int2(tile[q], tile[q] >= 0 ? tile_seg0[tile[q]] : 0);  // the block's tile and its first segment
+    }
 }
 
 // Partition policy that sorts tiles by the bucket of their relative position inside a long segment; tiles that are
@@ -183,6 +262,74 @@ __device__ __forceinline__ void load_dy_pair(const uint16_t* dY, int row, int di
 }
 __device__ __forceinline__ void load_dy_pair(const float*, int, int, int, float4&, float4&) {}  // never selected
 
+// Variant (tunable "bwd_singles_by_bag", pooled modes, fp32 upstream gradients, plain sink): a key with ONE lookup needs no
+// reduction, its gradient row is a copy of its bag's upstream row.  Such keys are served bag by bag, each upstream row
+// read once and in order, instead of being gathered one row per key in key order; bwd_main then skips them.
+//   bwd_single_fill   sdst[j] = -1 for every lookup
+//   bwd_single_mark   for every key with one lookup j: sdst[j] = the row of grads it owns
+//   bwd_single_copy   one LPR-lane group per bag: reads the bag's slice of sdst, and if any entry is set the bag's upstream
+//                     row once; writes it (0 + x, or w * x for mean pooling: the operations of the key-major walk, so the
+//                     bits are the same) to every set entry's row
+__global__ void __launch_bounds__(256)
+bwd_single_fill_kernel(int32_t* __restrict__ sdst, int n) {
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n; i += static_cast<int64_t>(gridDim.x) * 256) sdst[i] = -1;
+}
+
+__global__ void __launch_bounds__(256)
+bwd_single_mark_kernel(const int32_t* __restrict__ occ_offsets, const int32_t* __restrict__ occ, const int32_t* __restrict__ d_num_unique,
+                       int ucap, const int32_t* __restrict__ unique_to_send, int32_t* __restrict__ sdst) {
+    const int U = device_count(d_num_unique, ucap);
+    for (int64_t u = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; u < U; u += static_cast<int64_t>(gridDim.x) * 256) {
+        const int a = occ_offsets[u];
+        if (occ_offsets[u + 1] - a == 1) sdst[occ[a]] = unique_to_send ? unique_to_send[u] : static_cast<int32_t>(u);
+    }
+}
+
+template <int LPR, int NV, bool MEAN>
+__global__ void __launch_bounds__(256)
+bwd_single_copy_kernel(const float* __restrict__ dY, int dim, const int32_t* __restrict__ bag_offsets, int num_bags,
+                       const int32_t* __restrict__ sdst, float* __restrict__ grads) {
+    constexpr int GPB = 256 / LPR;
+    const int r = threadIdx.x % LPR;
+    const int64_t b = static_cast<int64_t>(blockIdx.x) * GPB + threadIdx.x / LPR;
+    if (b >= num_bags) return;  // whole groups leave together
+    const int lo = bag_offsets[b], hi = bag_offsets[b + 1];
+    const int words = dim / 4;
+    const int gl = __lane_id() & ~(LPR - 1);
+    const uint64_t gmask = (LPR == 64 ? ~0ull : ((1ull << (LPR & 63)) - 1ull)) << gl;
+    float w = 1.f;
+    if (MEAN && hi > lo) w = 1.f / static_cast<float>(hi - lo);
+    bool have = false;
+    float4 x[NV];
+    for (int base = lo; base < hi; base += LPR) {
+        const int j = base + r;
+        const int mine = j < hi ? load_stream(sdst + j) : -1;
+        uint64_t set = __ballot(mine >= 0) & gmask;
+        if (set && !have) {  // uniform inside the group
+            have = true;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int wv = r + v * LPR;
+                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (wv < words) t = load_dy(dY, static_cast<int>(b), dim, wv);
+                // the first (and only) step of the key-major running sum
+                if (MEAN) x[v] = make_float4(fmaf(w, t.x, 0.f), fmaf(w, t.y, 0.f), fmaf(w, t.z, 0.f), fmaf(w, t.w, 0.f));
+                else x[v] = make_float4(0.f + t.x, 0.f + t.y, 0.f + t.z, 0.f + t.w);
+            }
+        }
+        while (set) {
+            const int lane = __builtin_ctzll(set);
+            set &= set - 1;
+            const int dst = __shfl(mine, lane, kWave);
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int wv = r + v * LPR;
+                if (wv < words) store_stream(reinterpret_cast<float4*>(grads + static_cast<size_t>(dst) * dim) + wv, x[v]);
+            }
+        }
+    }
+}
+
 // Where a finished gradient row goes.  Plain (FUSED == 0): grads[dst, :].  Fused (np_lookup_bwd_adagrad): the row is
 // consumed on the spot by the row-wise Adagrad step on table[keys[dst], :] and never reaches HBM; the arithmetic is
 // the one of np_sparse_adagrad (same butterfly over the LPR lanes of a row, same store rounding), so both routes
@@ -201,21 +348,34 @@ struct RowSink {
     float lr, eps, inv_dim;
 };
 
-// Called by all LPR lanes that hold a row (lane r holds float4 word r; NV == 1 on the fused route).
-template <int LPR, int FUSED>
-__device__ __forceinline__ void sink_row(const RowSink& sk, int dst, int dim, int r, int words, const float4& g) {
+// Called by all LPR lanes that hold a row: lane r holds the float4 words r, r + LPR, ... in g[0 .. NV-1].  The fused
+// arithmetic is that of np_sparse_adagrad's kernel, operation by operation (squares summed over the lane's words in
+// ascending v, then the butterfly over the LPR lanes), so both routes give the same bits.
+template <int LPR, int NV, int FUSED>
+__device__ __forceinline__ void sink_row(const RowSink& sk, int dst, int dim, int r, int words, const float4 (&g)[NV]) {
     if (FUSED == kSinkGrads) {
-        if (r < words) store_stream(reinterpret_cast<float4*>(sk.grads + static_cast<size_t>(dst) * dim) + r, g);
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int wv = r + v * LPR;
+            if (wv < words) store_stream(reinterpret_cast<float4*>(sk.grads + static_cast<size_t>(dst) * dim) + wv, g[v]);
+        }
         return;
     }
     using TabT = typename SinkTable<FUSED>::type;
     const int64_t key = sk.keys[dst];
     TabT* wrow = static_cast<TabT*>(sk.table) + static_cast<size_t>(key) * dim;
-    float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 w[NV];
     float ss = 0.f;
-    if (r < words) {
-        w = load_word(wrow, r);
-        ss += sumsq4(g);
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int wv = r + v * LPR;
+        w[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 gv = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (wv < words) {
+            w[v] = load_word(wrow, wv);
+            gv = g[v];
+        }
+        ss += sumsq4(gv);
     }
     const float s_old = sk.state[key];
 #pragma unroll
@@ -223,9 +383,13 @@ __device__ __forceinline__ void sink_row(const RowSink& sk, int dst, int dim, in
     const float G = adagrad_state(s_old, ss, sk.inv_dim);
     const float denom = sqrtf(G) + sk.eps;
     if (r == 0) sk.state[key] = G;
-    if (r < words) {
-        adagrad_step4(w, g, sk.lr, denom);
-        store_word_stream(wrow, r, w);
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int wv = r + v * LPR;
+        if (wv < words) {
+            adagrad_step4(w[v], g[v], sk.lr, denom);
+            store_word_stream(wrow, wv, w[v]);
+        }
     }
 }
 
@@ -244,7 +408,8 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                 const int32_t* __restrict__ unique_to_send, const BagMapEntry* __restrict__ bagmap,
                 const int32_t* __restrict__ tile_seg0, const int32_t* __restrict__ order, const int32_t* __restrict__ order_offsets,
                 int num_tiles, int ucap, RowSink sink, float* __restrict__ tile_left, float* __restrict__ tile_right,
-                int32_t* __restrict__ tile_rseg) {
+                int32_t* __restrict__ tile_rseg, const int32_t* __restrict__ srow, const float* __restrict__ sweight,
+                const int2* __restrict__ slot_info, int skip_singles) {
     static_assert(!PAIR || (NV == 2 && FUSED == kSinkGrads), "the pair layout is two words per lane, plain sink");
     constexpr int GPB = 256 / LPR;
     constexpr int ROWW = LPR * NV;  // float4 words per (padded) row
@@ -255,78 +420,78 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     __shared__ int l_exists[GPB], l_closed[GPB], l_dst[GPB], r_exists[GPB];
 
     const int t = threadIdx.x;
-    // block -> tile: die x (blocks x, x+8, ...) first runs its contiguous share of the locality-ordered tiles, then
-    // every 8th of the remaining ones
-    int tile;
-    {
-        const int nh = order ? order_offsets[kOrderBuckets] : 0;  // no order given: tiles run in index order
-        const int nc = num_tiles - nh;
-        const int hc = (nh + kNumXcd - 1) / kNumXcd;
-        const int x = blockIdx.x % kNumXcd, sl = blockIdx.x / kNumXcd;
-        int k;
-        if (!NP_ORDER_XCD_SPLIT) {
-            k = blockIdx.x;
-            if (k >= num_tiles) return;
-        } else if (NP_ORDER_INTERLEAVE) {
-            // variant: the die's hc locality-ordered slots spread evenly between its cc other slots, so that tiles whose rows
-            // come from the last-level cache and tiles whose rows come from HBM are in flight together.  Slower than running
-            // them one kind after the other: the stream of once-read rows pushes the shared bands out of the caches.
-            const int cc = (nc + kNumXcd - 1) / kNumXcd;
-            const int T = hc + cc;
-            if (sl >= T) return;
-            const int h0 = static_cast<int>(static_cast<int64_t>(sl) * hc / T), h1 = static_cast<int>(static_cast<int64_t>(sl + 1) * hc / T);
-            if (h1 > h0) {
-                k = x * hc + h0;
-                if (k >= nh) return;
-            } else {
-                const int kc = (sl - h0) * kNumXcd + x;
-                if (kc >= nc) return;
-                k = nh + kc;
-            }
-        } else if (sl < hc) {
-            k = x * hc + sl;
-            if (k >= nh) return;
-        } else {
-            const int kc = (sl - hc) * kNumXcd + x;
-            if (kc >= nc) return;
-            k = nh + kc;
-        }
-        tile = order ? order[k] : k;
+    const int words = dim / 4;
+    const int g = t / LPR, r = t % LPR;
+    const int wv_id = t / kWave;
+    // With the row index (srow, laid out block by block) the rows of this block's positions are known before the block
+    // even knows its tile: the first batch of row loads goes out at once and is in flight while the tile, its segments
+    // and the destinations are being found.
+    const bool indexed = srow != nullptr;
+    int sr = -1;
+    float w = 1.f;
+    int tile, u0;
+    if (indexed) {
+        sr = load_stream(srow + static_cast<int64_t>(blockIdx.x) * kBwdTile + t);
+        if (MEAN) w = load_stream(sweight + static_cast<int64_t>(blockIdx.x) * kBwdTile + t);
+        const int2 info = slot_info[blockIdx.x];
+        tile = info.x;
+        u0 = info.y;
+    } else {
+        tile = bwd_tile_of_block(blockIdx.x, num_tiles, order, order_offsets);
+        u0 = tile >= 0 ? tile_seg0[tile] : 0;
     }
+    if (tile < 0) return;  // uniform
     const int tile_start = tile * kBwdTile;
     const int i = tile_start + t;
     const bool valid = i < n;
     const int U = device_count(d_num_unique, ucap);  // ucap = min(n, cap): rows of grads / entries of unique_to_send
-    int u0 = tile_seg0[tile];
     if (u0 >= U) u0 = U > 0 ? U - 1 : 0;  // only with a count above the caller's bound (a broken precondition): stay inside the lists
-    const int words = dim / 4;
-    const int g = t / LPR, r = t % LPR;
-    const int wv_id = t / kWave;
-
-    // loads that depend on nothing but the tile go out first
-    const int j = valid ? load_stream(occ + i) : 0;
+    // The segment boundaries are requested BEFORE the rows: loads come back in the order they were issued, so what is
+    // needed first has to be asked for first (unconditional, from a clamped index: occ_offsets[U] exists).
     const int cand = u0 + 1 + t;
-    const int rel = cand <= U ? occ_offsets[cand] - tile_start : INT32_MAX;  // >= 1
+    const int rel_raw = occ_offsets[cand <= U ? cand : U] - tile_start;
     const int seg0_start = occ_offsets[u0];
+    const int j = (valid && !indexed) ? load_stream(occ + i) : 0;
+    float4 x[kBwdUnroll][NV];
+    // rows of positions k0 .. k0 + kBwdUnroll - 1 of the strip; a position without a row (sr < 0) or past `limit` loads nothing
+    auto load_batch = [&](int k0, int limit) {
+#pragma unroll
+        for (int q = 0; q < kBwdUnroll; ++q) {
+            const int srk = group_bcast<LPR>(sr, (k0 + q) & (LPR - 1));
+            const bool on = k0 + q < limit && srk >= 0;
+            if constexpr (PAIR) {
+                x[q][0] = x[q][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (on && 2 * r < words) load_dy_pair(dY, srk, dim, r, x[q][0], x[q][1]);  // words is even here
+            } else {
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const int wv = r + v * LPR;
+                    x[q][v] = (on && wv < words) ? load_dy(dY, srk, dim, wv) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+        }
+    };
+    const bool early = indexed && !skip_singles;  // (the single-lookup variant decides later which rows it does not want)
+    if (early) load_batch(0, LPR);
+    const int rel = cand <= U ? rel_raw : INT32_MAX;  // >= 1
+    // (the three barriers of this prologue order LDS traffic only: lds_barrier leaves the row loads in flight)
     headmark[t] = 0;
     if (t == 0) headmark[kBwdTile] = 0;
-    __syncthreads();
+    lds_barrier();
     if (rel <= kBwdTile) headmark[rel] = 1;
-    int sr = 0;
-    float w = 1.f;
-    if (valid) {
+    if (!indexed && valid) {
         int bag, start;
         bag_of_lookup(bagmap, bag_offsets, j, bag, start);
         sr = seq ? bag * max_len + (j - start) : bag;
         if (MEAN) w = 1.f / static_cast<float>(bag_offsets[bag + 1] - start);
     }
-    __syncthreads();
+    lds_barrier();
     // segment of every position: heads strictly after the tile start, counted with one ballot per wave
     const int flag = t > 0 ? headmark[t] : 0;
     const int is_tail = headmark[t + 1];
     const uint64_t fmask = __ballot(flag);
     if (__lane_id() == 0) wave_heads[wv_id] = __popcll(fmask);
-    __syncthreads();
+    lds_barrier();
     int seg = u0 + __popcll(fmask & lanemask_lt()) + flag;
 #pragma unroll
     for (int ww = 0; ww < 3; ++ww)
@@ -345,6 +510,12 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
         tile_rseg[tile] = code;
     }
 
+    if (skip_singles && valid && is_tail && (t == 0 ? seg0_start == tile_start : flag != 0)) {
+        // a key with one lookup, served by the bag-major copy: no row to load here (sr < 0), nothing to store (-2: the
+        // position closes nothing and leaves nothing open)
+        sr = -1;
+        dst = -2;
+    }
     // ---- each group walks its strip of LPR positions ---------------------------------------------------
     // Position k > 0 starts a segment exactly when position k - 1 ends one, so the walk needs the end marks
     // (dst >= 0) and, for position 0 alone, whether the strip begins inside a segment that started earlier.
@@ -359,22 +530,7 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     bool le = false, lc = false, re = false;
     int ld = -1, dlast = 0;
     for (int k0 = 0; k0 < cnt; k0 += kBwdUnroll) {
-        float4 x[kBwdUnroll][NV];
-#pragma unroll
-        for (int q = 0; q < kBwdUnroll; ++q) {
-            const bool on = k0 + q < cnt;
-            const int srk = group_bcast<LPR>(sr, (k0 + q) & (LPR - 1));
-            if constexpr (PAIR) {
-                x[q][0] = x[q][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (on && 2 * r < words) load_dy_pair(dY, srk, dim, r, x[q][0], x[q][1]);  // words is even here
-            } else {
-#pragma unroll
-                for (int v = 0; v < NV; ++v) {
-                    const int wv = r + v * LPR;
-                    x[q][v] = (on && wv < words) ? load_dy(dY, srk, dim, wv) : make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-            }
-        }
+        if (!(early && k0 == 0)) load_batch(k0, cnt);
 #pragma unroll
         for (int q = 0; q < kBwdUnroll; ++q) {
             const int k = k0 + q;
@@ -395,17 +551,17 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                         acc[v].w += x[q][v].w;
                     }
                 }
-                dlast = dk;
+                dlast = dk == -2 ? 0 : dk;  // a skipped single-lookup key closes nothing and leaves nothing open
                 if (dk >= 0) {  // a segment ends here
                     if (!first_open) {
-                        if (FUSED) {
-                            sink_row<LPR, FUSED>(sink, dk, dim, r, words, acc[0]);
-                        } else {
+                        if constexpr (PAIR) {
 #pragma unroll
                             for (int v = 0; v < NV; ++v) {
                                 const int wv = word_of<LPR, PAIR>(r, v);
                                 if (wv < words) store_stream(reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dk) * dim) + wv, acc[v]);
                             }
+                        } else {
+                            sink_row<LPR, NV, FUSED>(sink, dk, dim, r, words, acc);
                         }
                     } else {
 #pragma unroll
@@ -441,42 +597,53 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     }
     __syncthreads();
 
-    // ---- combine the cut sums across the groups, in strip order; thread c owns word c of the row ----
-    if (t < ROWW) {
-        float4 carry = make_float4(0.f, 0.f, 0.f, 0.f);
+    // ---- combine the cut sums across the groups, in strip order; thread c < LPR owns words c, c + LPR, ... of the row ----
+    if (t < LPR) {
+        float4 carry[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) carry[v] = make_float4(0.f, 0.f, 0.f, 0.f);
         bool open = false, started_here = false;
         for (int gg = 0; gg < GPB; ++gg) {
             if (l_exists[gg]) {
-                const float4 p = lpart[gg * ROWW + t];
-                if (open) {
-                    carry.x += p.x;
-                    carry.y += p.y;
-                    carry.z += p.z;
-                    carry.w += p.w;
-                } else {
-                    carry = p;
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const float4 p = lpart[gg * ROWW + t + v * LPR];
+                    if (open) {
+                        carry[v].x += p.x;
+                        carry[v].y += p.y;
+                        carry[v].z += p.z;
+                        carry[v].w += p.w;
+                    } else {
+                        carry[v] = p;
+                    }
+                }
+                if (!open) {
                     started_here = false;
                     open = true;
                 }
                 if (l_closed[gg]) {
                     if (started_here) {
-                        if (FUSED) sink_row<LPR, FUSED>(sink, l_dst[gg], dim, t, words, carry);  // ROWW == LPR here
-                        else if (t < words) store_stream(reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(l_dst[gg]) * dim) + t, carry);
-                    } else if (t < words) {
-                        reinterpret_cast<float4*>(tile_left + static_cast<size_t>(tile) * dim)[t] = carry;
+                        sink_row<LPR, NV, FUSED>(sink, l_dst[gg], dim, t, words, carry);
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < NV; ++v)
+                            if (t + v * LPR < words) reinterpret_cast<float4*>(tile_left + static_cast<size_t>(tile) * dim)[t + v * LPR] = carry[v];
                     }
                     open = false;
                 }
             }
             if (r_exists[gg]) {
-                carry = rpart[gg * ROWW + t];
+#pragma unroll
+                for (int v = 0; v < NV; ++v) carry[v] = rpart[gg * ROWW + t + v * LPR];
                 open = true;
                 started_here = true;
             }
         }
-        if (open && t < words) {
-            if (started_here) reinterpret_cast<float4*>(tile_right + static_cast<size_t>(tile) * dim)[t] = carry;
-            else reinterpret_cast<float4*>(tile_left + static_cast<size_t>(tile) * dim)[t] = carry;
+        if (open) {
+            float* side = started_here ? tile_right : tile_left;
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+                if (t + v * LPR < words) reinterpret_cast<float4*>(side + static_cast<size_t>(tile) * dim)[t + v * LPR] = carry[v];
         }
     }
 }
@@ -523,15 +690,7 @@ __device__ __forceinline__ void fixup_short_part(int first_block_tile, int dim, 
         }
     }
     const int dst = unique_to_send ? unique_to_send[seg] : seg;
-    if (FUSED) {
-        sink_row<LPR, FUSED>(sink, dst, dim, r, words, acc[0]);
-    } else {
-#pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const int wv = r + v * LPR;
-            if (wv < words) store_stream(reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dst) * dim) + wv, acc[v]);
-        }
-    }
+    sink_row<LPR, NV, FUSED>(sink, dst, dim, r, words, acc);
 }
 
 // One launch for both kinds of chain: the last short_blocks blocks take one tile per LPR-lane group (chains of up to
@@ -618,21 +777,27 @@ bwd_fixup_kernel(int dim, int num_tiles, int short_blocks, const int32_t* __rest
         for (int v = 0; v < NV; ++v) part[g * ROWW + r + v * LPR] = acc[v];
         __syncthreads();
         const int t = threadIdx.x;
-        if (t < ROWW) {  // the first ROWW threads hold one word of the row each (words past the row are zeros)
-            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (t < words) s = reinterpret_cast<const float4*>(tile_right + static_cast<size_t>(tile) * dim)[t];
+        if (t < LPR) {  // the first LPR threads hold NV words of the row each (words past the row are zeros)
+            float4 sum[NV];
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                sum[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (t + v * LPR < words) sum[v] = reinterpret_cast<const float4*>(tile_right + static_cast<size_t>(tile) * dim)[t + v * LPR];
+            }
             for (int gg = 0; gg < GPB; ++gg) {
                 if (gg * per < count) {
-                    const float4 q = part[gg * ROWW + t];
-                    s.x += q.x;
-                    s.y += q.y;
-                    s.z += q.z;
-                    s.w += q.w;
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) {
+                        const float4 q = part[gg * ROWW + t + v * LPR];
+                        sum[v].x += q.x;
+                        sum[v].y += q.y;
+                        sum[v].z += q.z;
+                        sum[v].w += q.w;
+                    }
                 }
             }
             const int dst = unique_to_send ? unique_to_send[seg] : seg;
-            if (FUSED) sink_row<LPR, FUSED>(sink, dst, dim, t, words, s);
-            else if (t < words) store_stream(reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dst) * dim) + t, s);
+            sink_row<LPR, NV, FUSED>(sink, dst, dim, t, words, sum);
         }
       }
     }
@@ -643,7 +808,10 @@ struct BwdWs {
     int num_tiles;
 };
 
-inline BwdWs bwd_ws_layout(int32_t n, int32_t dim) {
+// Blocks of bwd_main: one per tile, plus room for the dies' shares of the two kinds of tiles not being whole multiples.
+inline size_t bwd_num_slots(int num_tiles) { return static_cast<size_t>((num_tiles + 2 * kNumXcd + kNumXcd - 1) / kNumXcd * kNumXcd); }
+
+inline BwdWs bwd_ws_layout(int32_t n, int32_t dim, int32_t mode = NP_POOL_MEAN) {
     BwdWs w;
     w.num_tiles = (n + kBwdTile - 1) / kBwdTile;
     w.total = align_up(sizeof(BagMapEntry) * ((static_cast<size_t>(n) + 63) / 64), 256)  // bag map
@@ -651,7 +819,11 @@ inline BwdWs bwd_ws_layout(int32_t n, int32_t dim) {
               + 3 * align_up(4 * static_cast<size_t>(w.num_tiles), 256)              // tile_seg0, tile_rseg, order
               + align_up(4 * static_cast<size_t>(kOrderBuckets + 2), 256)             // bucket offsets of the order
               + align_up(4 * part_hist_elems(make_chunk_plan(w.num_tiles), kOrderBuckets + 1), 256)
-              + align_up(4 * static_cast<size_t>(kOrderBuckets + 1), 256);
+              + align_up(4 * static_cast<size_t>(kOrderBuckets + 1), 256)
+              + align_up(4 * bwd_num_slots(w.num_tiles) * kBwdTile, 256)                // row index per block and position
+              + (mode == NP_POOL_MEAN ? align_up(4 * bwd_num_slots(w.num_tiles) * kBwdTile, 256) : 0)   // and its weight
+              + align_up(8 * bwd_num_slots(w.num_tiles), 256)                             // tile and first segment of every block
+              + (mode != NP_SEQ ? align_up(4 * static_cast<size_t>(n), 256) : 0);       // owner row of single-lookup keys (variant)
     return w;
 }
 
@@ -686,10 +858,15 @@ struct BwdPlan {
     ChunkPlan oplan;
     int num_tiles, map_entries;
     bool ordered;
+    int32_t* srow;   // "bwd_row_index": upstream-gradient row per block and position
+    float* sweight;  // mean pooling only
+    int2* slot_info;   // tile and first segment of every block
+    int num_slots;
+    int32_t* sdst;   // variant "bwd_singles_by_bag", pooled modes only
 };
 
 inline BwdPlan bwd_plan(const BwdArgs& a) {
-    const BwdWs L = bwd_ws_layout(a.n, a.dim);
+    const BwdWs L = bwd_ws_layout(a.n, a.dim, a.mode);
     WsCursor cur(a.ws);
     BwdPlan P;
     P.num_tiles = L.num_tiles;
@@ -704,13 +881,18 @@ inline BwdPlan bwd_plan(const BwdArgs& a) {
     P.oplan = make_chunk_plan(L.num_tiles);
     P.oH = cur.take<uint32_t>(part_hist_elems(P.oplan, kOrderBuckets + 1));
     P.obin = cur.take<uint32_t>(kOrderBuckets + 1);
+    P.num_slots = static_cast<int>(bwd_num_slots(L.num_tiles));
+    P.srow = cur.take<int32_t>(static_cast<size_t>(P.num_slots) * kBwdTile);
+    P.sweight = a.mode == NP_POOL_MEAN ? cur.take<float>(static_cast<size_t>(P.num_slots) * kBwdTile) : nullptr;
+    P.slot_info = cur.take<int2>(P.num_slots);
+    P.sdst = a.mode != NP_SEQ ? cur.take<int32_t>(a.n) : nullptr;
     const bool seq = a.mode == NP_SEQ;
     // The locality order pays when dY is larger than the last-level cache (2.42 -> 2.06 ms at 1.3 GB); below that it only
     // costs three launches (0.63 -> 0.57 ms per step at 109 MB).  In sequence mode every dY row is read exactly once, so
     // there is nothing to share: the pass would cost more (0.04 ms) than the slightly friendlier read order returns
     // (0.02 ms on configuration 3).
     const size_t dy_bytes = static_cast<size_t>(a.num_bags) * (seq ? a.max_len : 1) * a.dim * (a.dy_dtype == NP_BF16 ? 2 : 4);
-    P.ordered = dy_bytes > kOrderMinDyBytes && !seq;
+    P.ordered = static_cast<int64_t>(dy_bytes) > tune_get(kTuneBwdOrderMinDyBytes) && !seq;  // initially 256 MB, the Infinity Cache: a dY that fits it is re-read from there anyway
     return P;
 }
 
@@ -724,12 +906,46 @@ inline void bwd_prepare_launch(const BwdArgs& a, const BwdPlan& P) {
         run_partition_pass(pol, P.num_tiles, nullptr, kOrderBuckets + 1, 11, P.oplan, P.oH, P.obin, nullptr, P.order_offsets,
                            a.stream, "bwd_order_hist", "bwd_order_colscan", "bwd_order_scatter");
     }
+    if (tune_get(kTuneBwdRowIndex) != 0) {
+        const int32_t* order = P.ordered ? P.order : nullptr;
+        const int32_t* order_offsets = P.ordered ? P.order_offsets : nullptr;
+        const int g = (P.num_slots + kRowsSlots - 1) / kRowsSlots;
+        if (a.mode == NP_POOL_MEAN)
+            NP_LAUNCH("bwd_rows", bwd_rows_kernel<true>, dim3(g), dim3(256), 0, a.stream, a.occ, a.n, P.bagmap, a.bag_offsets, 0, a.max_len,
+                      P.num_tiles, order, order_offsets, P.tile_seg0, P.num_slots, P.srow, P.sweight, P.slot_info);
+        else
+            NP_LAUNCH("bwd_rows", bwd_rows_kernel<false>, dim3(g), dim3(256), 0, a.stream, a.occ, a.n, P.bagmap, a.bag_offsets,
+                      a.mode == NP_SEQ ? 1 : 0, a.max_len, P.num_tiles, order, order_offsets, P.tile_seg0, P.num_slots, P.srow,
+                      P.sweight, P.slot_info);
+    }
 }
 
 template <int LPR, int NV, int FUSED>
 void bwd_launch(const BwdArgs& a) {
     const BwdPlan P = bwd_plan(a);
     if (!a.prepared) bwd_prepare_launch(a, P);
+    const bool row_index = tune_get(kTuneBwdRowIndex) != 0;  // the preparing call wrote the index under the same setting
+    const int32_t* srow = row_index ? P.srow : nullptr;
+    const float* sweight = row_index ? P.sweight : nullptr;
+    const int2* slot_info = row_index ? P.slot_info : nullptr;
+    // single-lookup keys bag by bag: pooled modes, fp32 upstream gradients, gradient rows as the sink
+    const bool singles = FUSED == kSinkGrads && a.mode != NP_SEQ && a.dy_dtype == NP_F32 && !a.prepared &&
+                         tune_get(kTuneBwdSinglesByBag) != 0;
+    if (singles) {
+        int g = (a.n + 255) / 256;
+        if (g > 16384) g = 16384;
+        NP_LAUNCH("bwd_single_fill", bwd_single_fill_kernel, dim3(g), dim3(256), 0, a.stream, P.sdst, a.n);
+        NP_LAUNCH("bwd_single_mark", bwd_single_mark_kernel, dim3(g), dim3(256), 0, a.stream, a.occ_offsets, a.occ, a.d_num_unique,
+                  a.cap < a.n ? a.cap : a.n, a.unique_to_send, P.sdst);
+        constexpr int GPB = 256 / LPR;
+        const unsigned cg = static_cast<unsigned>((static_cast<int64_t>(a.num_bags) + GPB - 1) / GPB);
+        if (a.mode == NP_POOL_MEAN)
+            NP_LAUNCH("bwd_single_copy", (bwd_single_copy_kernel<LPR, NV, true>), dim3(cg), dim3(256), 0, a.stream,
+                      static_cast<const float*>(a.dY), a.dim, a.bag_offsets, a.num_bags, P.sdst, a.sink.grads);
+        else
+            NP_LAUNCH("bwd_single_copy", (bwd_single_copy_kernel<LPR, NV, false>), dim3(cg), dim3(256), 0, a.stream,
+                      static_cast<const float*>(a.dY), a.dim, a.bag_offsets, a.num_bags, P.sdst, a.sink.grads);
+    }
     struct { int num_tiles; } L{P.num_tiles};
     BagMapEntry* bagmap = P.bagmap;
     float* tile_left = P.tile_left;
@@ -739,12 +955,12 @@ void bwd_launch(const BwdArgs& a) {
     int32_t* order = P.ordered ? P.order : nullptr;  // no order: tiles run in index order
     int32_t* order_offsets = P.ordered ? P.order_offsets : nullptr;
     const int seq = a.mode == NP_SEQ ? 1 : 0;
-    const unsigned main_grid = static_cast<unsigned>((L.num_tiles + 2 * kNumXcd + kNumXcd - 1) / kNumXcd * kNumXcd);
+    const unsigned main_grid = static_cast<unsigned>(P.num_slots);
     const bool mean = a.mode == NP_POOL_MEAN;
 #define NP_BWD_MAIN(L_, N_, M_, T_, P_)                                                                                        \
     NP_LAUNCH("bwd_main", (bwd_main_kernel<L_, N_, M_, T_, FUSED, P_>), dim3(main_grid), dim3(256), 0, a.stream,                 \
               static_cast<const T_*>(a.dY), a.dim, seq, a.max_len, a.bag_offsets, a.n, a.occ_offsets, a.occ, a.d_num_unique,     \
-              a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.cap < a.n ? a.cap : a.n, a.sink, tile_left, tile_right, tile_rseg)
+              a.unique_to_send, bagmap, tile_seg0, order, order_offsets, L.num_tiles, a.cap < a.n ? a.cap : a.n, a.sink, tile_left, tile_right, tile_rseg, srow, sweight, slot_info, singles ? 1 : 0)
     bool launched = false;
     if constexpr (FUSED == kSinkGrads && NV == 1 && LPR >= 8) {
         // bf16 rows a multiple of 8 elements wide: half the lanes per row, 16-byte loads (words 2r, 2r + 1 per lane)
@@ -770,12 +986,14 @@ void bwd_launch(const BwdArgs& a) {
 }
 
 template <int FUSED>
-void bwd_fused_dispatch(const BwdArgs& a, int words) {
+void bwd_dispatch(const BwdArgs& a, int words) {
     if (words <= 4) bwd_launch<4, 1, FUSED>(a);
     else if (words <= 8) bwd_launch<8, 1, FUSED>(a);
     else if (words <= 16) bwd_launch<16, 1, FUSED>(a);
     else if (words <= 32) bwd_launch<32, 1, FUSED>(a);
-    else bwd_launch<64, 1, FUSED>(a);
+    else if (words <= 64) bwd_launch<64, 1, FUSED>(a);
+    else if (words <= 128) bwd_launch<64, 2, FUSED>(a);
+    else bwd_launch<64, 4, FUSED>(a);
 }
 
 }  // namespace np
@@ -786,7 +1004,7 @@ size_t np_lookup_bwd_workspace_bytes(int32_t num_bags, int32_t n, int32_t dim, i
     (void)num_bags;
     (void)mode;
     if (n <= 0 || dim < 4) return 0;
-    return np::bwd_ws_layout(n, dim).total;
+    return np::bwd_ws_layout(n, dim, mode).total;
 }
 
 // Argument checks shared by np_lookup_bwd_prepare (dY, occ and grads absent) and the reducing calls.
@@ -811,13 +1029,14 @@ static int bwd_check_common(int32_t dy_dtype, int32_t dim, int32_t mode, int32_t
 }
 
 int np_lookup_bwd_prepare(int32_t dy_dtype, int32_t dim, int32_t mode, int32_t max_len, const int32_t* bag_offsets,
-                          int32_t num_bags, int32_t n, const int32_t* occ_offsets, const int32_t* d_num_unique, void* ws,
-                          size_t ws_bytes, void* stream) {
+                          int32_t num_bags, int32_t n, const int32_t* occ_offsets, const int32_t* occ, const int32_t* d_num_unique,
+                          void* ws, size_t ws_bytes, void* stream) {
     bool nothing = false;
     const int rc = bwd_check_common(dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, d_num_unique, NP_MAX_DIM, ws,
                                     ws_bytes, &nothing);
     if (rc != NP_OK || nothing) return rc;
-    np::BwdArgs a{nullptr, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, nullptr, d_num_unique, n, nullptr,
+    if (!occ) return NP_ERR_INVALID_ARG;
+    np::BwdArgs a{nullptr, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, n, nullptr,
                   np::RowSink{nullptr, nullptr, nullptr, nullptr, 0.f, 0.f, 0.f}, ws, static_cast<hipStream_t>(stream), false};
     np::bwd_prepare_launch(a, np::bwd_plan(a));
     return np::launch_status();
@@ -836,14 +1055,7 @@ static int bwd_reduce(const void* dY, int32_t dy_dtype, int32_t dim, int32_t mod
     if (!np::aligned(dY, dy_dtype == NP_BF16 ? 8 : 16) || !np::aligned(grads, 16)) return NP_ERR_INVALID_ARG;
     np::BwdArgs a{dY, dy_dtype, dim, mode, max_len, bag_offsets, num_bags, n, occ_offsets, occ, d_num_unique, cap, unique_to_send,
                   np::RowSink{grads, nullptr, nullptr, nullptr, 0.f, 0.f, 0.f}, ws, static_cast<hipStream_t>(stream), prepared};
-    const int words = dim / 4;
-    if (words <= 4) np::bwd_launch<4, 1, np::kSinkGrads>(a);
-    else if (words <= 8) np::bwd_launch<8, 1, np::kSinkGrads>(a);
-    else if (words <= 16) np::bwd_launch<16, 1, np::kSinkGrads>(a);
-    else if (words <= 32) np::bwd_launch<32, 1, np::kSinkGrads>(a);
-    else if (words <= 64) np::bwd_launch<64, 1, np::kSinkGrads>(a);
-    else if (words <= 128) np::bwd_launch<64, 2, np::kSinkGrads>(a);
-    else np::bwd_launch<64, 4, np::kSinkGrads>(a);
+    np::bwd_dispatch<np::kSinkGrads>(a, dim / 4);
     return np::launch_status();
 }
 
@@ -873,7 +1085,7 @@ int np_lookup_bwd_adagrad_t(const void* dY, int32_t dy_dtype, int32_t dim, int32
     if (mode != NP_POOL_SUM && mode != NP_POOL_MEAN && mode != NP_SEQ) return NP_ERR_INVALID_ARG;
     if (dy_dtype != NP_F32 && dy_dtype != NP_BF16) return NP_ERR_INVALID_ARG;
     if (mode == NP_SEQ && max_len < 1) return NP_ERR_INVALID_ARG;
-    if (dim < 4 || dim % 4 != 0 || dim > 256) return NP_ERR_UNSUPPORTED;  // a row must fit one wave of float4 words
+    if (dim < 4 || dim % 4 != 0 || dim > NP_MAX_DIM) return NP_ERR_UNSUPPORTED;
     if (mode == NP_SEQ && static_cast<int64_t>(num_bags) * max_len > INT32_MAX) return NP_ERR_UNSUPPORTED;
     if (n == 0) return NP_OK;
     if (n > INT32_MAX - (1 << 20)) return NP_ERR_UNSUPPORTED;
@@ -885,9 +1097,9 @@ int np_lookup_bwd_adagrad_t(const void* dY, int32_t dy_dtype, int32_t dim, int32
                   np::RowSink{nullptr, table, state, unique, lr, eps, 1.0f / static_cast<float>(dim)}, ws,
                   static_cast<hipStream_t>(stream), false};
     const int words = dim / 4;
-    if (table_dtype == NP_BF16) np::bwd_fused_dispatch<np::kSinkBf16>(a, words);
-    else if (table_dtype == NP_F16) np::bwd_fused_dispatch<np::kSinkF16>(a, words);
-    else np::bwd_fused_dispatch<np::kSinkF32>(a, words);
+    if (table_dtype == NP_BF16) np::bwd_dispatch<np::kSinkBf16>(a, words);
+    else if (table_dtype == NP_F16) np::bwd_dispatch<np::kSinkF16>(a, words);
+    else np::bwd_dispatch<np::kSinkF32>(a, words);
     return np::launch_status();
 }
 

@@ -31,6 +31,7 @@ constexpr int kPartWaves = kPartThreads / kWave;
 constexpr int kPartIPT = NP_PART_IPT;
 constexpr int kPartTile = kPartThreads * kPartIPT;
 static_assert(kPartIPT * kWave <= 65535, "per-wave digit counters are 16 bits wide");
+static_assert((kPartWaves * 2) % 16 == 0, "the per-wave 16-bit counters of one bin fill whole 16-byte words");
 constexpr int kPartMaxBins = 4096;
 #ifndef NP_TARGET_CHUNKS
 #define NP_TARGET_CHUNKS 512  // two blocks on each of the 256 CUs: 384, 640, 768 and 1024 leave a ragged last round
@@ -123,10 +124,9 @@ part_hist_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, Chunk
     for (int64_t base = lo; base < hi; base += static_cast<int64_t>(kHistThreads) * kBatch) {
         typename P::KeyT k[kBatch];
 #pragma unroll
-        for (int q = 0; q < kBatch; ++q) {
+        for (int q = 0; q < kBatch; ++q) {  // unconditional loads (past the end: the chunk's last item, masked below)
             const int64_t i = base + q * kHistThreads + threadIdx.x;
-            k[q] = typename P::KeyT(0);
-            if (i < hi) k[q] = pol.load_key(i);
+            k[q] = pol.load_key(i < hi ? i : hi - 1);
         }
 #pragma unroll
         for (int q = 0; q < kBatch; ++q) {
@@ -197,6 +197,9 @@ part_colscan_kernel(uint32_t* __restrict__ H, int num_chunks, int bins, uint32_t
     }
 }
 
+// Measured and not taken (three sort passes over 42 M items, 0.95 ms as it stands): the digit width as a template
+// argument so that the ballot loop unrolls (1.02 ms), the per-bin scan over the waves with all reads issued before the
+// writes (1.09 ms).
 template <class P>
 __global__ void __launch_bounds__(kPartThreads)
 part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, int nbits, ChunkPlan plan,
@@ -209,7 +212,11 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
     uint32_t* btot = binstart + bins;
     int* scan_tmp = reinterpret_cast<int*>(btot + bins);  // 16 ints
     unsigned char* un = smem_raw + part_fixed_lds_bytes(bins);
-    volatile uint16_t* cnt = reinterpret_cast<volatile uint16_t*>(un);  // [waves][bins], aliased with the staging area
+    // Per-wave digit counters [waves][bins], aliased with the staging area.  Plain (not volatile) accesses: a volatile LDS
+    // access makes the compiler wait for every outstanding global load as well, which would drain the prefetch of the
+    // next tile at the first counter access.  Where lanes of a wave hand values to each other through a counter, a
+    // compiler-only fence keeps the accesses in program order; the wave's LDS operations execute in that order.
+    uint16_t* cnt = reinterpret_cast<uint16_t*>(un);
     KeyT* skey = reinterpret_cast<KeyT*>(un);
     uint32_t* sval = reinterpret_cast<uint32_t*>(skey + kPartTile);
     uint16_t* sdig = reinterpret_cast<uint16_t*>(sval + kPartTile);
@@ -245,19 +252,31 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
 
     // the items of the first tile; later tiles are fetched one iteration ahead and stay in flight across the LDS
     // barriers of the tile being ranked
+    // Loads past the chunk's end are redirected to its last item instead of being skipped: unconditional loads are issued
+    // back to back and stay in flight, conditional ones are waited for one by one.  What they bring is never used
+    // (positions past tile_count are masked everywhere below).
     KeyT kn[kPartIPT];
     uint32_t vn[kPartIPT];
+    const int64_t last = hi - 1;
 #pragma unroll
     for (int i = 0; i < kPartIPT; ++i) {
-        const int64_t at = lo + w * (kWave * kPartIPT) + i * kWave + lane;
         kn[i] = KeyT(0);
         vn[i] = 0;
-        if (at < hi) pol.load(at, kn[i], vn[i]);
+    }
+    if (lo < hi) {  // uniform
+#pragma unroll
+        for (int i = 0; i < kPartIPT; ++i) {
+            const int64_t at = lo + w * (kWave * kPartIPT) + i * kWave + lane;
+            pol.load(at < hi ? at : last, kn[i], vn[i]);
+        }
     }
 
     for (int64_t tile_base = lo; tile_base < hi; tile_base += kPartTile) {
         const int tile_count = hi - tile_base < kPartTile ? static_cast<int>(hi - tile_base) : kPartTile;
-        for (int i = tid; i < kPartWaves * bins; i += kPartThreads) cnt[i] = 0;  // 16-bit stores
+        {
+            uint4* z = reinterpret_cast<uint4*>(un);  // kPartWaves * bins halfwords = bins * (kPartWaves / 8) 16-byte words
+            for (int i = tid; i < bins * (kPartWaves * 2 / 16); i += kPartThreads) z[i] = make_uint4(0u, 0u, 0u, 0u);
+        }
         lds_barrier();
 
         KeyT k[kPartIPT];
@@ -272,9 +291,7 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
 #pragma unroll
         for (int i = 0; i < kPartIPT; ++i) {
             const int64_t at = tile_base + kPartTile + w * (kWave * kPartIPT) + i * kWave + lane;
-            kn[i] = KeyT(0);
-            vn[i] = 0;
-            if (at < hi) pol.load(at, kn[i], vn[i]);
+            pol.load(at < hi ? at : last, kn[i], vn[i]);
         }
         // stable rank of every item among the items of its wave with the same digit
 #pragma unroll
@@ -282,12 +299,14 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
             const bool valid = idx < tile_count;
             const uint64_t peers = match_any(d[i], nbits, valid);
-            volatile uint16_t* ctr = cnt + w * bins + d[i];
+            uint16_t* ctr = cnt + w * bins + d[i];
             const uint32_t pre = *ctr;
             const uint64_t below = peers & lt;
             r[i] = pre + __popcll(below);
+            compiler_fence();
             __builtin_amdgcn_wave_barrier();
             if (valid && below == 0) *ctr = static_cast<uint16_t>(pre + __popcll(peers));
+            compiler_fence();
             __builtin_amdgcn_wave_barrier();
         }
         lds_barrier();
@@ -314,7 +333,7 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
 #pragma unroll
         for (int i = 0; i < kPartIPT; ++i) {
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
-            const uint32_t in_bin = cnt[w * bins + d[i]] + r[i];
+            const uint32_t in_bin = static_cast<uint32_t>(cnt[w * bins + d[i]]) + r[i];
             r[i] = binstart[d[i]] + in_bin;  // position inside the reordered tile
             if (idx < tile_count && gofs[d[i]] + in_bin < static_cast<uint32_t>(n)) pol.placed(tile_base + idx, gofs[d[i]] + in_bin);
         }

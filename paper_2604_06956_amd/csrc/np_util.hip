@@ -1,5 +1,7 @@
 // Host-side odds and ends of the library (version, status text, per-kernel event timing) and the two
 // harness kernels: the stateless table initialiser and the plain copy used as a bandwidth yardstick.
+#include <atomic>
+#include <cstring>
 #include <string>
 #include <vector>
 
@@ -18,6 +20,24 @@ std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_pool;  // events created s
 size_t g_prof_next = 0;
 std::vector<std::string> g_prof_only;                     // when not empty: only launches with these names are timed
 }  // namespace
+
+namespace {
+struct TunableSpec {
+    const char* name;
+    int64_t initial, lo, hi;
+};
+// initial values: where each alternative starts to pay on an MI355X (the measurements are in the kernels' comments)
+const TunableSpec kTunables[kTuneCount] = {
+    {"emit_order_min_n", int64_t(1) << 22, 0, INT64_MAX},          // np_dedup: lookups from which the inverse map is written tile-ordered
+    {"bwd_order_min_dy_bytes", int64_t(256) << 20, 0, INT64_MAX},  // np_lookup_bwd: upstream-gradient bytes from which tiles run locality-ordered
+    {"bwd_row_index", 0, 0, 1},  // np_lookup_bwd: 1 = resolve the upstream-gradient row of every sorted position in a pass of its own
+    {"bwd_singles_by_bag", 0, 0, 1},  // np_lookup_bwd: 1 = keys with one lookup are copied bag by bag, the reduction skips them
+};
+std::atomic<int64_t> g_tune[kTuneCount] = {{kTunables[0].initial}, {kTunables[1].initial}, {kTunables[2].initial},
+                                           {kTunables[3].initial}};
+}  // namespace
+
+int64_t tune_get(Tunable which) { return g_tune[which].load(std::memory_order_relaxed); }
 
 void prof_begin(const char* name, hipStream_t stream) {
     if (!g_prof_on) return;
@@ -160,11 +180,65 @@ __global__ void __launch_bounds__(256) stream_copy_kernel(float4* __restrict__ d
     for (; w < hi; w += 256) store_stream(dst + w, load_stream(src + w));
 }
 
+// Yardstick for the row kernels: random gathers of whole rows of 64 floats (16 lanes x 16 bytes, eight rows in flight per
+// lane group, the access pattern of np_lookup_fwd / np_lookup_bwd), summed in groups of 64 so that next to nothing is
+// written.  rows[i] = (a hash of i) mod num_rows: the working set is num_rows * 256 bytes.
+__global__ void __launch_bounds__(256)
+gather_rate_kernel(const float4* __restrict__ src, uint32_t num_rows, int64_t n, uint32_t seed, float4* __restrict__ out) {
+    constexpr int LPR = 16, UN = 8;
+    const int r = threadIdx.x % LPR;
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * (256 / LPR) + threadIdx.x / LPR;
+    const int64_t base = g * 64;
+    if (base >= n) return;
+    const int gl = __lane_id() & ~(LPR - 1);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = 0; c < 64; c += LPR) {
+        uint32_t h = static_cast<uint32_t>(base + c + r) * 2654435761u + seed;
+        h ^= h >> 16; h *= 0x7feb352dU; h ^= h >> 15; h *= 0x846ca68bU; h ^= h >> 16;
+        const uint32_t mine = static_cast<uint32_t>((static_cast<uint64_t>(h) * num_rows) >> 32);
+        for (int k0 = 0; k0 < LPR; k0 += UN) {
+            float4 x[UN];
+#pragma unroll
+            for (int q = 0; q < UN; ++q) {
+                const uint32_t row = static_cast<uint32_t>(__shfl(static_cast<int>(mine), gl + k0 + q, kWave));
+                x[q] = src[static_cast<uint64_t>(row) * LPR + r];
+            }
+#pragma unroll
+            for (int q = 0; q < UN; ++q) {
+                acc.x += x[q].x;
+                acc.y += x[q].y;
+                acc.z += x[q].z;
+                acc.w += x[q].w;
+            }
+        }
+    }
+    out[g * LPR + r] = acc;
+}
+
 }  // namespace np
 
 extern "C" {
 
-int np_version(void) { return 10200; }  // 1.2.0: np_util_check_batch, wider loads of bf16 upstream gradients
+int np_tune_set(const char* name, int64_t value) {
+    if (!name) return NP_ERR_INVALID_ARG;
+    for (int i = 0; i < np::kTuneCount; ++i) {
+        if (std::strcmp(name, np::kTunables[i].name) == 0) {
+            if (value < np::kTunables[i].lo || value > np::kTunables[i].hi) return NP_ERR_INVALID_ARG;
+            np::g_tune[i].store(value, std::memory_order_relaxed);
+            return NP_OK;
+        }
+    }
+    return NP_ERR_INVALID_ARG;
+}
+
+int64_t np_tune_get(const char* name) {
+    if (!name) return -1;
+    for (int i = 0; i < np::kTuneCount; ++i)
+        if (std::strcmp(name, np::kTunables[i].name) == 0) return np::g_tune[i].load(std::memory_order_relaxed);
+    return -1;
+}
+
+int np_version(void) { return 10300; }  // 1.3.0: np_route_static, np_tune_set / np_tune_get, tile-ordered inverse map
 
 const char* np_status_string(int status) {
     switch (status) {
@@ -254,6 +328,17 @@ int np_util_stream_copy(void* dst, const void* src, size_t bytes, void* stream) 
     const unsigned grid = static_cast<unsigned>(want < 16384 ? want : 16384);
     NP_LAUNCH("stream_copy", np::stream_copy_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
               static_cast<float4*>(dst), static_cast<const float4*>(src), words);
+    return np::launch_status();
+}
+
+int np_util_gather_rate(const float* src, int64_t num_rows, int64_t n, uint32_t seed, float* out, void* stream) {
+    if (!src || !out || num_rows < 1 || num_rows > 0xFFFFFFFFll || n < 0 || n % 64 != 0) return NP_ERR_INVALID_ARG;
+    if (!np::aligned(src, 16) || !np::aligned(out, 16)) return NP_ERR_INVALID_ARG;
+    if (n == 0) return NP_OK;
+    const int64_t blocks = (n / 64 + 15) / 16;
+    if (blocks > 0x7FFFFFFFll) return NP_ERR_UNSUPPORTED;
+    NP_LAUNCH("gather_rate", np::gather_rate_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, static_cast<hipStream_t>(stream),
+              reinterpret_cast<const float4*>(src), static_cast<uint32_t>(num_rows), n, seed, reinterpret_cast<float4*>(out));
     return np::launch_status();
 }
 

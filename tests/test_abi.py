@@ -45,6 +45,18 @@ def test_status_strings_and_version(lib):
     assert lib.np_version() >= 100
 
 
+def test_tunables_are_host_only(lib):
+    lib.np_tune_get.restype = ctypes.c_int64
+    lib.np_tune_get.argtypes = [ctypes.c_char_p]
+    lib.np_tune_set.restype = ctypes.c_int
+    lib.np_tune_set.argtypes = [ctypes.c_char_p, ctypes.c_int64]
+    assert lib.np_tune_get(b"emit_order_min_n") == 1 << 22
+    assert lib.np_tune_get(b"nope") == -1 and lib.np_tune_get(None) == -1
+    assert lib.np_tune_set(b"nope", 1) == -1 and lib.np_tune_set(b"emit_order_min_n", -1) == -1
+    assert lib.np_tune_set(b"emit_order_min_n", 77) == 0 and lib.np_tune_get(b"emit_order_min_n") == 77
+    assert lib.np_tune_set(b"emit_order_min_n", 1 << 22) == 0
+
+
 def test_workspace_sizes_are_monotone_and_aligned(lib):
     f = lib.np_dedup_workspace_bytes
     f.restype = ctypes.c_size_t

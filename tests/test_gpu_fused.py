@@ -34,7 +34,7 @@ def _run_both(H, table0, state0, keys, off, dY, mode, max_len, key_bits):
     return t1, s1, t2, s2, d, U, g
 
 
-@pytest.mark.parametrize("dim", [4, 16, 48, 64, 128, 256])
+@pytest.mark.parametrize("dim", [4, 16, 48, 64, 128, 256, 260, 512, 768, 1024])
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("hot", [0.0, 0.6])
 def test_fused_equals_separate_calls_bitwise(H, dim, mode, hot):
@@ -63,7 +63,7 @@ def test_fused_equals_separate_calls_bitwise(H, dim, mode, hot):
 
 
 @pytest.mark.parametrize("kind", ["bf16", "f16"])
-@pytest.mark.parametrize("dim,mode", [(8, 0), (64, 1), (256, 0)])
+@pytest.mark.parametrize("dim,mode", [(8, 0), (64, 1), (256, 0), (512, 1), (1024, 0)])
 def test_fused_on_16bit_tables_equals_separate_calls_bitwise(H, kind, dim, mode):
     """np_lookup_bwd_adagrad_t on a bf16 / fp16 table against np_lookup_bwd + np_sparse_adagrad_t: same bits."""
     import torch
@@ -136,12 +136,12 @@ def test_fused_scaled_large_config(H):
     assert torch.equal(t1, t2) and torch.equal(s1, s2)
 
 
-def test_fused_rejects_wide_rows(H):
+def test_fused_rejects_rows_wider_than_the_library_takes(H):
     import torch
-    t = torch.zeros((10, 512), device="cuda")
+    t = torch.zeros((10, 2048), device="cuda")
     s = torch.zeros(10, device="cuda")
     z = torch.zeros(4, dtype=torch.int32, device="cuda")
     with pytest.raises(H.B.NestPipeError) as e:
-        H.B.np_lookup_bwd_adagrad(torch.zeros((1, 512), device="cuda"), 0, 1, z[:2], 1, z, z, torch.zeros(4, dtype=torch.int64, device="cuda"),
+        H.B.np_lookup_bwd_adagrad(torch.zeros((1, 2048), device="cuda"), 0, 1, z[:2], 1, z, z, torch.zeros(4, dtype=torch.int64, device="cuda"),
                                   z[:1], 1, t, s, 0.01, 1e-8)
     assert e.value.status == -3

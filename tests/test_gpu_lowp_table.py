@@ -174,6 +174,40 @@ def test_adagrad_16bit_table(H, K, dim):
     assert np.array_equal(tgot[keys[5]], t0[keys[5]]) and sgot[keys[5]] == 0.0
 
 
+@pytest.mark.parametrize("dim", [8, 64, 512])
+def test_fused_bwd_adagrad_16bit_table_against_the_oracle(H, K, dim):
+    """np_lookup_bwd_adagrad_t on a 16-bit table held against the oracle directly (not through the separate HIP calls):
+    oracle gradient sums, then the oracle's 16-bit update.  The upstream gradients are small integers, so the fp32 sums
+    are exact and the update on both sides starts from the same gradient rows; what remains is the update's own rounding."""
+    import torch
+    rng = np.random.default_rng(dim + 5)
+    R, Bn = 4000, 2501
+    off, keys = _bags(rng, Bn, 9, R)
+    keys[rng.random(keys.shape[0]) < 0.35] = 17                       # one key with a long occurrence list
+    n = keys.shape[0]
+    t0 = K.to_bits(rng.standard_normal((R, dim)) * 0.01)
+    s0 = (rng.random(R) * 0.1).astype(np.float32)
+    dY = rng.integers(-6, 7, size=(Bn, dim)).astype(np.float32)
+    unique, inverse, *_ = H.O.dedup(keys)
+    U = unique.size
+    grads, _ = H.O.lookup_bwd(dY, H.O.F32, dim, 0, 1, off, inverse, U)
+    tr, sr = t0.copy(), s0.copy()
+    K.oracle_adagrad(H.O)(tr, sr, unique, grads, 0.01, 1e-8)
+    tg, sg = K.dev(t0), H.dev(s0)
+    d = H.B.np_dedup(H.dev(keys), 12)
+    H.B.np_lookup_bwd_adagrad_t(H.dev(dY), 0, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["unique"], d["num_unique"], n, tg, sg,
+                                0.01, 1e-8)
+    torch.cuda.synchronize()
+    assert int(d["num_unique"].item()) == U
+    tgot, sgot = _host_bits(tg), H.host(sg)
+    w0 = K.widen(t0).astype(np.float64)
+    delta = np.abs(K.widen(tr).astype(np.float64) - w0)
+    _assert_rows(H, K, tgot[unique], tr[unique], np.abs(w0[unique]) + delta[unique], f"fused update of {K.name} rows dim={dim}")
+    H.assert_close(sgot[unique], sr[unique], np.abs(sr[unique]), H.RTOL_F32, "updated state")
+    rest = np.setdiff1d(np.arange(R), unique)
+    assert np.array_equal(tgot[rest], t0[rest]) and sgot[rest].tobytes() == s0[rest].tobytes()
+
+
 def test_bad_table_dtype_and_alignment_are_refused(H):
     import torch
     t = torch.zeros((16, 8), dtype=torch.bfloat16, device="cuda")

@@ -28,6 +28,28 @@ def test_table_init_matches_the_numpy_generator(H):
         assert H.host(t).tobytes() == ref.tobytes()
 
 
+def test_gather_yardstick_reads_the_rows_it_says(H):
+    """np_util_gather_rate against its definition: row read i = hash(i, seed) mod-scaled into num_rows, sums of 64 reads."""
+    import torch
+    rng = np.random.default_rng(3)
+    R, n, seed = 1000, 64 * 37, 5
+    src = rng.integers(-3, 4, size=(R + 50, 64)).astype(np.float32)         # small integers: the sums are exact in any order
+    out = torch.full((n // 64, 64), -1.0, dtype=torch.float32, device="cuda")
+    H.B.np_util_gather_rate(H.dev(src), R, n, seed, out)
+    torch.cuda.synchronize()
+    i = np.arange(n, dtype=np.uint64)
+    h = (i * 2654435761 + seed) & 0xFFFFFFFF
+    h ^= h >> 16
+    h = (h * 0x7feb352d) & 0xFFFFFFFF
+    h ^= h >> 15
+    h = (h * 0x846ca68b) & 0xFFFFFFFF
+    h ^= h >> 16
+    rows = ((h * R) >> 32).astype(np.int64)
+    assert rows.max() < R
+    want = src[rows].reshape(n // 64, 64, 64).sum(axis=1)
+    assert np.array_equal(H.host(out), want)
+
+
 # ------------------------------------------------------------------------------------------ dedup
 
 def _keys_case(name):
@@ -81,6 +103,56 @@ def test_dedup_bit_exact(H, case):
     keys, bits = _keys_case(case)
     g, _ = H.gpu_dedup(keys, bits)
     H.assert_dedup_equal(g, keys)
+
+
+@pytest.fixture
+def tile_ordered_emit(H):
+    """Forces np_dedup's tile-ordered way of writing the inverse map (taken on its own only for batches of millions of
+    lookups) for every size; the outputs are the same bits either way."""
+    old = H.B.np_tune_get("emit_order_min_n")
+    H.B.np_tune_set("emit_order_min_n", 0)
+    yield
+    H.B.np_tune_set("emit_order_min_n", old)
+
+
+@pytest.mark.parametrize("case", DEDUP_CASES + ["tile1024_minus_1", "tile1024_exact", "tile1024_plus_1", "hot_runs"])
+def test_dedup_bit_exact_with_the_tile_ordered_inverse_map(H, tile_ordered_emit, case):
+    if case.startswith("tile1024"):
+        rng = np.random.default_rng(len(case))
+        keys = rng.integers(0, 300, size=1024 * 3 + {"minus_1": -1, "exact": 0, "plus_1": 1}[case.split("_", 1)[1]]).astype(np.int64)
+        bits = 9
+    elif case == "hot_runs":    # several keys whose segments cover whole tiles, beside many cold keys, ragged end
+        rng = np.random.default_rng(99)
+        keys = rng.integers(0, 1 << 22, size=700_001).astype(np.int64)
+        pick = rng.random(keys.size)
+        keys[pick < 0.30] = 12345
+        keys[(pick >= 0.30) & (pick < 0.45)] = 4_000_000
+        keys[(pick >= 0.45) & (pick < 0.50)] = 0
+        bits = 22
+    else:
+        keys, bits = _keys_case(case)
+    g, _ = H.gpu_dedup(keys, bits)
+    H.assert_dedup_equal(g, keys)
+    d = H.B.np_dedup(H.dev(keys), bits, want_inverse=False)      # without the inverse map the chunked kernel runs: same bits
+    import torch
+    torch.cuda.synchronize()
+    U = g["U"]
+    for name, k in (("unique", U), ("counts", U), ("occ_offsets", U + 1), ("occ", keys.shape[0])):
+        assert H.host(d[name])[:k].tobytes() == g[name].tobytes(), name
+
+
+def test_tunables(H):
+    B = H.B
+    assert B.np_tune_get("no_such_knob") == -1
+    with pytest.raises(B.NestPipeError):
+        B.np_tune_set("no_such_knob", 1)
+    with pytest.raises(B.NestPipeError):
+        B.np_tune_set("emit_order_min_n", -5)
+    old = B.np_tune_get("bwd_order_min_dy_bytes")
+    assert old == 256 << 20
+    B.np_tune_set("bwd_order_min_dy_bytes", 12345)
+    assert B.np_tune_get("bwd_order_min_dy_bytes") == 12345
+    B.np_tune_set("bwd_order_min_dy_bytes", old)
 
 
 def test_dedup_empty(H):
@@ -269,6 +341,47 @@ def test_bwd_pooled(H, dim, mode, hot):
         assert np.array_equal(H.host(gc)[:U], np.repeat(counts[:, None], dim, 1).astype(np.float32))
 
 
+@pytest.mark.parametrize("knob", ["bwd_row_index", "bwd_singles_by_bag"])
+@pytest.mark.parametrize("dim,mode", [(16, 0), (64, 1), (256, 0), (512, 1), (72, 2), (128, 2)])
+def test_bwd_variants_give_the_same_bits(H, knob, dim, mode):
+    """np_tune_set switches between ways of doing the same reduction; the gradients must not change by a bit (and are the
+    oracle's within tolerance).  Pooled modes with fp32 upstream gradients, sequence mode with bf16 ones; empty bags, a
+    popular key, and keys with a single lookup are all present."""
+    import torch
+    rng = np.random.default_rng(dim * 7 + mode)
+    seq = mode == 2
+    Bn, R = (97, 900) if seq else (3001, 2500)
+    off, keys = _bags(rng, Bn, 300 if seq else 11, R)
+    keys[rng.random(keys.shape[0]) < 0.3] = 7
+    n = keys.shape[0]
+    max_len = int(np.diff(off).max()) if seq else 1
+    if seq:
+        dY = H.wl.round_to_bf16(rng.standard_normal((Bn, max_len, dim)).astype(np.float32))
+        dYd = H.bf16_dev(dY)
+        dY_ref, dt = H.host(dYd), 1
+    else:
+        dY = rng.standard_normal((Bn, dim)).astype(np.float32)
+        dYd, dY_ref, dt = H.dev(dY), dY, 0
+    g, d = H.gpu_dedup(keys, 12)
+    unique, inverse, *_ = H.assert_dedup_equal(g, keys)
+    U = unique.shape[0]
+    _, _, _, _, uts = H.O.route(unique, 16, 1)
+    ref, ab = H.O.lookup_bwd(dY_ref, dt, dim, mode, max_len, off, inverse, U, uts, want_abs=True)
+    old = H.B.np_tune_get(knob)
+    got = {}
+    try:
+        for v in (0, 1):
+            H.B.np_tune_set(knob, v)
+            grads = H.B.np_lookup_bwd(dYd, dim, mode, max_len, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], n,
+                                      unique_to_send=H.dev(uts))
+            torch.cuda.synchronize()
+            got[v] = H.host(grads)[:U].copy()
+    finally:
+        H.B.np_tune_set(knob, old)
+    assert got[0].tobytes() == got[1].tobytes()
+    H.assert_close(got[1], ref, ab, H.RTOL_F32, f"bwd {knob} dim={dim} mode={mode}")
+
+
 @pytest.mark.parametrize("dim,Bn,mode", [(64, 1_100_000, 0), (1024, 70_000, 1)])
 def test_bwd_with_an_upstream_gradient_larger_than_the_last_level_cache(H, dim, Bn, mode):
     """Above 256 MB of dY the backward runs its tiles in the locality order (long segments sorted by relative position,
@@ -299,7 +412,7 @@ def test_bwd_with_an_upstream_gradient_larger_than_the_last_level_cache(H, dim, 
     assert torch.equal(grads[:U], grads2[:U])
     # the same in two parts: the index work first, the reduction on the prepared workspace
     ws = torch.empty(H.B.np_lookup_bwd_workspace_bytes(Bn, n, dim, mode), dtype=torch.uint8, device="cuda")
-    H.B.np_lookup_bwd_prepare(H.B.F32, dim, mode, 1, H.dev(off), n, d["occ_offsets"], d["num_unique"], ws)
+    H.B.np_lookup_bwd_prepare(H.B.F32, dim, mode, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], ws)
     grads3 = H.B.np_lookup_bwd_prepared(dYd, dim, mode, 1, H.dev(off), n, d["occ_offsets"], d["occ"], d["num_unique"], U, ws)
     torch.cuda.synchronize()
     assert torch.equal(grads[:U], grads3[:U])
@@ -617,9 +730,21 @@ def test_batch_precondition_check(H):
 
 @pytest.mark.parametrize("dim,mode,bf16", [(4, 0, False), (16, 1, False), (64, 0, False), (64, 1, True), (128, 2, True), (24, 2, True),
                                            (520, 0, False)])
-def test_bwd_in_two_parts_equals_the_single_call(H, dim, mode, bf16):
+@pytest.mark.parametrize("row_index", [0, 1])
+def test_bwd_in_two_parts_equals_the_single_call(H, dim, mode, bf16, row_index):
     """np_lookup_bwd_prepare on a second stream, ordered by an event, then np_lookup_bwd_prepared: the bits of np_lookup_bwd,
-    also when the prepared workspace is used for two different gradients in a row."""
+    also when the prepared workspace is used for two different gradients in a row; with and without the row index."""
+    import torch
+    B = H.B
+    old = B.np_tune_get("bwd_row_index")
+    B.np_tune_set("bwd_row_index", row_index)
+    try:
+        _two_parts(H, dim, mode, bf16)
+    finally:
+        B.np_tune_set("bwd_row_index", old)
+
+
+def _two_parts(H, dim, mode, bf16):
     import torch
     B = H.B
     rng = np.random.default_rng(dim * 3 + mode)
@@ -637,7 +762,7 @@ def test_bwd_in_two_parts_equals_the_single_call(H, dim, mode, bf16):
     ready = torch.cuda.Event()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        B.np_lookup_bwd_prepare(B.BF16 if bf16 else B.F32, dim, mode, max_len, offd, n, d["occ_offsets"], d["num_unique"], ws)
+        B.np_lookup_bwd_prepare(B.BF16 if bf16 else B.F32, dim, mode, max_len, offd, n, d["occ_offsets"], d["occ"], d["num_unique"], ws)
         ready.record(side)
     torch.cuda.current_stream().wait_event(ready)
     for rep in range(2):
@@ -656,13 +781,15 @@ def test_bwd_prepare_checks_its_arguments(H):
     off = torch.tensor([0, 2, 5], dtype=torch.int32, device="cuda")
     oo = torch.tensor([0, 3, 5], dtype=torch.int32, device="cuda")
     nu = torch.tensor([2], dtype=torch.int32, device="cuda")
+    oc = torch.tensor([0, 2, 4, 1, 3], dtype=torch.int32, device="cuda")
     need = B.np_lookup_bwd_workspace_bytes(2, 5, 8, 0)
     ws = torch.empty(need, dtype=torch.uint8, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
-    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == 0
-    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), nu.data_ptr(), ws.data_ptr(), need - 1, st) == -2
-    assert L.np_lookup_bwd_prepare(0, 6, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == -3
-    assert L.np_lookup_bwd_prepare(7, 8, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == -1
-    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, 0, 2, 5, oo.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == -1
-    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, off.data_ptr(), 2, 0, oo.data_ptr(), nu.data_ptr(), 0, 0, st) == 0     # no lookups
+    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), oc.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == 0
+    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), oc.data_ptr(), nu.data_ptr(), ws.data_ptr(), need - 1, st) == -2
+    assert L.np_lookup_bwd_prepare(0, 6, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), oc.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == -3
+    assert L.np_lookup_bwd_prepare(7, 8, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), oc.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == -1
+    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, 0, 2, 5, oo.data_ptr(), oc.data_ptr(), nu.data_ptr(), ws.data_ptr(), need, st) == -1
+    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, off.data_ptr(), 2, 0, oo.data_ptr(), oc.data_ptr(), nu.data_ptr(), 0, 0, st) == 0     # no lookups
+    assert L.np_lookup_bwd_prepare(0, 8, 0, 1, off.data_ptr(), 2, 5, oo.data_ptr(), 0, nu.data_ptr(), ws.data_ptr(), need, st) == -1    # no occ
     torch.cuda.synchronize()
