@@ -279,6 +279,22 @@ def main() -> int:
     torch.cuda.synchronize()
     route_alone_ms = r0.elapsed_time(r1) / 10
 
+    # ---- bandwidth yardstick: a plain 16-byte copy kernel, 2 GiB each way
+    words = 2 ** 31
+    src = torch.empty(words, dtype=torch.uint8, device=dev)
+    dst = torch.empty(words, dtype=torch.uint8, device=dev)
+    B.np_util_stream_copy(dst, src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        B.np_util_stream_copy(dst, src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * words * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+
+
     line = {
         "metric": "embedding lookups/sec (fwd+bwd+update) and achieved HBM GB/s on 1 MI355X",
         "value": value,
@@ -318,6 +334,7 @@ def main() -> int:
         "streams": "np_route runs on a second stream beside np_lookup_fwd; its event times in `kernels` / `calls` include "
                    "that sharing, calls.np_route.alone_ms is its time with the GPU to itself",
         "ms_per_step_with_events_on_every_launch": ms_per_step_all_events,
+        "stream_copy_GBps": copy_gbs,
         "input_generation_s": gen_s,
     }
     line["calls"]["np_route"]["alone_ms"] = route_alone_ms
@@ -350,6 +367,30 @@ def extras(line, args, cfg, wl, B, torch, dev, batches, stats, dbatch, dd, rr, d
     line["forward_through_inverse_step"] = {
         "ms_per_step": inv_ms, "lookups_per_s": rate(inv_ms),
         "what": "np_lookup_fwd(list_keys = unique, idx = inverse): what a requester does with the owners' answers; no events"}
+
+    # ---- the forward by key does not need np_dedup's result: it can run beside np_dedup and np_route on the second stream
+    ev_begin, ev_fwd = torch.cuda.Event(), torch.cuda.Event()
+
+    def step_fwd_beside_dedup(i: int) -> None:
+        bt = dbatch[i % 2]
+        n = bt["n"]
+        main_stream = torch.cuda.current_stream()
+        ev_begin.record(main_stream)            # after the previous step's update
+        side_stream.wait_event(ev_begin)
+        with torch.cuda.stream(side_stream):
+            fwd_call(table, bt["keys"], None, bt["off"], n, cfg.mode, max_len, out_dtype, out=out)
+            ev_fwd.record(side_stream)
+        B.np_dedup(bt["keys"], cfg.key_bits, out=dd, ws=ws_d)
+        B.np_route(dd["unique"], dd["num_unique"], cap, S, cfg.shard_fn, out=rr, ws=ws_r)
+        main_stream.wait_event(ev_fwd)          # the dense model would sit here
+        B.np_lookup_bwd(bt["dY"], D, cfg.mode, max_len, bt["off"], n, dd["occ_offsets"], dd["occ"], dd["num_unique"], cap,
+                        unique_to_send=rr["unique_to_send"], grads=grads, ws=ws_b)
+        adagrad_call(table, state, rr["send_keys"], grads, dd["num_unique"], cap, cfg.lr, cfg.eps)
+
+    ovl_ms = timed_loop(step_fwd_beside_dedup, K)
+    line["forward_beside_dedup_step"] = {
+        "ms_per_step": ovl_ms, "lookups_per_s": rate(ovl_ms),
+        "what": "np_lookup_fwd (by key) on the second stream beside np_dedup + np_route on the first; backward and update after both; no events"}
 
     # ---- a worker that reads its own table by key needs no inverse map at all: np_dedup without it
     local_ms = timed_loop(lambda i: step(i, want_inverse=False), K)
@@ -481,21 +522,6 @@ def extras(line, args, cfg, wl, B, torch, dev, batches, stats, dbatch, dd, rr, d
     line["hip_graph_replay"] = {"ms_per_step": graph_ms, "lookups_per_s": rate(graph_ms)}
     del graphs
 
-    # ---- bandwidth yardstick: a plain 16-byte copy kernel, 2 GiB each way
-    words = 2 ** 31
-    src = torch.empty(words, dtype=torch.uint8, device=dev)
-    dst = torch.empty(words, dtype=torch.uint8, device=dev)
-    B.np_util_stream_copy(dst, src)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(5):
-        B.np_util_stream_copy(dst, src)
-    e1.record()
-    torch.cuda.synchronize()
-    line["stream_copy_GBps"] = 2 * words * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del src, dst
-
     # ---- gather yardstick: random 256-byte row reads with the row kernels' access pattern, by working-set size (what L2,
     # the last-level cache and HBM deliver to a gather on this GPU; the table itself is the source)
     if not lowp_table and table.numel() >= 64 * 4096:
@@ -503,6 +529,7 @@ def extras(line, args, cfg, wl, B, torch, dev, batches, stats, dbatch, dd, rr, d
         rows_total = flat.numel() // 64
         n_g = 32 << 20
         sink = torch.empty((n_g // 64, 64), dtype=torch.float32, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         gy = {}
         for label, rows in (("2MB_L2", 8192), ("128MB_last_level_cache", 1 << 19), ("1GB", 1 << 22), ("whole_table_HBM", rows_total)):
             rows = min(rows, rows_total, (1 << 32) - 1)

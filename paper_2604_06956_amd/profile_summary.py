@@ -26,6 +26,9 @@ FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
 SHORT = (("bwd_main_kernel", "bwd_main"), ("bwd_fixup_kernel", "bwd_fixup"), ("bwd_prepare_kernel", "bwd_prepare"),
          ("fwd_pool", "fwd_pool"), ("fwd_seq", "fwd_seq"), ("fwd_rows", "fwd_rows"), ("adagrad_kernel", "sparse_adagrad"),
          ("dedup_emit", "dedup_emit"), ("dedup_count_heads", "dedup_count_heads"), ("dedup_counts", "dedup_counts"),
+         ("dedup_tile_heads", "dedup_tile_heads"), ("dedup_tile_scan", "dedup_tile_scan"),
+         ("part_scatter_kernel<np::EmitOrder", "dedup_order_scatter"), ("part_hist_kernel<np::EmitOrder", "dedup_order_hist"),
+         ("bwd_rows", "bwd_rows"), ("bwd_single", "bwd_single"), ("gather_rate", "gather_rate"),
          ("part_scatter_kernel<np::Sort", "dedup_sort_scatter"), ("part_hist_kernel<np::Sort", "dedup_sort_hist"),
          ("part_scatter_kernel<np::Route", "route_scatter"), ("part_hist_kernel<np::Route", "route_hist"),
          ("part_scatter_kernel<np::TileOrder", "bwd_order_scatter"), ("part_hist_kernel<np::TileOrder", "bwd_order_hist"),
