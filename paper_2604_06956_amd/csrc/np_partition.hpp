@@ -31,7 +31,12 @@ constexpr int kPartWaves = kPartThreads / kWave;
 constexpr int kPartIPT = NP_PART_IPT;
 constexpr int kPartTile = kPartThreads * kPartIPT;
 static_assert(kPartIPT * kWave <= 65535, "per-wave digit counters are 16 bits wide");
-static_assert((kPartWaves * 2) % 16 == 0, "the per-wave 16-bit counters of one bin fill whole 16-byte words");
+// The 16-bit per-wave counters of one bin lie side by side and are scanned through one wide LDS access per kCntRowWaves waves.
+constexpr int kCntRowWaves = kPartWaves % 8 == 0 ? 8 : 4;
+static_assert(kPartWaves % kCntRowWaves == 0, "the per-wave 16-bit counters of one bin fill whole 8- or 16-byte words");
+struct __align__(kCntRowWaves * 2) CntRow {
+    uint32_t w[kCntRowWaves / 2];
+};
 constexpr int kPartMaxBins = 4096;
 #ifndef NP_TARGET_CHUNKS
 #define NP_TARGET_CHUNKS 512  // two blocks on each of the 256 CUs: 384, 640, 768 and 1024 leave a ragged last round
@@ -72,10 +77,23 @@ __host__ __device__ __forceinline__ size_t part_fixed_lds_bytes(int bins) {
     return (3 * sizeof(uint32_t) * static_cast<size_t>(bins) + 64 + 15) / 16 * 16;
 }
 
+// The low kMaskBits bits of a digit are matched through a per-wave table of 64-bit lane masks in LDS (one OR, one read and
+// one clearing write per item) instead of one ballot per bit; only the bits above them are matched with ballots.
+#ifndef NP_PART_MASK_BITS
+#define NP_PART_MASK_BITS 8
+#endif
+constexpr int kMaskBits = NP_PART_MASK_BITS;
+constexpr int kMaskSlots = 1 << kMaskBits;
+
+__host__ __device__ __forceinline__ size_t part_cnt_bytes(int bins) {  // per-wave digit counters, 16-byte rounded
+    return (sizeof(uint16_t) * kPartWaves * static_cast<size_t>(bins) + 15) / 16 * 16;
+}
+
 template <typename KeyT>
 inline size_t part_scatter_lds_bytes(int bins, bool stage_digit) {
     const size_t fixed = part_fixed_lds_bytes(bins);
-    const size_t cnt = align_up(sizeof(uint16_t) * kPartWaves * bins, 16);  // a wave ranks kPartIPT * 64 <= 65535 items
+    // a wave ranks kPartIPT * 64 <= 65535 items; the lane-mask tables lie behind the counters
+    const size_t cnt = part_cnt_bytes(bins) + (kMaskBits > 0 ? sizeof(uint64_t) * kPartWaves * kMaskSlots : 0);
     size_t stage = (sizeof(KeyT) + sizeof(uint32_t)) * kPartTile;
     if (stage_digit) stage += sizeof(uint16_t) * kPartTile;
     return fixed + (cnt > stage ? cnt : stage);
@@ -199,7 +217,8 @@ part_colscan_kernel(uint32_t* __restrict__ H, int num_chunks, int bins, uint32_t
 
 // Measured and not taken (three sort passes over 42 M items, 0.95 ms as it stands): the digit width as a template
 // argument so that the ballot loop unrolls (1.02 ms), the per-bin scan over the waves with all reads issued before the
-// writes (1.09 ms).
+// writes (1.09 ms), three blocks per CU instead of two by capping the kernel at 80 registers (amdgpu_waves_per_eu 6: the
+// ranks and the prefetched tile no longer fit and spill, 1.80 ms with 768 chunks, 2.05 ms with 512).
 template <class P>
 __global__ void __launch_bounds__(kPartThreads)
 part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, int nbits, ChunkPlan plan,
@@ -212,11 +231,13 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
     uint32_t* btot = binstart + bins;
     int* scan_tmp = reinterpret_cast<int*>(btot + bins);  // 16 ints
     unsigned char* un = smem_raw + part_fixed_lds_bytes(bins);
-    // Per-wave digit counters [waves][bins], aliased with the staging area.  Plain (not volatile) accesses: a volatile LDS
+    // Per-wave digit counters [bins][waves] and, behind them, the per-wave lane-mask tables, both aliased with the staging area.  Plain (not volatile) accesses: a volatile LDS
     // access makes the compiler wait for every outstanding global load as well, which would drain the prefetch of the
     // next tile at the first counter access.  Where lanes of a wave hand values to each other through a counter, a
     // compiler-only fence keeps the accesses in program order; the wave's LDS operations execute in that order.
     uint16_t* cnt = reinterpret_cast<uint16_t*>(un);
+    unsigned long long* wmask = reinterpret_cast<unsigned long long*>(un + part_cnt_bytes(bins)) + (threadIdx.x / kWave) * kMaskSlots;
+    const unsigned long long lanebit = 1ull << (threadIdx.x % kWave);
     KeyT* skey = reinterpret_cast<KeyT*>(un);
     uint32_t* sval = reinterpret_cast<uint32_t*>(skey + kPartTile);
     uint16_t* sdig = reinterpret_cast<uint16_t*>(sval + kPartTile);
@@ -274,8 +295,9 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
     for (int64_t tile_base = lo; tile_base < hi; tile_base += kPartTile) {
         const int tile_count = hi - tile_base < kPartTile ? static_cast<int>(hi - tile_base) : kPartTile;
         {
-            uint4* z = reinterpret_cast<uint4*>(un);  // kPartWaves * bins halfwords = bins * (kPartWaves / 8) 16-byte words
-            for (int i = tid; i < bins * (kPartWaves * 2 / 16); i += kPartThreads) z[i] = make_uint4(0u, 0u, 0u, 0u);
+            uint4* z = reinterpret_cast<uint4*>(un);  // counters (16-byte rounded) and mask tables, contiguous
+            const int zn = static_cast<int>((part_cnt_bytes(bins) + (kMaskBits > 0 ? sizeof(uint64_t) * kPartWaves * kMaskSlots : 0)) / 16);
+            for (int i = tid; i < zn; i += kPartThreads) z[i] = make_uint4(0u, 0u, 0u, 0u);
         }
         lds_barrier();
 
@@ -298,27 +320,59 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
         for (int i = 0; i < kPartIPT; ++i) {
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
             const bool valid = idx < tile_count;
-            const uint64_t peers = match_any(d[i], nbits, valid);
-            uint16_t* ctr = cnt + w * bins + d[i];
-            const uint32_t pre = *ctr;
-            const uint64_t below = peers & lt;
-            r[i] = pre + __popcll(below);
-            compiler_fence();
-            __builtin_amdgcn_wave_barrier();
-            if (valid && below == 0) *ctr = static_cast<uint16_t>(pre + __popcll(peers));
-            compiler_fence();
-            __builtin_amdgcn_wave_barrier();
+            uint64_t peers;
+            if (kMaskBits > 0) {
+                // every lane sets its bit in the slot of its digit's low bits, then reads the slot back: the lanes whose
+                // digits agree in those bits.  A wave's LDS operations execute in program order, so the read sees all 64
+                // ORs; the lowest peer clears the slot for the next round.
+                unsigned long long* slot = wmask + (d[i] & (kMaskSlots - 1));
+                if (valid) atomicOr(slot, lanebit);
+                compiler_fence();
+                __builtin_amdgcn_wave_barrier();
+                peers = *slot;
+                if (nbits > kMaskBits) peers &= match_any(d[i] >> kMaskBits, nbits - kMaskBits, valid);
+                uint16_t* ctr = cnt + d[i] * kPartWaves + w;
+                const uint32_t pre = *ctr;
+                const uint64_t below = peers & lt;
+                r[i] = pre + __popcll(below);
+                compiler_fence();
+                __builtin_amdgcn_wave_barrier();
+                if (valid && below == 0) {
+                    *ctr = static_cast<uint16_t>(pre + __popcll(peers));
+                    *slot = 0;
+                }
+                compiler_fence();
+                __builtin_amdgcn_wave_barrier();
+            } else {
+                peers = match_any(d[i], nbits, valid);
+                uint16_t* ctr = cnt + d[i] * kPartWaves + w;
+                const uint32_t pre = *ctr;
+                const uint64_t below = peers & lt;
+                r[i] = pre + __popcll(below);
+                compiler_fence();
+                __builtin_amdgcn_wave_barrier();
+                if (valid && below == 0) *ctr = static_cast<uint16_t>(pre + __popcll(peers));
+                compiler_fence();
+                __builtin_amdgcn_wave_barrier();
+            }
         }
         lds_barrier();
-        // per bin: exclusive scan over the waves, total of the tile
+        // per bin: exclusive scan over the waves, total of the tile.  The counters of one bin lie side by side
+        // ([bin][wave], 16 bytes per 8 waves): one wide read, the prefixes in registers, one wide write.
         int local = 0;
         for (int b = b0; b < b1; ++b) {
+            CntRow* row = reinterpret_cast<CntRow*>(cnt + b * kPartWaves);
             uint32_t s = 0;
 #pragma unroll
-            for (int ww = 0; ww < kPartWaves; ++ww) {
-                const uint32_t t = cnt[ww * bins + b];
-                cnt[ww * bins + b] = static_cast<uint16_t>(s);
-                s += t;
+            for (int q = 0; q < kPartWaves / kCntRowWaves; ++q) {
+                CntRow x = row[q];
+#pragma unroll
+                for (int j = 0; j < kCntRowWaves / 2; ++j) {
+                    const uint32_t lo16 = x.w[j] & 0xffffu, hi16 = x.w[j] >> 16;
+                    x.w[j] = s | ((s + lo16) << 16);  // both prefixes stay below 65536 (a tile has fewer items)
+                    s += lo16 + hi16;
+                }
+                row[q] = x;
             }
             btot[b] = s;
             local += static_cast<int>(s);
@@ -333,7 +387,7 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
 #pragma unroll
         for (int i = 0; i < kPartIPT; ++i) {
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
-            const uint32_t in_bin = static_cast<uint32_t>(cnt[w * bins + d[i]]) + r[i];
+            const uint32_t in_bin = static_cast<uint32_t>(cnt[d[i] * kPartWaves + w]) + r[i];
             r[i] = binstart[d[i]] + in_bin;  // position inside the reordered tile
             if (idx < tile_count && gofs[d[i]] + in_bin < static_cast<uint32_t>(n)) pol.placed(tile_base + idx, gofs[d[i]] + in_bin);
         }

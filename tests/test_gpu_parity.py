@@ -115,9 +115,31 @@ def tile_ordered_emit(H):
     H.B.np_tune_set("emit_order_min_n", old)
 
 
-@pytest.mark.parametrize("case", DEDUP_CASES + ["tile1024_minus_1", "tile1024_exact", "tile1024_plus_1", "hot_runs"])
+@pytest.mark.parametrize("case", DEDUP_CASES + ["tile1024_minus_1", "tile1024_exact", "tile1024_plus_1", "hot_runs",
+                                                "hot_runs_wide_keys", "counts_around_33", "keys_34_each"])
 def test_dedup_bit_exact_with_the_tile_ordered_inverse_map(H, tile_ordered_emit, case):
-    if case.startswith("tile1024"):
+    if case == "hot_runs_wide_keys":    # 64-bit sort keys: popular keys beside cold ones
+        rng = np.random.default_rng(7)
+        keys = rng.integers(0, 1 << 40, size=300_001).astype(np.int64)
+        pick = rng.random(keys.size)
+        keys[pick < 0.25] = (1 << 39) + 5
+        keys[(pick >= 0.25) & (pick < 0.40)] = 3
+        hot = rng.integers(0, 1 << 40, size=500)
+        sel = (pick >= 0.40) & (pick < 0.70)
+        keys[sel] = hot[rng.integers(0, hot.size, size=int(sel.sum()))]
+        bits = 40
+    elif case == "counts_around_33":    # keys with 31 .. 35 lookups each, shuffled
+        rng = np.random.default_rng(33)
+        reps = np.repeat(np.arange(31, 36), 400)
+        keys = np.repeat(rng.permutation(1 << 20)[:reps.size].astype(np.int64), reps)
+        keys = keys[rng.permutation(keys.size)]
+        bits = 20
+    elif case == "keys_34_each":    # 100 000 keys with 34 lookups each, shuffled: no segment fills a tile, every tile holds ~30 heads
+        rng = np.random.default_rng(34)
+        keys = np.repeat(np.arange(100_000, dtype=np.int64) * 7919 % (1 << 24), 34)
+        keys = keys[rng.permutation(keys.size)]
+        bits = 24
+    elif case.startswith("tile1024"):
         rng = np.random.default_rng(len(case))
         keys = rng.integers(0, 300, size=1024 * 3 + {"minus_1": -1, "exact": 0, "plus_1": 1}[case.split("_", 1)[1]]).astype(np.int64)
         bits = 9
