@@ -80,6 +80,47 @@ struct SortNextPolicy {
     __device__ __forceinline__ void placed(int64_t, uint32_t) const {}
 };
 
+// 32-bit sort keys travel between the passes as (key, position) pairs in ONE array: a run of items that a tile appends to
+// a bin is then one contiguous piece instead of one piece in each of two arrays.  The scatter passes are bound by the number
+// of such pieces (every one leaves the CU, and mostly L2, as a partial line of its own), not by their bytes.  The last pass
+// writes the sorted keys and the positions (the occurrence list, an output) as arrays of their own.
+template <bool FIRST, bool LAST>
+struct SortPairPolicy {
+    using KeyT = uint32_t;
+    static constexpr bool kStageDigit = false;
+    const int64_t* keys;  // FIRST: the batch
+    const uint2* in;      // otherwise: the previous pass's pairs
+    uint2* out;           // not LAST
+    uint32_t* out_k;      // LAST
+    uint32_t* out_v;
+    int shift;
+    uint32_t mask;
+    __device__ __forceinline__ uint32_t load_key(int64_t i) const {
+        if (FIRST) return static_cast<uint32_t>(keys[i]);
+        return in[i].x;
+    }
+    __device__ __forceinline__ void load(int64_t i, uint32_t& k, uint32_t& v) const {
+        if (FIRST) {
+            k = static_cast<uint32_t>(keys[i]);
+            v = static_cast<uint32_t>(i);
+        } else {
+            const uint2 t = in[i];
+            k = t.x;
+            v = t.y;
+        }
+    }
+    __device__ __forceinline__ uint32_t digit(uint32_t k) const { return (k >> shift) & mask; }
+    __device__ __forceinline__ void store(uint32_t dst, uint32_t k, uint32_t v) const {
+        if (LAST) {
+            out_k[dst] = k;
+            out_v[dst] = v;
+        } else {
+            out[dst] = make_uint2(k, v);
+        }
+    }
+    __device__ __forceinline__ void placed(int64_t, uint32_t) const {}
+};
+
 // ---- after the sort: segment heads -> ranks ------------------------------------------------------------
 
 #ifndef NP_HEAD_THREADS
@@ -428,10 +469,9 @@ inline DedupWs dedup_ws_layout(int32_t n, int32_t key_bits) {
     w.plan = make_chunk_plan(n);
     w.passes = make_pass_plan(key_bits);
     w.max_bins = 1 << w.passes.bits[0];
-    const size_t ksz = key_bits <= 32 ? 4 : 8;
-    w.key_bytes = align_up(ksz * static_cast<size_t>(n), 256);
-    w.total = 2 * w.key_bytes                                                 // key ping-pong
-              + align_up(4 * static_cast<size_t>(n), 256)                     // second position buffer
+    // 32-bit sort keys: two buffers of (key, position) pairs; 64-bit: two key buffers and a second position buffer
+    w.key_bytes = align_up(8 * static_cast<size_t>(n), 256);
+    w.total = 2 * w.key_bytes + (key_bits <= 32 ? 0 : align_up(4 * static_cast<size_t>(n), 256))
               + align_up(4 * part_hist_elems(w.plan, w.max_bins), 256)        // histogram matrix
               + align_up(4 * static_cast<size_t>(w.max_bins), 256)            // bin totals
               + align_up(4 * static_cast<size_t>(kEmitChunks), 256);          // heads per chunk
@@ -448,32 +488,58 @@ int dedup_impl(const int64_t* keys, int32_t n, int32_t key_bits, int64_t* unique
                int32_t* occ_offsets, int32_t* occ, int32_t* d_num_unique, void* ws, hipStream_t stream) {
     const DedupWs L = dedup_ws_layout(n, key_bits);
     WsCursor cur(ws);
-    K* kbuf[2] = {cur.take<K>(L.key_bytes / sizeof(K)), cur.take<K>(L.key_bytes / sizeof(K))};
-    uint32_t* vtmp = cur.take<uint32_t>(n);
+    unsigned char* buf[2] = {cur.take<unsigned char>(L.key_bytes), cur.take<unsigned char>(L.key_bytes)};
+    uint32_t* vtmp = sizeof(K) == 4 ? nullptr : cur.take<uint32_t>(n);
     uint32_t* H = cur.take<uint32_t>(part_hist_elems(L.plan, L.max_bins));
     uint32_t* bin_total = cur.take<uint32_t>(L.max_bins);
     int* chunk_heads = cur.take<int>(kEmitChunks);
     uint32_t* vocc = reinterpret_cast<uint32_t*>(occ);
 
-    // payload buffers alternate so that the last pass lands in occ
     const int P = L.passes.passes;
-    for (int p = 0; p < P; ++p) {
-        const int bits = L.passes.bits[p], bins = 1 << bits;
-        const uint32_t mask = static_cast<uint32_t>(bins - 1);
-        uint32_t* vout = ((P - 1 - p) % 2 == 0) ? vocc : vtmp;
-        K* kout = kbuf[p % 2];
-        if (p == 0) {
-            SortFirstPolicy<K> pol{keys, kout, vout, L.passes.shift[p], mask};
-            run_partition_pass(pol, n, nullptr, bins, bits, L.plan, H, bin_total, nullptr, nullptr, stream,
-                               "dedup_sort_hist", "dedup_sort_colscan", "dedup_sort_scatter");
-        } else {
-            const uint32_t* vin = ((P - p) % 2 == 0) ? vocc : vtmp;
-            SortNextPolicy<K> pol{kbuf[(p - 1) % 2], vin, kout, vout, L.passes.shift[p], mask};
-            run_partition_pass(pol, n, nullptr, bins, bits, L.plan, H, bin_total, nullptr, nullptr, stream,
-                               "dedup_sort_hist", "dedup_sort_colscan", "dedup_sort_scatter");
+    const K* sorted;
+    if constexpr (sizeof(K) == 4) {
+        // pass p writes pairs into buf[p % 2]; the last pass reads buf[(P - 2) % 2] and puts the sorted keys into the other one
+        uint2* pairs[2] = {reinterpret_cast<uint2*>(buf[0]), reinterpret_cast<uint2*>(buf[1])};
+        uint32_t* sorted_out = reinterpret_cast<uint32_t*>(buf[(P - 1) % 2]);
+        for (int p = 0; p < P; ++p) {
+            const int bits = L.passes.bits[p], bins = 1 << bits, shift = L.passes.shift[p];
+            const uint32_t mask = static_cast<uint32_t>(bins - 1);
+            const uint2* in = p > 0 ? pairs[(p - 1) % 2] : nullptr;
+            const bool first = p == 0, last = p == P - 1;
+#define NP_SORT_PASS(F, Z)                                                                                                   \
+    do {                                                                                                                     \
+        SortPairPolicy<F, Z> pol{keys, in, pairs[p % 2], sorted_out, vocc, shift, mask};                                      \
+        run_partition_pass(pol, n, nullptr, bins, bits, L.plan, H, bin_total, nullptr, nullptr, stream, "dedup_sort_hist",   \
+                           "dedup_sort_colscan", "dedup_sort_scatter");                                                      \
+    } while (0)
+            if (first && last) NP_SORT_PASS(true, true);
+            else if (first) NP_SORT_PASS(true, false);
+            else if (last) NP_SORT_PASS(false, true);
+            else NP_SORT_PASS(false, false);
+#undef NP_SORT_PASS
         }
+        sorted = sorted_out;
+    } else {
+        K* kbuf[2] = {reinterpret_cast<K*>(buf[0]), reinterpret_cast<K*>(buf[1])};
+        // payload buffers alternate so that the last pass lands in occ
+        for (int p = 0; p < P; ++p) {
+            const int bits = L.passes.bits[p], bins = 1 << bits;
+            const uint32_t mask = static_cast<uint32_t>(bins - 1);
+            uint32_t* vout = ((P - 1 - p) % 2 == 0) ? vocc : vtmp;
+            K* kout = kbuf[p % 2];
+            if (p == 0) {
+                SortFirstPolicy<K> pol{keys, kout, vout, L.passes.shift[p], mask};
+                run_partition_pass(pol, n, nullptr, bins, bits, L.plan, H, bin_total, nullptr, nullptr, stream,
+                                   "dedup_sort_hist", "dedup_sort_colscan", "dedup_sort_scatter");
+            } else {
+                const uint32_t* vin = ((P - p) % 2 == 0) ? vocc : vtmp;
+                SortNextPolicy<K> pol{kbuf[(p - 1) % 2], vin, kout, vout, L.passes.shift[p], mask};
+                run_partition_pass(pol, n, nullptr, bins, bits, L.plan, H, bin_total, nullptr, nullptr, stream,
+                                   "dedup_sort_hist", "dedup_sort_colscan", "dedup_sort_scatter");
+            }
+        }
+        sorted = kbuf[(P - 1) % 2];
     }
-    const K* sorted = kbuf[(P - 1) % 2];
     if (inverse && n >= tune_get(kTuneEmitOrderMinN)) {
         const int ord_tiles = static_cast<int>((static_cast<int64_t>(n) + kOrdTile - 1) / kOrdTile);
         int32_t* tile_heads = cur.take<int32_t>(ord_tiles);

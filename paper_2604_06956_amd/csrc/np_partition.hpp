@@ -89,14 +89,51 @@ __host__ __device__ __forceinline__ size_t part_cnt_bytes(int bins) {  // per-wa
     return (sizeof(uint16_t) * kPartWaves * static_cast<size_t>(bins) + 15) / 16 * 16;
 }
 
+__host__ __device__ __forceinline__ size_t part_rank_bytes(int bins) {  // counters and, behind them, the lane-mask tables
+    return part_cnt_bytes(bins) + (kMaskBits > 0 ? sizeof(unsigned long long) * kPartWaves * kMaskSlots : 0);
+}
+
+template <typename KeyT>
+inline size_t part_stage_bytes(bool stage_digit) {
+    return (sizeof(KeyT) + sizeof(uint32_t) + (stage_digit ? sizeof(uint16_t) : 0)) * kPartTile;
+}
+
+// The staging area of the reordered tile gets LDS of its own when two blocks per CU still fit (fewer barriers per tile:
+// the counters of the next tile are cleared while this one is staged); otherwise it shares the counters' storage.
+constexpr size_t kPartLdsPerBlock = 80 * 1024;  // half of a CU's 160 KB
+template <typename KeyT>
+inline bool part_stage_aliased(int bins, bool stage_digit) {
+    return part_fixed_lds_bytes(bins) + part_rank_bytes(bins) + part_stage_bytes<KeyT>(stage_digit) > kPartLdsPerBlock;
+}
+
 template <typename KeyT>
 inline size_t part_scatter_lds_bytes(int bins, bool stage_digit) {
     const size_t fixed = part_fixed_lds_bytes(bins);
-    // a wave ranks kPartIPT * 64 <= 65535 items; the lane-mask tables lie behind the counters
-    const size_t cnt = part_cnt_bytes(bins) + (kMaskBits > 0 ? sizeof(uint64_t) * kPartWaves * kMaskSlots : 0);
-    size_t stage = (sizeof(KeyT) + sizeof(uint32_t)) * kPartTile;
-    if (stage_digit) stage += sizeof(uint16_t) * kPartTile;
-    return fixed + (cnt > stage ? cnt : stage);
+    const size_t rank = part_rank_bytes(bins);  // a wave ranks kPartIPT * 64 <= 65535 items
+    const size_t stage = part_stage_bytes<KeyT>(stage_digit);
+    if (!part_stage_aliased<KeyT>(bins, stage_digit)) return fixed + rank + stage;
+    return fixed + (rank > stage ? rank : stage);
+}
+
+// The counters of bin d lie side by side, wave w at column w ^ (cnt_swizzle(d) << 1): without the swizzle the lanes of one
+// wave, which differ in d only, would all fall into a quarter of the LDS banks.
+constexpr int kCntSwzShift = kPartWaves >= 16 ? 2 : (kPartWaves == 8 ? 3 : 4);
+constexpr int kCntSwzMask = kCntRowWaves / 2 - 1;
+__device__ __forceinline__ uint32_t cnt_swizzle(uint32_t d) { return (d >> kCntSwzShift) & kCntSwzMask; }
+__device__ __forceinline__ uint32_t cnt_index(uint32_t d, int w) { return d * kPartWaves + (static_cast<uint32_t>(w) ^ (cnt_swizzle(d) << 1)); }
+__device__ __forceinline__ void cnt_row_permute(CntRow& x, uint32_t swz) {  // its own inverse
+    if (kCntRowWaves == 8) {
+        if (swz & 1u) {
+            uint32_t t = x.w[0]; x.w[0] = x.w[1]; x.w[1] = t;
+            t = x.w[2 % (kCntRowWaves / 2)]; x.w[2 % (kCntRowWaves / 2)] = x.w[3 % (kCntRowWaves / 2)]; x.w[3 % (kCntRowWaves / 2)] = t;
+        }
+        if (swz & 2u) {
+            uint32_t t = x.w[0]; x.w[0] = x.w[2 % (kCntRowWaves / 2)]; x.w[2 % (kCntRowWaves / 2)] = t;
+            t = x.w[1]; x.w[1] = x.w[3 % (kCntRowWaves / 2)]; x.w[3 % (kCntRowWaves / 2)] = t;
+        }
+    } else if (swz & 1u) {
+        const uint32_t t = x.w[0]; x.w[0] = x.w[1]; x.w[1] = t;
+    }
 }
 
 // Lanes of the wave holding the same digit as this lane (only lanes with valid == true take part).
@@ -139,12 +176,24 @@ part_hist_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, Chunk
     if (hi > n) hi = n;
     constexpr int kBatch = 8;  // independent loads in flight per thread
     const int lane = threadIdx.x % kWave;
-    for (int64_t base = lo; base < hi; base += static_cast<int64_t>(kHistThreads) * kBatch) {
-        typename P::KeyT k[kBatch];
+    // the next batch is requested before the current one is counted (unconditional loads; past the end: the chunk's last
+    // item, masked below)
+    typename P::KeyT k[kBatch], kn[kBatch];
 #pragma unroll
-        for (int q = 0; q < kBatch; ++q) {  // unconditional loads (past the end: the chunk's last item, masked below)
-            const int64_t i = base + q * kHistThreads + threadIdx.x;
-            k[q] = pol.load_key(i < hi ? i : hi - 1);
+    for (int q = 0; q < kBatch; ++q) kn[q] = typename P::KeyT(0);
+    if (lo < hi) {  // uniform
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            const int64_t i = lo + q * kHistThreads + threadIdx.x;
+            kn[q] = pol.load_key(i < hi ? i : hi - 1);
+        }
+    }
+    for (int64_t base = lo; base < hi; base += static_cast<int64_t>(kHistThreads) * kBatch) {
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            k[q] = kn[q];
+            const int64_t i = base + static_cast<int64_t>(kHistThreads) * kBatch + q * kHistThreads + threadIdx.x;
+            kn[q] = pol.load_key(i < hi ? i : hi - 1);
         }
 #pragma unroll
         for (int q = 0; q < kBatch; ++q) {
@@ -215,32 +264,53 @@ part_colscan_kernel(uint32_t* __restrict__ H, int num_chunks, int bins, uint32_t
     }
 }
 
-// Measured and not taken (three sort passes over 42 M items, 0.95 ms as it stands): the digit width as a template
-// argument so that the ballot loop unrolls (1.02 ms), the per-bin scan over the waves with all reads issued before the
-// writes (1.09 ms), three blocks per CU instead of two by capping the kernel at 80 registers (amdgpu_waves_per_eu 6: the
-// ranks and the prefetched tile no longer fit and spill, 1.80 ms with 768 chunks, 2.05 ms with 512).
-template <class P>
+// One exclusive scan of an int per thread across the block with a single barrier inside; `smem` (kPartWaves ints) must not
+// be in use by a previous call any more (here: several barriers lie between two calls).
+__device__ __forceinline__ int part_block_scan(int v, int* smem, int* total) {
+    const int w = threadIdx.x / kWave;
+    const int inc = wave_incl_scan(v);
+    if (__lane_id() == kWave - 1) smem[w] = inc;
+    lds_barrier();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < kPartWaves; ++i) {
+        const int s = smem[i];
+        if (i < w) base += s;
+        tot += s;
+    }
+    *total = tot;
+    return base + inc - v;
+}
+
+// Measured and not taken (three sort passes over 42 M items): the digit width as a template argument so that the ballot
+// loop unrolls (1.02 ms against 0.95), three blocks per CU instead of two by capping the kernel at 80 registers
+// (amdgpu_waves_per_eu 6: the ranks and the prefetched tile no longer fit and spill, 1.80 ms with 768 chunks, 2.05 ms with
+// 512), blocks of 256 threads, four per CU (tiles of 2048 items make runs half as long: 1.13 ms against 0.90).
+template <class P, bool ALIAS>
 __global__ void __launch_bounds__(kPartThreads)
 part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, int nbits, ChunkPlan plan,
                     const uint32_t* __restrict__ H, const uint32_t* __restrict__ bin_total,
                     int32_t* __restrict__ totals_out /* nullable: [bins] */, int32_t* __restrict__ offsets_out /* nullable: [bins+1] */) {
     using KeyT = typename P::KeyT;
+    constexpr bool kPairs = sizeof(KeyT) == 4;  // 32-bit keys are staged side by side with their payload: one 8-byte access
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    uint32_t* gofs = reinterpret_cast<uint32_t*>(smem_raw);
-    uint32_t* binstart = gofs + bins;
-    uint32_t* btot = binstart + bins;
-    int* scan_tmp = reinterpret_cast<int*>(btot + bins);  // 16 ints
+    uint32_t* gofs = reinterpret_cast<uint32_t*>(smem_raw);  // where the chunk's next item of every bin goes
+    uint32_t* binstart = gofs + bins;                         // first slot of every bin in the reordered tile
+    uint32_t* delta = binstart + bins;                        // the tile's count per bin, then gofs - binstart of this tile
+    int* scan_tmp = reinterpret_cast<int*>(delta + bins);     // 16 ints
     unsigned char* un = smem_raw + part_fixed_lds_bytes(bins);
-    // Per-wave digit counters [bins][waves] and, behind them, the per-wave lane-mask tables, both aliased with the staging area.  Plain (not volatile) accesses: a volatile LDS
-    // access makes the compiler wait for every outstanding global load as well, which would drain the prefetch of the
-    // next tile at the first counter access.  Where lanes of a wave hand values to each other through a counter, a
+    // Per-wave digit counters [bins][waves] and, behind them, the per-wave lane-mask tables.  Plain (not volatile) accesses:
+    // a volatile LDS access makes the compiler wait for every outstanding global load as well, which would drain the
+    // prefetch of the next tile at the first counter access.  Where lanes of a wave hand values to each other through LDS, a
     // compiler-only fence keeps the accesses in program order; the wave's LDS operations execute in that order.
     uint16_t* cnt = reinterpret_cast<uint16_t*>(un);
     unsigned long long* wmask = reinterpret_cast<unsigned long long*>(un + part_cnt_bytes(bins)) + (threadIdx.x / kWave) * kMaskSlots;
     const unsigned long long lanebit = 1ull << (threadIdx.x % kWave);
-    KeyT* skey = reinterpret_cast<KeyT*>(un);
+    unsigned char* st = ALIAS ? un : un + part_rank_bytes(bins);
+    KeyT* skey = reinterpret_cast<KeyT*>(st);
     uint32_t* sval = reinterpret_cast<uint32_t*>(skey + kPartTile);
-    uint16_t* sdig = reinterpret_cast<uint16_t*>(sval + kPartTile);
+    uint2* spair = reinterpret_cast<uint2*>(st);
+    uint16_t* sdig = reinterpret_cast<uint16_t*>(st + (sizeof(KeyT) + sizeof(uint32_t)) * kPartTile);
 
     const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
     const int c = xcd_remap(blockIdx.x, gridDim.x);
@@ -248,6 +318,8 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
     const int bpt = (bins + kPartThreads - 1) / kPartThreads;
     const int b0 = tid * bpt;
     const int b1 = b0 + bpt < bins ? b0 + bpt : bins;
+    const int zn = static_cast<int>(part_rank_bytes(bins) / 16);
+    uint4* zero_from = reinterpret_cast<uint4*>(un);
 
     // global offset of this chunk's first item of every bin
     {
@@ -264,6 +336,8 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
         }
         if (c == 0 && offsets_out && tid == 0) offsets_out[bins] = total;
     }
+    if (!ALIAS)
+        for (int i = tid; i < zn; i += kPartThreads) zero_from[i] = make_uint4(0u, 0u, 0u, 0u);
     __syncthreads();
 
     const int64_t lo = chunk_begin(plan, c);
@@ -294,12 +368,10 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
 
     for (int64_t tile_base = lo; tile_base < hi; tile_base += kPartTile) {
         const int tile_count = hi - tile_base < kPartTile ? static_cast<int>(hi - tile_base) : kPartTile;
-        {
-            uint4* z = reinterpret_cast<uint4*>(un);  // counters (16-byte rounded) and mask tables, contiguous
-            const int zn = static_cast<int>((part_cnt_bytes(bins) + (kMaskBits > 0 ? sizeof(uint64_t) * kPartWaves * kMaskSlots : 0)) / 16);
-            for (int i = tid; i < zn; i += kPartThreads) z[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (ALIAS) {  // the previous tile was staged where the counters and the mask tables live
+            for (int i = tid; i < zn; i += kPartThreads) zero_from[i] = make_uint4(0u, 0u, 0u, 0u);
+            lds_barrier();
         }
-        lds_barrier();
 
         KeyT k[kPartIPT];
         uint32_t v[kPartIPT], d[kPartIPT], r[kPartIPT];
@@ -320,97 +392,110 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
         for (int i = 0; i < kPartIPT; ++i) {
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
             const bool valid = idx < tile_count;
+            uint16_t* ctr = cnt + cnt_index(d[i], w);
             uint64_t peers;
+            unsigned long long* slot = wmask + (d[i] & (kMaskSlots - 1));
             if (kMaskBits > 0) {
                 // every lane sets its bit in the slot of its digit's low bits, then reads the slot back: the lanes whose
                 // digits agree in those bits.  A wave's LDS operations execute in program order, so the read sees all 64
                 // ORs; the lowest peer clears the slot for the next round.
-                unsigned long long* slot = wmask + (d[i] & (kMaskSlots - 1));
                 if (valid) atomicOr(slot, lanebit);
                 compiler_fence();
                 __builtin_amdgcn_wave_barrier();
                 peers = *slot;
                 if (nbits > kMaskBits) peers &= match_any(d[i] >> kMaskBits, nbits - kMaskBits, valid);
-                uint16_t* ctr = cnt + d[i] * kPartWaves + w;
-                const uint32_t pre = *ctr;
-                const uint64_t below = peers & lt;
-                r[i] = pre + __popcll(below);
-                compiler_fence();
-                __builtin_amdgcn_wave_barrier();
-                if (valid && below == 0) {
-                    *ctr = static_cast<uint16_t>(pre + __popcll(peers));
-                    *slot = 0;
-                }
-                compiler_fence();
-                __builtin_amdgcn_wave_barrier();
             } else {
                 peers = match_any(d[i], nbits, valid);
-                uint16_t* ctr = cnt + d[i] * kPartWaves + w;
-                const uint32_t pre = *ctr;
-                const uint64_t below = peers & lt;
-                r[i] = pre + __popcll(below);
-                compiler_fence();
-                __builtin_amdgcn_wave_barrier();
-                if (valid && below == 0) *ctr = static_cast<uint16_t>(pre + __popcll(peers));
-                compiler_fence();
-                __builtin_amdgcn_wave_barrier();
             }
+            const uint32_t pre = *ctr;
+            const uint64_t below = peers & lt;
+            r[i] = pre + __popcll(below);
+            compiler_fence();
+            __builtin_amdgcn_wave_barrier();
+            if (valid && below == 0) {
+                *ctr = static_cast<uint16_t>(pre + __popcll(peers));
+                if (kMaskBits > 0) *slot = 0;
+            }
+            compiler_fence();
+            __builtin_amdgcn_wave_barrier();
         }
         lds_barrier();
-        // per bin: exclusive scan over the waves, total of the tile.  The counters of one bin lie side by side
-        // ([bin][wave], 16 bytes per 8 waves): one wide read, the prefixes in registers, one wide write.
+        // per bin: exclusive scan over the waves, total of the tile: one wide read, the prefixes in registers, one wide write
         int local = 0;
         for (int b = b0; b < b1; ++b) {
             CntRow* row = reinterpret_cast<CntRow*>(cnt + b * kPartWaves);
+            const uint32_t swz = cnt_swizzle(static_cast<uint32_t>(b));
             uint32_t s = 0;
 #pragma unroll
             for (int q = 0; q < kPartWaves / kCntRowWaves; ++q) {
                 CntRow x = row[q];
+                cnt_row_permute(x, swz);
 #pragma unroll
                 for (int j = 0; j < kCntRowWaves / 2; ++j) {
                     const uint32_t lo16 = x.w[j] & 0xffffu, hi16 = x.w[j] >> 16;
                     x.w[j] = s | ((s + lo16) << 16);  // both prefixes stay below 65536 (a tile has fewer items)
                     s += lo16 + hi16;
                 }
+                cnt_row_permute(x, swz);
                 row[q] = x;
             }
-            btot[b] = s;
+            delta[b] = s;
             local += static_cast<int>(s);
         }
         int total;
-        int run = block_excl_scan<kPartWaves>(local, scan_tmp, &total);
+        int run = part_block_scan(local, scan_tmp, &total);
         for (int b = b0; b < b1; ++b) {
+            const uint32_t t = delta[b], g = gofs[b];
             binstart[b] = static_cast<uint32_t>(run);
-            run += static_cast<int>(btot[b]);
+            delta[b] = g - static_cast<uint32_t>(run);  // slot p of the reordered tile goes to delta[bin] + p
+            gofs[b] = g + t;
+            run += static_cast<int>(t);
         }
         lds_barrier();
 #pragma unroll
         for (int i = 0; i < kPartIPT; ++i) {
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
-            const uint32_t in_bin = static_cast<uint32_t>(cnt[d[i] * kPartWaves + w]) + r[i];
-            r[i] = binstart[d[i]] + in_bin;  // position inside the reordered tile
-            if (idx < tile_count && gofs[d[i]] + in_bin < static_cast<uint32_t>(n)) pol.placed(tile_base + idx, gofs[d[i]] + in_bin);
+            r[i] += binstart[d[i]] + static_cast<uint32_t>(cnt[cnt_index(d[i], w)]);  // position inside the reordered tile
+            const uint32_t dst = delta[d[i]] + r[i];
+            if (idx < tile_count && dst < static_cast<uint32_t>(n)) pol.placed(tile_base + idx, dst);
         }
-        lds_barrier();  // the counters are dead from here on: their storage becomes the staging area
+        lds_barrier();  // the counters are dead from here on
+        if (!ALIAS) {   // cleared for the next tile beside the staging; the mask tables are clear already (every round clears its slots)
+            const int zc = static_cast<int>(part_cnt_bytes(bins) / 16);
+            for (int i = tid; i < zc; i += kPartThreads) zero_from[i] = make_uint4(0u, 0u, 0u, 0u);
+        }
 #pragma unroll
         for (int i = 0; i < kPartIPT; ++i) {
             const int idx = w * (kWave * kPartIPT) + i * kWave + lane;
             if (idx < tile_count) {
-                skey[r[i]] = k[i];
-                sval[r[i]] = v[i];
+                if constexpr (kPairs) {
+                    spair[r[i]] = make_uint2(static_cast<uint32_t>(k[i]), v[i]);
+                } else {
+                    skey[r[i]] = k[i];
+                    sval[r[i]] = v[i];
+                }
                 if (P::kStageDigit) sdig[r[i]] = static_cast<uint16_t>(d[i]);
             }
         }
         lds_barrier();
         for (int p = tid; p < tile_count; p += kPartThreads) {
-            const KeyT key = skey[p];
+            KeyT key;
+            uint32_t val;
+            if constexpr (kPairs) {
+                const uint2 kv = spair[p];
+                key = static_cast<KeyT>(kv.x);
+                val = kv.y;
+            } else {
+                key = skey[p];
+                val = sval[p];
+            }
             const uint32_t dd = P::kStageDigit ? static_cast<uint32_t>(sdig[p]) : pol.digit(key);
-            const uint32_t dst = gofs[dd] + (static_cast<uint32_t>(p) - binstart[dd]);
-            if (dst < static_cast<uint32_t>(n)) pol.store(dst, key, sval[p]);  // always true; keeps a broken histogram from writing out of bounds
+            const uint32_t dst = delta[dd] + static_cast<uint32_t>(p);
+            if (dst < static_cast<uint32_t>(n)) pol.store(dst, key, val);  // always true; keeps a broken histogram from writing out of bounds
         }
-        lds_barrier();
-        for (int b = b0; b < b1; ++b) gofs[b] += btot[b];
-        // the next iteration's first barrier orders these updates before any use
+        // Aliased, the next tile clears the staging area at its top: wait for the readers.  Otherwise the next writes to
+        // anything read above (delta, the staging area) lie behind the next tile's barriers.
+        if (ALIAS) lds_barrier();
     }
 }
 
@@ -425,21 +510,27 @@ inline void run_partition_pass(const P& pol, int n_host, const int* d_n, int bin
     NP_LAUNCH(tag_scan, part_colscan_kernel<kColscanThreads>, dim3((bins + kWave - 1) / kWave), dim3(kColscanThreads), 0, stream, H,
               plan.num_chunks, bins, bin_total);
     const size_t lds = part_scatter_lds_bytes<typename P::KeyT>(bins, P::kStageDigit);
+    const bool aliased = part_stage_aliased<typename P::KeyT>(bins, P::kStageDigit);
+    const void* fn = aliased ? reinterpret_cast<const void*>(part_scatter_kernel<P, true>)
+                             : reinterpret_cast<const void*>(part_scatter_kernel<P, false>);
     if (lds > 48 * 1024) {
-        // above the default dynamic-LDS allowance: opt in, once per device and size (a failure shows up as a failed
+        // above the default dynamic-LDS allowance: opt in, once per device, kernel and size (a failure shows up as a failed
         // launch); later calls, e.g. while a caller records a graph, then enqueue kernels only
-        static std::atomic<int> granted[kMaxDevices];
+        static std::atomic<int> granted[2][kMaxDevices];
         int dev = 0;
         (void)hipGetDevice(&dev);
         const bool tracked = dev >= 0 && dev < kMaxDevices;
-        if (!tracked || granted[dev].load(std::memory_order_relaxed) < static_cast<int>(lds)) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(part_scatter_kernel<P>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-            if (tracked) granted[dev].store(static_cast<int>(lds), std::memory_order_relaxed);
+        if (!tracked || granted[aliased][dev].load(std::memory_order_relaxed) < static_cast<int>(lds)) {
+            (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+            if (tracked) granted[aliased][dev].store(static_cast<int>(lds), std::memory_order_relaxed);
         }
     }
-    NP_LAUNCH(tag_scatter, part_scatter_kernel<P>, dim3(plan.num_chunks), dim3(kPartThreads), lds, stream, pol, n_host,
-              d_n, bins, nbits, plan, H, bin_total, totals_out, offsets_out);
+    if (aliased)
+        NP_LAUNCH(tag_scatter, (part_scatter_kernel<P, true>), dim3(plan.num_chunks), dim3(kPartThreads), lds, stream, pol, n_host,
+                  d_n, bins, nbits, plan, H, bin_total, totals_out, offsets_out);
+    else
+        NP_LAUNCH(tag_scatter, (part_scatter_kernel<P, false>), dim3(plan.num_chunks), dim3(kPartThreads), lds, stream, pol, n_host,
+                  d_n, bins, nbits, plan, H, bin_total, totals_out, offsets_out);
 }
 
 }  // namespace np
