@@ -122,6 +122,10 @@ __device__ __forceinline__ int wave_incl_scan(int v) {
     return v;
 }
 
+// s_waitcnt vmcnt(0) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt
+// 11:8): every global load and store this wave has issued is complete.
+__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // Exclusive scan of one int per thread over a block of NW waves.  `smem` holds NW + 1 ints.  Returns the
 // exclusive prefix; *total receives the block sum.  Contains two LDS barriers.
 template <int NW>

@@ -348,36 +348,23 @@ struct RowSink {
     float lr, eps, inv_dim;
 };
 
-// Called by all LPR lanes that hold a row: lane r holds the float4 words r, r + LPR, ... in g[0 .. NV-1].  The fused
-// arithmetic is that of np_sparse_adagrad's kernel, operation by operation (squares summed over the lane's words in
-// ascending v, then the butterfly over the LPR lanes), so both routes give the same bits.
+// The fused step once its operands are in registers: the key, the old state and the table row (lane r holds words
+// r, r + LPR, ... in w[0 .. NV-1], zero past the row's end).  The arithmetic is that of np_sparse_adagrad's kernel,
+// operation by operation (squares summed over the lane's words in ascending v, then the butterfly over the LPR lanes),
+// so both routes give the same bits.
 template <int LPR, int NV, int FUSED>
-__device__ __forceinline__ void sink_row(const RowSink& sk, int dst, int dim, int r, int words, const float4 (&g)[NV]) {
-    if (FUSED == kSinkGrads) {
-#pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const int wv = r + v * LPR;
-            if (wv < words) store_stream(reinterpret_cast<float4*>(sk.grads + static_cast<size_t>(dst) * dim) + wv, g[v]);
-        }
-        return;
-    }
+__device__ __forceinline__ void sink_row_loaded(const RowSink& sk, int64_t key, float s_old, int dim, int r, int words, float4 (&w)[NV],
+                                                const float4 (&g)[NV]) {
     using TabT = typename SinkTable<FUSED>::type;
-    const int64_t key = sk.keys[dst];
     TabT* wrow = static_cast<TabT*>(sk.table) + static_cast<size_t>(key) * dim;
-    float4 w[NV];
     float ss = 0.f;
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
         const int wv = r + v * LPR;
-        w[v] = make_float4(0.f, 0.f, 0.f, 0.f);
         float4 gv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (wv < words) {
-            w[v] = load_word(wrow, wv);
-            gv = g[v];
-        }
+        if (wv < words) gv = g[v];
         ss += sumsq4(gv);
     }
-    const float s_old = sk.state[key];
 #pragma unroll
     for (int d = LPR / 2; d > 0; d >>= 1) ss += __shfl_xor(ss, d, kWave);
     const float G = adagrad_state(s_old, ss, sk.inv_dim);
@@ -390,6 +377,31 @@ __device__ __forceinline__ void sink_row(const RowSink& sk, int dst, int dim, in
             adagrad_step4(w[v], g[v], sk.lr, denom);
             store_word_stream(wrow, wv, w[v]);
         }
+    }
+}
+
+// Called by all LPR lanes that hold a row: lane r holds the float4 words r, r + LPR, ... in g[0 .. NV-1].
+template <int LPR, int NV, int FUSED>
+__device__ __forceinline__ void sink_row(const RowSink& sk, int dst, int dim, int r, int words, const float4 (&g)[NV]) {
+    if constexpr (FUSED == kSinkGrads) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int wv = r + v * LPR;
+            if (wv < words) store_stream(reinterpret_cast<float4*>(sk.grads + static_cast<size_t>(dst) * dim) + wv, g[v]);
+        }
+    } else {
+        using TabT = typename SinkTable<FUSED>::type;
+        const int64_t key = sk.keys[dst];
+        const TabT* wrow = static_cast<const TabT*>(sk.table) + static_cast<size_t>(key) * dim;
+        float4 w[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int wv = r + v * LPR;
+            w[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (wv < words) w[v] = load_word(wrow, wv);
+        }
+        const float s_old = sk.state[key];
+        sink_row_loaded<LPR, NV, FUSED>(sk, key, s_old, dim, r, words, w, g);
     }
 }
 
@@ -516,6 +528,25 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
         sr = -1;
         dst = -2;
     }
+    // Fused sink, rows of up to LPR words: what the Adagrad step of a finished row needs is requested ahead, so that no
+    // group waits inside the walk for loads that depend on each other.  Every tail position fetches its key and the old
+    // state here; the table rows travel with the dY rows of the batch they end in (load_table_batch).  A row's key, state
+    // and table row are touched by exactly one sink per launch, so reading them early reads the same values.
+    constexpr bool kSinkAhead = FUSED != kSinkGrads && NV == 1;
+    int skey_lo = 0, skey_hi = 0;
+    float sold = 0.f;
+    int first_tail = LPR;
+    if constexpr (kSinkAhead) {
+        if (dst >= 0) {
+            const int64_t key = sink.keys[dst];
+            skey_lo = static_cast<int>(static_cast<uint32_t>(static_cast<uint64_t>(key)));
+            skey_hi = static_cast<int>(static_cast<uint64_t>(key) >> 32);
+            sold = sink.state[key];
+        }
+        const uint64_t tails = __ballot(dst >= 0) >> (__lane_id() & ~(LPR - 1) & (kWave - 1));
+        const uint64_t mine = LPR == kWave ? tails : tails & ((1ull << (LPR & 63)) - 1);
+        if (mine) first_tail = __builtin_ctzll(mine);
+    }
     // ---- each group walks its strip of LPR positions ---------------------------------------------------
     // Position k > 0 starts a segment exactly when position k - 1 ends one, so the walk needs the end marks
     // (dst >= 0) and, for position 0 alone, whether the strip begins inside a segment that started earlier.
@@ -529,8 +560,31 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
     bool le = false, lc = false, re = false;
     int ld = -1, dlast = 0;
+    float4 tw[kSinkAhead ? kBwdUnroll : 1][NV];
+    using TabT = typename SinkTable<FUSED>::type;
+    const bool first_cut = first_open;  // the strip's first tail closes a run that began before the strip: no sink here
+    // table rows of the tails among positions k0 .. k0 + kBwdUnroll - 1 that are finished inside this walk
+    auto load_table_batch = [&](int k0) {
+        if constexpr (kSinkAhead) {
+#pragma unroll
+            for (int q = 0; q < kBwdUnroll; ++q) {
+                const int kk = (k0 + q) & (LPR - 1);
+                const int dkq = group_bcast<LPR>(dst, kk);
+                const int64_t key = static_cast<int64_t>((static_cast<uint64_t>(static_cast<uint32_t>(group_bcast<LPR>(skey_hi, kk))) << 32) |
+                                                         static_cast<uint32_t>(group_bcast<LPR>(skey_lo, kk)));
+                const bool need = k0 + q < cnt && dkq >= 0 && !(first_cut && k0 + q == first_tail) && r < words;
+                const TabT* wrow = static_cast<const TabT*>(sink.table) + static_cast<size_t>(key) * dim;
+                tw[q][0] = need ? load_word(wrow, r) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    };
     for (int k0 = 0; k0 < cnt; k0 += kBwdUnroll) {
         if (!(early && k0 == 0)) load_batch(k0, cnt);
+        load_table_batch(k0);
+        // One explicit wait for the batch, outside every condition.  The loads above sit in conditional blocks, so without it
+        // the compiler waits for "all outstanding memory operations" at every position that uses a loaded row, and after
+        // a row has been stored that includes the store: every finished row would cost a round trip to memory.
+        wait_vmem_all();
 #pragma unroll
         for (int q = 0; q < kBwdUnroll; ++q) {
             const int k = k0 + q;
@@ -560,6 +614,11 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                                 const int wv = word_of<LPR, PAIR>(r, v);
                                 if (wv < words) store_stream(reinterpret_cast<float4*>(sink.grads + static_cast<size_t>(dk) * dim) + wv, acc[v]);
                             }
+                        } else if constexpr (kSinkAhead) {
+                            const int64_t key = static_cast<int64_t>((static_cast<uint64_t>(static_cast<uint32_t>(group_bcast<LPR>(skey_hi, k))) << 32) |
+                                                                     static_cast<uint32_t>(group_bcast<LPR>(skey_lo, k)));
+                            const float so = __int_as_float(group_bcast<LPR>(__float_as_int(sold), k));
+                            sink_row_loaded<LPR, NV, FUSED>(sink, key, so, dim, r, words, tw[q], acc);
                         } else {
                             sink_row<LPR, NV, FUSED>(sink, dk, dim, r, words, acc);
                         }

@@ -4,8 +4,9 @@
 //
 //   part_hist     one block per chunk: LDS histogram of the chunk's digits           -> H[chunk][bin]
 //   part_colscan  exclusive scan of every column of H over the chunks (in place)      -> binTotal[bin]
-//   part_scatter  one block per chunk, tile by tile: wave-ballot ranking gives every item its stable
-//                 rank inside the tile, the tile is reordered through LDS and written out in runs
+//   part_scatter  one block per chunk, tile by tile: every item gets its stable rank among the items of its wave with
+//                 the same digit (lane masks collected in LDS, ballots for the digit's upper bits), per-bin prefix sums
+//                 over the waves and the bins give its slot, the tile is reordered through LDS and written out in runs
 //
 // A chunk is a run of consecutive tiles owned by one block, sized so that at most kTargetChunks blocks
 // cover the input: all of them are resident at once, the same number on every CU (no tail round), and the
@@ -100,7 +101,10 @@ inline size_t part_stage_bytes(bool stage_digit) {
 
 // The staging area of the reordered tile gets LDS of its own when two blocks per CU still fit (fewer barriers per tile:
 // the counters of the next tile are cleared while this one is staged); otherwise it shares the counters' storage.
-constexpr size_t kPartLdsPerBlock = 80 * 1024;  // half of a CU's 160 KB
+#ifndef NP_PART_LDS_PER_BLOCK
+#define NP_PART_LDS_PER_BLOCK (80 * 1024)  // half of a CU's 160 KB
+#endif
+constexpr size_t kPartLdsPerBlock = NP_PART_LDS_PER_BLOCK;
 template <typename KeyT>
 inline bool part_stage_aliased(int bins, bool stage_digit) {
     return part_fixed_lds_bytes(bins) + part_rank_bytes(bins) + part_stage_bytes<KeyT>(stage_digit) > kPartLdsPerBlock;
@@ -282,10 +286,19 @@ __device__ __forceinline__ int part_block_scan(int v, int* smem, int* total) {
     return base + inc - v;
 }
 
-// Measured and not taken (three sort passes over 42 M items): the digit width as a template argument so that the ballot
-// loop unrolls (1.02 ms against 0.95), three blocks per CU instead of two by capping the kernel at 80 registers
-// (amdgpu_waves_per_eu 6: the ranks and the prefetched tile no longer fit and spill, 1.80 ms with 768 chunks, 2.05 ms with
-// 512), blocks of 256 threads, four per CU (tiles of 2048 items make runs half as long: 1.13 ms against 0.90).
+// What the kernel costs (three sort passes over 42 M items of a Zipf batch, 0.77 ms): with the stores redirected to
+// consecutive addresses the passes take 0.50 ms, so a third of the time is the scattered stores, and they cost by their
+// NUMBER, not their bytes: every run of items that a tile appends to a bin leaves the CU as a write of its own (uniformly
+// random keys, four items per bin and tile: 0.70 ms for 63 M runs of 16 bytes; the 42 M single stores of np_dedup's inverse map
+// cost the same per store).  Hence pairs instead of two arrays where a policy can (np_dedup's 32-bit keys: 0.90 -> 0.77 ms).
+// The rest is the ranking: lane masks in LDS instead of ten ballots per item (0.95 -> 0.90 ms), the counters of a bin side by
+// side and bank-swizzled, five barriers per tile instead of eight (no measurable change: the kernel is not bound by LDS).
+// Measured and not taken: the digit width as a template argument so that the ballot loop unrolls (1.02 ms against 0.95),
+// three blocks per CU instead of two by capping the kernel at 80 registers (amdgpu_waves_per_eu 6: the ranks and the
+// prefetched tile no longer fit and spill, 1.80 ms with 768 chunks, 2.05 ms with 512), blocks of 256 threads, four per CU
+// (tiles of 2048 items make the runs half as long: 1.13 ms against 0.90), blocks of 1024 threads, one per CU (tiles of 8192
+// items: 0.75 ms against 0.77, and the counters of 4096 bins no longer fit), 10 or 12 items per thread (150 / 170
+// registers: one block per CU).
 template <class P, bool ALIAS>
 __global__ void __launch_bounds__(kPartThreads)
 part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, int nbits, ChunkPlan plan,
