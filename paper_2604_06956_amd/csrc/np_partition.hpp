@@ -408,7 +408,13 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
             uint16_t* ctr = cnt + cnt_index(d[i], w);
             uint64_t peers;
             unsigned long long* slot = wmask + (d[i] & (kMaskSlots - 1));
-            if (kMaskBits > 0) {
+            // One digit in the whole wave (a popular key's run after the first pass, or few bins): every valid lane is a
+            // peer, no table needed; 64 lanes would also serialise on one slot.
+            const uint64_t vmask = __ballot(valid);
+            const bool one_digit = __ballot(valid && d[i] == static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(d[i]))) == vmask;
+            if (one_digit) {  // uniform
+                peers = vmask;
+            } else if (kMaskBits > 0) {
                 // every lane sets its bit in the slot of its digit's low bits, then reads the slot back: the lanes whose
                 // digits agree in those bits.  A wave's LDS operations execute in program order, so the read sees all 64
                 // ORs; the lowest peer clears the slot for the next round.
@@ -427,7 +433,7 @@ part_scatter_kernel(P pol, int n_host, const int* __restrict__ d_n, int bins, in
             __builtin_amdgcn_wave_barrier();
             if (valid && below == 0) {
                 *ctr = static_cast<uint16_t>(pre + __popcll(peers));
-                if (kMaskBits > 0) *slot = 0;
+                if (kMaskBits > 0 && !one_digit) *slot = 0;
             }
             compiler_fence();
             __builtin_amdgcn_wave_barrier();
