@@ -87,6 +87,13 @@ def _keys_case(name):
     if name == "bits_63":
         base = rng.integers(0, (1 << 63) - 1, size=5000).astype(np.int64)
         return base[rng.integers(0, 5000, size=60000)], 63
+    if name == "bits_32_many_tiles":   # 2048 bins: staging shares the counters' LDS; several tiles per chunk
+        k = rng.integers(0, 1 << 32, size=3_000_001).astype(np.int64)
+        k[rng.random(k.size) < 0.2] = (1 << 32) - 7
+        return k, 32
+    if name == "bits_40_many_tiles":   # 64-bit sort keys (separate key and position arrays), several tiles per chunk
+        base = rng.integers(0, 1 << 40, size=400_000).astype(np.int64)
+        return base[rng.integers(0, base.size, size=2_500_003)], 40
     if name == "hot_key":
         k = rng.integers(0, 1 << 28, size=300000).astype(np.int64)
         k[rng.random(300000) < 0.4] = 77777777
@@ -95,7 +102,8 @@ def _keys_case(name):
 
 
 DEDUP_CASES = ["one", "all_equal", "all_distinct", "wave_edges", "tile_minus_1", "tile_exact", "tile_plus_1",
-               "multi_chunk", "bits_1", "bits_32", "bits_33", "bits_40_dups", "bits_63", "hot_key"]
+               "multi_chunk", "bits_1", "bits_32", "bits_33", "bits_40_dups", "bits_63", "hot_key", "bits_32_many_tiles",
+               "bits_40_many_tiles"]
 
 
 @pytest.mark.parametrize("case", DEDUP_CASES)
