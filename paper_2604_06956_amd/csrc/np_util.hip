@@ -238,7 +238,7 @@ int64_t np_tune_get(const char* name) {
     return -1;
 }
 
-int np_version(void) { return 10300; }  // 1.3.0: np_route_static, np_tune_set / np_tune_get, tile-ordered inverse map
+int np_version(void) { return 10301; }  // 1.3.1: same interface as 1.3.0 (np_route_static, np_tune_set / np_tune_get); sort passes on (key, position) pairs
 
 const char* np_status_string(int status) {
     switch (status) {
