@@ -535,7 +535,6 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     constexpr bool kSinkAhead = FUSED != kSinkGrads && NV == 1;
     int skey_lo = 0, skey_hi = 0;
     float sold = 0.f;
-    int first_tail = LPR;
     if constexpr (kSinkAhead) {
         if (dst >= 0) {
             const int64_t key = sink.keys[dst];
@@ -543,6 +542,10 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
             skey_hi = static_cast<int>(static_cast<uint64_t>(key) >> 32);
             sold = sink.state[key];
         }
+    }
+    // the first position of the strip that ends a segment (LPR: none does)
+    int first_tail = LPR;
+    {
         const uint64_t tails = __ballot(dst >= 0) >> (__lane_id() & ~(LPR - 1) & (kWave - 1));
         const uint64_t mine = LPR == kWave ? tails : tails & ((1ull << (LPR & 63)) - 1);
         if (mine) first_tail = __builtin_ctzll(mine);
@@ -553,16 +556,17 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
     int cnt = n - (tile_start + g * LPR);
     cnt = cnt < 0 ? 0 : (cnt > LPR ? LPR : cnt);
     const int head_here = t == 0 ? (seg0_start == tile_start ? 1 : 0) : flag;
-    bool first_open = group_bcast<LPR>(head_here, 0) == 0;  // the strip's first run continues an earlier one
+    // Everything the walk has to decide is known per group before it starts: whether the strip's first run continues an
+    // earlier one (then the first segment end closes a cut run: its sum is parked, not stored), and whether the last
+    // position leaves a run open.  The loop carries the running sum and nothing else.
+    const bool first_cut = group_bcast<LPR>(head_here, 0) == 0;
+    const bool open_after = cnt > 0 && group_bcast<LPR>(dst, cnt > 0 ? cnt - 1 : 0) == -1;  // (-2, a skipped single-lookup key, leaves nothing open)
     const int wbits = __float_as_int(w);
     float4 acc[NV];
 #pragma unroll
     for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
-    bool le = false, lc = false, re = false;
-    int ld = -1, dlast = 0;
     float4 tw[kSinkAhead ? kBwdUnroll : 1][NV];
     using TabT = typename SinkTable<FUSED>::type;
-    const bool first_cut = first_open;  // the strip's first tail closes a run that began before the strip: no sink here
     // table rows of the tails among positions k0 .. k0 + kBwdUnroll - 1 that are finished inside this walk
     auto load_table_batch = [&](int k0) {
         if constexpr (kSinkAhead) {
@@ -605,9 +609,8 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                         acc[v].w += x[q][v].w;
                     }
                 }
-                dlast = dk == -2 ? 0 : dk;  // a skipped single-lookup key closes nothing and leaves nothing open
                 if (dk >= 0) {  // a segment ends here
-                    if (!first_open) {
+                    if (!(first_cut && k == first_tail)) {
                         if constexpr (PAIR) {
 #pragma unroll
                             for (int v = 0; v < NV; ++v) {
@@ -625,10 +628,6 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
                     } else {
 #pragma unroll
                         for (int v = 0; v < NV; ++v) lpart[g * ROWW + word_of<LPR, PAIR>(r, v)] = acc[v];
-                        le = true;
-                        lc = true;
-                        ld = dk;
-                        first_open = false;
                     }
 #pragma unroll
                     for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -636,17 +635,19 @@ bwd_main_kernel(const DyT* __restrict__ dY, int dim, int seq, int max_len, const
             }
         }
     }
-    if (cnt > 0 && dlast < 0) {  // the last run goes on past the strip
-        if (first_open) {        // one segment covers the whole strip
+    // what the strip hands to the combine stage
+    const bool has_tail = first_tail < cnt;
+    const bool le = first_cut && cnt > 0 && (has_tail || open_after);  // a run that began before the strip ...
+    const bool lc = first_cut && has_tail;                               // ... and ends inside it
+    const int ld = lc ? group_bcast<LPR>(dst, first_tail & (LPR - 1)) : -1;
+    const bool whole = first_cut && !has_tail && open_after;             // one run covers the whole strip
+    const bool re = open_after && !whole;                                // a run that starts in the strip and goes on
+    if (whole) {
 #pragma unroll
-            for (int v = 0; v < NV; ++v) lpart[g * ROWW + word_of<LPR, PAIR>(r, v)] = acc[v];
-            le = true;
-            lc = false;
-        } else {
+        for (int v = 0; v < NV; ++v) lpart[g * ROWW + word_of<LPR, PAIR>(r, v)] = acc[v];
+    } else if (re) {
 #pragma unroll
-            for (int v = 0; v < NV; ++v) rpart[g * ROWW + word_of<LPR, PAIR>(r, v)] = acc[v];
-            re = true;
-        }
+        for (int v = 0; v < NV; ++v) rpart[g * ROWW + word_of<LPR, PAIR>(r, v)] = acc[v];
     }
     if (r == 0) {
         l_exists[g] = le;
