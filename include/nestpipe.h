@@ -37,6 +37,9 @@
  *    device: they may be issued from several host threads and on several devices.  Ordering
  *    calls that share a buffer (through streams and events) is the caller's job.  The np_prof_*
  *    timing hooks are the exception (process-wide state, one thread at a time).
+ *  - The first np_dedup / np_route / np_lookup_bwd call of a process on a device opts its partition kernel in to
+ *    more than 48 KB of dynamic LDS (hipFuncSetAttribute, once per device; no stream work, no allocation).
+ *    Record a HIP graph after one ordinary call has been made.
  */
 #ifndef NESTPIPE_H_
 #define NESTPIPE_H_
